@@ -1,0 +1,259 @@
+"""Seeded synthetic workloads: shapes, permutations and input values.
+
+This module only *describes* problems (dims, perm, element size, seed) and
+draws input values.  It holds none of the transpose arithmetic and is the one
+module that both the CPU checker's tests and the GPU path's tests feed from.
+
+Conventions: ``dims[0]`` is the stride-1 dimension; ``perm[j]`` is the input
+dimension found at output position ``j``.
+
+The five workload families are synthetic stand-ins, at 2^24..2^26 elements, for
+the paper's benchmark shapes: random-extent tensors of ranks 2-7 with 500
+permutations per rank (Section 3.1), rank-8/rank-12 tensors with four large and
+many small dimensions (Section 3.2) and the contraction sample whose tensors
+have a few large leading dimensions and all other extents 8 (Section 3.4).
+"""
+from __future__ import annotations
+
+import itertools
+import math
+from dataclasses import dataclass, field
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+SEED_BASE = 170501598 * 1_000_000
+LOG2_VOL = 26
+
+
+@dataclass(frozen=True)
+class Case:
+    config: int                 # 1..5 = workload family, 0 = ad-hoc test case
+    index: int                  # case number inside the family
+    dims: Tuple[int, ...]
+    perm: Tuple[int, ...]
+    elem_size: int              # 4 or 8 bytes
+    tag: str = ""
+    seed: int = field(default=0)
+
+    @property
+    def rank(self) -> int:
+        return len(self.dims)
+
+    @property
+    def volume(self) -> int:
+        return math.prod(self.dims)
+
+    @property
+    def bytes_moved(self) -> int:
+        """Read + write bytes: 2 * vol * E (bandwidth formula of Section 3.1)."""
+        return 2 * self.volume * self.elem_size
+
+    @property
+    def name(self) -> str:
+        return f"c{self.config}_{self.index:03d}{('_' + self.tag) if self.tag else ''}"
+
+
+def case_seed(config: int, index: int) -> int:
+    return SEED_BASE + 10_000 * config + index
+
+
+def make_case(config, index, dims, perm, elem_size, tag="") -> Case:
+    return Case(config, index, tuple(int(d) for d in dims), tuple(int(p) for p in perm),
+                int(elem_size), tag, case_seed(config, index))
+
+
+# ---------------------------------------------------------------------------
+# input values
+# ---------------------------------------------------------------------------
+
+def uniform_values(case: Case) -> np.ndarray:
+    """Flat input buffer, uniform in [-1, 1), float64 or float32 by element size."""
+    rng = np.random.default_rng(case.seed)
+    if case.elem_size == 8:
+        a = rng.random(case.volume, dtype=np.float64)
+        a *= 2.0
+        a -= 1.0
+        return a
+    a = rng.random(case.volume, dtype=np.float32)
+    a *= np.float32(2.0)
+    a -= np.float32(1.0)
+    return a
+
+
+def stamp_values(case: Case) -> np.ndarray:
+    """Index stamp: element i holds the integer i (int64 or int32 by element size)."""
+    return np.arange(case.volume, dtype=np.int64 if case.elem_size == 8 else np.int32)
+
+
+def bitpattern_values(case: Case) -> np.ndarray:
+    """Random raw bit patterns (NaN payloads, -0.0, denormals included) as unsigned ints."""
+    rng = np.random.default_rng(case.seed ^ 0x5A5A5A5A)
+    dt = np.uint64 if case.elem_size == 8 else np.uint32
+    a = rng.integers(0, np.iinfo(dt).max, size=case.volume, dtype=dt, endpoint=True)
+    if a.size >= 4:
+        if case.elem_size == 8:
+            a[:4] = [0x8000000000000000, 0x7FF8000000000001, 0x0000000000000001, 0xFFF0000000000000]
+        else:
+            a[:4] = [0x80000000, 0x7FC00001, 0x00000001, 0xFF800000]
+    return a
+
+
+def sample_positions(case: Case, n: int) -> np.ndarray:
+    """n seeded output scalar positions (first, last and random ones)."""
+    rng = np.random.default_rng(case.seed ^ 0x0C0FFEE)
+    pos = rng.integers(0, case.volume, size=n, dtype=np.int64)
+    pos[0] = 0
+    pos[-1] = case.volume - 1
+    return pos
+
+
+# ---------------------------------------------------------------------------
+# shape helpers
+# ---------------------------------------------------------------------------
+
+def _random_non_identity_perm(rng, r: int) -> Tuple[int, ...]:
+    while True:
+        p = tuple(int(x) for x in rng.permutation(r))
+        if p != tuple(range(r)):
+            return p
+
+
+def _random_dims(rng, r: int, lo: float, hi: float, log2_vol: int = LOG2_VOL,
+                 fixed0: int | None = None) -> Tuple[int, ...]:
+    """Extents with log2 ~ U[lo, hi], shifted so the logs sum to log2_vol, rounded to
+    integers >= 2; the largest extent is then reset so the volume lands within 3 % of
+    2^log2_vol.  ``fixed0`` pins dims[0] and rescales the others."""
+    target = float(2 ** log2_vol)
+    for _ in range(1000):
+        logs = rng.uniform(lo, hi, size=r)
+        if fixed0 is not None:
+            rest = logs[1:]
+            rest += (log2_vol - math.log2(fixed0) - rest.sum()) / max(1, r - 1)
+            logs = np.concatenate([[math.log2(fixed0)], rest])
+        else:
+            logs += (log2_vol - logs.sum()) / r
+        dims = [max(2, int(round(2.0 ** x))) for x in logs]
+        if fixed0 is not None:
+            dims[0] = int(fixed0)
+        free = range(1, r) if (fixed0 is not None and r > 1) else range(r)
+        big = max(free, key=lambda z: dims[z])
+        others = math.prod(d for z, d in enumerate(dims) if z != big)
+        dims[big] = max(2, int(round(target / others)))
+        vol = math.prod(dims)
+        if abs(vol - target) <= 0.03 * target:
+            return tuple(dims)
+    raise RuntimeError("could not draw dims")
+
+
+# ---------------------------------------------------------------------------
+# the five configurations
+# ---------------------------------------------------------------------------
+
+def config1() -> List[Case]:
+    """Rank-2 fp64 matrix transpose, 2048 x 2048."""
+    return [make_case(1, 0, (2048, 2048), (1, 0), 8, "r2")]
+
+
+def config2() -> List[Case]:
+    """Rank-4 fp64, 96^4, all 23 non-identity permutations in lexicographic order."""
+    cases = []
+    idx = 0
+    for p in itertools.permutations(range(4)):
+        if p == (0, 1, 2, 3):
+            continue
+        cases.append(make_case(2, idx, (96, 96, 96, 96), p, 8, "p" + "".join(map(str, p))))
+        idx += 1
+    return cases
+
+
+def config3() -> List[Case]:
+    """Rank-6 fp64, 20 cases at ~2^26 elements: cases 0-9 have a leading input extent in
+    2..8 (packed path), cases 10-19 one in 32..64 (tiled path); random permutations."""
+    cases = []
+    for i in range(20):
+        rng = np.random.default_rng(case_seed(3, i) ^ 0xD1D5)
+        d0 = int(rng.integers(2, 9)) if i < 10 else int(rng.integers(32, 65))
+        dims = _random_dims(rng, 6, 1.0, 6.0, fixed0=d0)
+        perm = _random_non_identity_perm(rng, 6)
+        cases.append(make_case(3, i, dims, perm, 8, "small0" if i < 10 else "large0"))
+    return cases
+
+
+def config4(ranks: Sequence[int] = tuple(range(2, 13)), per_rank: int = 30) -> List[Case]:
+    """Rank sweep 2..12, fp64, 30 cases per rank at ~2^26 elements.  Cases 0-23: uniformly
+    random non-identity permutation; cases 24-29: axis 0 stays first, the tail is a random
+    non-identity permutation (rank 2 has only (1,0))."""
+    cases = []
+    for r in ranks:
+        for i in range(per_rank):
+            index = (r - 2) * 30 + i
+            rng = np.random.default_rng(case_seed(4, index) ^ 0xD1D5)
+            dims = _random_dims(rng, r, 1.0, LOG2_VOL / r + 1.0)
+            if r == 2:
+                perm = (1, 0)
+            elif i < 24:
+                perm = _random_non_identity_perm(rng, r)
+            else:
+                tail = _random_non_identity_perm(rng, r - 1)
+                perm = (0,) + tuple(t + 1 for t in tail)
+            cases.append(make_case(4, index, dims, perm, 8, f"r{r}"))
+    return cases
+
+
+def config5() -> List[Case]:
+    """Contraction-feeding fp32 transposes: rank 8 with every extent 8 and rank 6 with
+    every extent 16 (2^24 elements each), 40 permutations each that move an index group
+    to the front (cases 0-19) or to the back (20-39); the group keeps its order in even
+    cases and is shuffled in odd ones."""
+    cases = []
+    index = 0
+    for r, ext in ((8, 8), (6, 16)):
+        for i in range(40):
+            rng = np.random.default_rng(case_seed(5, index) ^ 0xD1D5)
+            while True:
+                size = int(rng.integers(1, r))
+                group = sorted(int(x) for x in rng.choice(r, size=size, replace=False))
+                rest = [z for z in range(r) if z not in group]
+                if i % 2 == 1:
+                    group = [int(x) for x in rng.permutation(group)]
+                perm = tuple(group + rest) if i < 20 else tuple(rest + group)
+                if perm != tuple(range(r)):
+                    break
+            cases.append(make_case(5, index, (ext,) * r, perm, 4,
+                                   f"r{r}{'front' if i < 20 else 'back'}"))
+            index += 1
+    return cases
+
+
+def all_configs() -> dict:
+    return {1: config1(), 2: config2(), 3: config3(), 4: config4(), 5: config5()}
+
+
+# ---------------------------------------------------------------------------
+# further shapes printed in the paper (Section 3.2 and Figure 8)
+# ---------------------------------------------------------------------------
+
+SET2_RANK8_DIMS = (5, 3, 2, 4, 35, 33, 37, 40)
+SET2_RANK12_DIMS = (2, 3, 4, 3, 2, 2, 3, 2, 20, 18, 22, 24)
+
+
+def set2(n_random: int = 500) -> List[Case]:
+    """Section 3.2 shapes: the printed rank-8 and rank-12 extents with seeded random
+    permutations plus the trivial and the reverse one."""
+    cases = []
+    index = 0
+    for dims in (SET2_RANK8_DIMS, SET2_RANK12_DIMS):
+        r = len(dims)
+        perms = [tuple(range(r)), tuple(reversed(range(r)))]
+        rng = np.random.default_rng(case_seed(6, r) ^ 0xD1D5)
+        perms += [_random_non_identity_perm(rng, r) for _ in range(n_random)]
+        for p in perms:
+            cases.append(make_case(6, index, dims, p, 8, f"set2r{r}"))
+            index += 1
+    return cases
+
+
+def square_sweep() -> List[Case]:
+    """Figure 8 shapes: fp32 square matrices with side 13952..13968."""
+    return [make_case(7, s - 13952, (s, s), (1, 0), 4, f"side{s}") for s in range(13952, 13969)]
