@@ -1,0 +1,151 @@
+/*
+ * tperm -- out-of-place rank-n dense tensor transpose for AMD MI355X (gfx950).
+ *
+ * Computes B[perm(i)] = A[i]: the element of the input tensor A with multi-index
+ * (y_0, .., y_{n-1}) is stored in the output tensor B at multi-index
+ * (y_{perm[0]}, .., y_{perm[n-1]}).  This is the tensor transpose of Section 2 of the
+ * paper (scalar position, its inverse, and Eq. (1)), restated 0-based:
+ *
+ *   - dims[0] is the stride-1 dimension; later dimensions are more senior;
+ *   - perm[j] is the INPUT dimension found at OUTPUT position j (the paper's
+ *     w_{j+1} - 1), so the output extents are dims[perm[j]];
+ *   - elements are 4 or 8 bytes wide and are moved as raw bits.
+ *
+ * The interface is the create-plan / execute / destroy triple the paper describes for
+ * its library (Section 2.3): a plan is made once from (rank, extents, permutation),
+ * then executed any number of times.
+ *
+ * Plan creation and inspection are pure host code and need no GPU.  tperm_execute
+ * enqueues work on a HIP stream; `in` and `out` are DEVICE pointers owned by the
+ * caller.  The library keeps no reference to them.  No function throws or aborts:
+ * every failure is reported through the returned status.
+ */
+#ifndef TPERM_H
+#define TPERM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TPERM_MAX_RANK 16
+
+typedef struct tperm_plan_s *tperm_plan_t; /* opaque; created and freed by the library */
+
+typedef enum {
+    TPERM_OK = 0,
+    TPERM_ERR_NULL = 1,      /* a required pointer argument is NULL                       */
+    TPERM_ERR_RANK = 2,      /* rank outside [1, TPERM_MAX_RANK]                          */
+    TPERM_ERR_DIMS = 3,      /* an extent is < 1                                          */
+    TPERM_ERR_PERM = 4,      /* perm is not a permutation of 0..rank-1                    */
+    TPERM_ERR_ELEM_SIZE = 5, /* element size is not 4 or 8                                */
+    TPERM_ERR_TOO_LARGE = 6, /* volume >= 2^31 elements                                   */
+    TPERM_ERR_ALIAS = 7,     /* in == out (the transpose is out-of-place)                 */
+    TPERM_ERR_ALIGN = 8,     /* a data pointer is not a multiple of the element size      */
+    TPERM_ERR_HIP = 9,       /* a HIP call failed (no device, launch error)               */
+    TPERM_ERR_NOMEM = 10,    /* host allocation failed                                    */
+    TPERM_ERR_KERNEL = 11,   /* the forced kernel class / options cannot run this problem */
+    TPERM_ERR_INTERNAL = 12  /* self-check of a plan's index maps failed                  */
+} tperm_status_t;
+
+/* Kernel classes the plan selector chooses between (Section 2.3 lists the paper's:
+ * Tiled, TiledCopy, Packed, PackedSplit; the trivial permutation is a plain copy). */
+typedef enum {
+    TPERM_KERNEL_AUTO = 0,
+    TPERM_KERNEL_COPY = 1,    /* canonical permutation is the identity: out[i] = in[i]        */
+    TPERM_KERNEL_ROWCOPY = 2, /* leading dimension stays first and is long: rows are moved,    */
+                              /* no LDS stage (the paper's TiledCopy)                          */
+    TPERM_KERNEL_TILED = 3,   /* 2-D tile over (input dim 0, output dim 0) staged in LDS       */
+    TPERM_KERNEL_PACKED = 4,  /* several leading input/output dims packed into one LDS tile,   */
+                              /* the last one on each side possibly split (Packed/PackedSplit) */
+    TPERM_KERNEL_NAIVE = 5    /* one thread per output element, no staging (debug anchor)      */
+} tperm_kernel_class_t;
+
+/* Optional overrides for plan creation.  Zero-initialise; 0 always means "let the
+ * selector decide". */
+typedef struct {
+    int kernel_class;   /* tperm_kernel_class_t                                              */
+    int m;              /* number of leading INPUT dims (canonical) taken into the tile      */
+    int64_t tile_in;    /* tile extent of the last of those m dims (0 = full extent)         */
+    int k;              /* number of leading OUTPUT dims (canonical) taken into the tile     */
+    int64_t tile_out;   /* tile extent of the last of those k dims (0 = full extent)         */
+    int lds_pad;        /* -1 = search; >= 0 forces the LDS row padding (elements)           */
+    int grid_mode;      /* 0 = default tile order; 1 = one contiguous tile range per XCD     */
+    int reserved[8];
+} tperm_plan_opts_t;
+
+/* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
+ * that stay adjacent and in order in the output. */
+typedef struct {
+    int kernel_class;                      /* tperm_kernel_class_t actually chosen          */
+    int elem_size;
+    int rank;                              /* as given                                      */
+    int canon_rank;
+    int64_t canon_dims[TPERM_MAX_RANK];
+    int canon_perm[TPERM_MAX_RANK];
+    int64_t volume;
+    int64_t tile_extent[TPERM_MAX_RANK];   /* per canonical dim; 1 = not in the tile        */
+    int64_t tile_volume;                   /* elements staged per tile                      */
+    int64_t run_in;                        /* contiguous input run per tile, elements       */
+    int64_t run_out;                       /* contiguous output run per tile, elements      */
+    int64_t num_tiles;
+    int m, k;
+    int nreg;                              /* elements each thread moves per tile           */
+    int threads;                           /* threads per workgroup                         */
+    int lds_bytes;
+    int lds_pad;
+    double score;                          /* selector's estimate (relative, lower = better)*/
+    int reserved[8];
+} tperm_plan_info_t;
+
+/* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is
+ * set to NULL.  elem_size is in bytes (4 or 8). */
+tperm_status_t tperm_plan_create(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                 const int *perm, size_t elem_size);
+
+/* Same, with overrides (tests, sweeps).  opts may be NULL.  A kernel class that cannot
+ * legally run the problem gives TPERM_ERR_KERNEL. */
+tperm_status_t tperm_plan_create_ex(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                    const int *perm, size_t elem_size,
+                                    const tperm_plan_opts_t *opts);
+
+/* Measurement-based plan selection (Section 2.3): every candidate plan the selector
+ * enumerates is executed on (in, out) on `hip_stream` and timed with HIP events; the
+ * fastest is kept.  in/out are device buffers of at least volume*elem_size bytes; out is
+ * overwritten.  Synchronises the stream.  max_candidates <= 0 means all. */
+tperm_status_t tperm_plan_create_measured(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                          const int *perm, size_t elem_size, const void *in,
+                                          void *out, void *hip_stream, int max_candidates);
+
+/* Enqueue the transpose on hip_stream (a hipStream_t; NULL = the default stream) and
+ * return without synchronising.  in: device pointer to volume*elem_size bytes, read
+ * only.  out: device pointer to volume*elem_size bytes, fully overwritten; must not
+ * overlap in.  A plan is immutable: concurrent executes on several streams are allowed. */
+tperm_status_t tperm_execute(tperm_plan_t plan, const void *in, void *out, void *hip_stream);
+
+/* Fill *info from the plan (host only). */
+tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);
+
+/* Host-only self check of a plan's index arithmetic: runs, on the CPU, the very offset
+ * computations the kernel performs (tile enumeration, major/minor offsets, LDS slots,
+ * edge masks) and records, for every output scalar position o, the input scalar position
+ * whose element the kernel would store there.  out_to_in has volume entries; entries
+ * never written are -1.  Returns TPERM_ERR_INTERNAL if an output position is written
+ * twice, an LDS slot is read before it is written, or an offset leaves the tensor.
+ * Moves no tensor data; meant for volumes small enough to enumerate. */
+tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
+
+tperm_status_t tperm_plan_destroy(tperm_plan_t plan);
+
+const char *tperm_status_string(tperm_status_t s);
+
+/* Plain device-to-device copy of nbytes with the library's copy kernel (the bandwidth
+ * ceiling the transposes are compared with, in the way Section 3 uses a STREAM figure). */
+tperm_status_t tperm_copy_bytes(const void *in, void *out, size_t nbytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPERM_H */

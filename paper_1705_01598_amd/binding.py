@@ -1,0 +1,205 @@
+"""ctypes binding of libtperm.so: same names as the C ABI in include/tperm.h.
+
+Argument marshalling only.  Every step of the transpose runs in the library's kernels;
+there is no Python or CPU fallback: if the shared library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtperm.so")
+
+TPERM_MAX_RANK = 16
+
+# status codes
+OK, ERR_NULL, ERR_RANK, ERR_DIMS, ERR_PERM, ERR_ELEM_SIZE, ERR_TOO_LARGE, ERR_ALIAS, ERR_ALIGN, \
+    ERR_HIP, ERR_NOMEM, ERR_KERNEL, ERR_INTERNAL = range(13)
+
+# kernel classes
+KERNEL_AUTO, KERNEL_COPY, KERNEL_ROWCOPY, KERNEL_TILED, KERNEL_PACKED, KERNEL_NAIVE = range(6)
+KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowcopy",
+                KERNEL_TILED: "tiled", KERNEL_PACKED: "packed", KERNEL_NAIVE: "naive"}
+
+EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
+           "tperm_execute", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
+           "tperm_status_string", "tperm_copy_bytes"]
+
+
+class PlanOpts(ctypes.Structure):
+    _fields_ = [("kernel_class", ctypes.c_int), ("m", ctypes.c_int), ("tile_in", ctypes.c_int64),
+                ("k", ctypes.c_int), ("tile_out", ctypes.c_int64), ("lds_pad", ctypes.c_int),
+                ("grid_mode", ctypes.c_int), ("reserved", ctypes.c_int * 8)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("kernel_class", ctypes.c_int), ("elem_size", ctypes.c_int), ("rank", ctypes.c_int),
+                ("canon_rank", ctypes.c_int), ("canon_dims", ctypes.c_int64 * TPERM_MAX_RANK),
+                ("canon_perm", ctypes.c_int * TPERM_MAX_RANK), ("volume", ctypes.c_int64),
+                ("tile_extent", ctypes.c_int64 * TPERM_MAX_RANK), ("tile_volume", ctypes.c_int64),
+                ("run_in", ctypes.c_int64), ("run_out", ctypes.c_int64),
+                ("num_tiles", ctypes.c_int64), ("m", ctypes.c_int), ("k", ctypes.c_int),
+                ("nreg", ctypes.c_int), ("threads", ctypes.c_int), ("lds_bytes", ctypes.c_int),
+                ("lds_pad", ctypes.c_int), ("score", ctypes.c_double),
+                ("reserved", ctypes.c_int * 8)]
+
+
+class TpermError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtperm.so (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1705_01598_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.tperm_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip, ctypes.c_size_t]
+        L.tperm_plan_create_ex.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
+                                           ctypes.c_size_t, ctypes.POINTER(PlanOpts)]
+        L.tperm_plan_create_measured.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
+                                                 ctypes.c_size_t, vp, vp, vp, ctypes.c_int]
+        L.tperm_execute.argtypes = [vp, vp, vp, vp]
+        L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+        L.tperm_plan_index_map.argtypes = [vp, i64p]
+        L.tperm_plan_destroy.argtypes = [vp]
+        L.tperm_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.tperm_status_string.argtypes = [ctypes.c_int]
+        L.tperm_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name != "tperm_status_string":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().tperm_status_string(int(status)).decode()
+
+
+def _marshal(dims: Sequence[int], perm: Sequence[int]):
+    rank = len(dims)
+    cd = (ctypes.c_int64 * max(rank, 1))(*[int(d) for d in dims])
+    cp = (ctypes.c_int * max(rank, 1))(*[int(p) for p in perm])
+    return rank, cd, cp
+
+
+class Plan:
+    """Owns one tperm_plan_t."""
+
+    def __init__(self, handle: ctypes.c_void_p):
+        self._h = handle
+
+    @property
+    def handle(self):
+        return self._h
+
+    def describe(self) -> PlanInfo:
+        return tperm_plan_describe(self)
+
+    def execute(self, in_ptr: int, out_ptr: int, stream: int = 0) -> None:
+        tperm_execute(self, in_ptr, out_ptr, stream)
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            lib().tperm_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def tperm_plan_create(dims: Sequence[int], perm: Sequence[int], elem_size: int) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create(ctypes.byref(h), rank, cd, cp, int(elem_size))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create")
+    return Plan(h)
+
+
+def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: int,
+                         kernel_class: int = KERNEL_AUTO, m: int = 0, tile_in: int = 0, k: int = 0,
+                         tile_out: int = 0, lds_pad: int = -1, grid_mode: int = 0) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
+                    tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode))
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create_ex")
+    return Plan(h)
+
+
+def tperm_plan_create_measured(dims: Sequence[int], perm: Sequence[int], elem_size: int,
+                               in_ptr: int, out_ptr: int, stream: int = 0,
+                               max_candidates: int = 0) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create_measured(ctypes.byref(h), rank, cd, cp, int(elem_size),
+                                          ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                          ctypes.c_void_p(stream), int(max_candidates))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create_measured")
+    return Plan(h)
+
+
+def tperm_execute(plan: Plan, in_ptr: int, out_ptr: int, stream: int = 0) -> None:
+    st = lib().tperm_execute(plan.handle, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                             ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_execute")
+
+
+def tperm_plan_describe(plan: Plan) -> PlanInfo:
+    info = PlanInfo()
+    st = lib().tperm_plan_describe(plan.handle, ctypes.byref(info))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_describe")
+    return info
+
+
+def tperm_plan_index_map(plan: Plan):
+    """out_to_in map evaluated on the host from the plan's descriptors (numpy int64)."""
+    import numpy as np
+    info = tperm_plan_describe(plan)
+    buf = np.empty(int(info.volume), dtype=np.int64)
+    st = lib().tperm_plan_index_map(plan.handle, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_index_map")
+    return buf
+
+
+def tperm_plan_destroy(plan: Plan) -> None:
+    plan.destroy()
+
+
+def tperm_copy_bytes(in_ptr: int, out_ptr: int, nbytes: int, stream: int = 0) -> None:
+    st = lib().tperm_copy_bytes(ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr), int(nbytes),
+                                ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_copy_bytes")
+
+
+def info_dict(info: PlanInfo) -> dict:
+    r = info.canon_rank
+    return {"kernel": KERNEL_NAMES.get(info.kernel_class, "?"), "canon_dims": list(info.canon_dims[:r]),
+            "canon_perm": list(info.canon_perm[:r]), "tile": list(info.tile_extent[:r]),
+            "tile_volume": info.tile_volume, "run_in": info.run_in, "run_out": info.run_out,
+            "num_tiles": info.num_tiles, "nreg": info.nreg, "lds_bytes": info.lds_bytes,
+            "lds_pad": info.lds_pad, "score": round(info.score, 4)}

@@ -1,0 +1,333 @@
+// HIP kernels for gfx950 (MI355X): the tile kernel that every staged transpose class runs
+// through, the plain copy and the naive gather.
+//
+// Tile kernel, per workgroup (256 threads = 4 wavefronts of 64):
+//   prologue  every thread evaluates, once, the minor positions (Eqs. (4)-(6)) of the
+//             NREG tile slots it owns and keeps them in registers;
+//   per tile  the major offsets (Eqs. (2),(3)) are evaluated lane-parallel: lane j of a
+//             16-lane DPP row holds term j, a row_shr scan adds them, v_readlane moves the
+//             sum into scalar registers (the wave64 form of the paper's Algorithm 1);
+//             global -> registers -> LDS (input order), barrier, LDS (output order) ->
+//             registers -> global.  The loads of the next tile are issued before the
+//             stores of the current one so reads stay in flight all the time.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.hpp"
+#include "tperm_desc.h"
+
+namespace tperm {
+
+// ---------------------------------------------------------------------------------------
+// wave-level helpers
+// ---------------------------------------------------------------------------------------
+
+// Inclusive add-scan inside each row of 16 lanes with DPP row shifts; lane 15 of a row
+// ends up with the sum of the row.  Lanes shifted in from outside the row read 0.
+__device__ __forceinline__ uint32_t row_scan_add(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);  // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);  // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);  // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);  // row_shr:8
+    return v;
+}
+
+__device__ __forceinline__ uint32_t read_lane(uint32_t v, uint32_t lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
+}
+
+struct MajorPos {
+    uint32_t in, out;        // element offsets of the tile (wave-uniform)
+    uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
+};
+
+// One lane's term of the major sums, kept in registers for the whole kernel.
+struct MajorLane {
+    FastDiv cum, ext_div;
+    uint32_t ext, stride_in, stride_out;
+};
+
+__device__ __forceinline__ MajorPos major_position(const TileDesc& d, const MajorLane& ml,
+                                                   uint32_t b) {
+    const uint32_t q = fdiv(b, ml.cum);
+    const uint32_t c = q - fdiv(q, ml.ext_div) * ml.ext;
+    const uint32_t sum_in = row_scan_add(c * ml.stride_in);
+    const uint32_t sum_out = row_scan_add(c * ml.stride_out);
+    MajorPos p;
+    p.in = read_lane(sum_in, 15);
+    p.out = read_lane(sum_out, 15);
+    p.rem_a = split_remaining(d.split_ext[0], d.split_tile[0], read_lane(c, d.lane_a));
+    p.rem_b = split_remaining(d.split_ext[1], d.split_tile[1], read_lane(c, d.lane_b));
+    return p;
+}
+
+__device__ __forceinline__ bool slot_valid(uint32_t packed, uint32_t rem_a, uint32_t rem_b) {
+    return ((packed & 0xFFFFu) < rem_a) && ((packed >> 16) < rem_b);
+}
+
+// ---------------------------------------------------------------------------------------
+// buffer addressing
+// ---------------------------------------------------------------------------------------
+// Global accesses of the tile kernel go through buffer instructions: a 128-bit resource in
+// scalar registers describes the whole tensor, the tile's major offset rides in the scalar
+// offset operand and each lane supplies only its 32-bit minor byte offset.  One VGPR per
+// address instead of two, no 64-bit vector adds, and the hardware drops any access past
+// the end of the tensor.
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T> struct Elem;
+template <> struct Elem<uint32_t> {
+    typedef uint32_t reg;
+    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+    }
+    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
+                                                 uint32_t soff) {
+        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, 0);
+    }
+};
+template <> struct Elem<uint64_t> {
+    typedef u32x2 reg;
+    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+    }
+    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
+                                                 uint32_t soff) {
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, 0);
+    }
+};
+
+// Raw (untyped, unstrided) buffer resource over `bytes` bytes starting at p.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// ---------------------------------------------------------------------------------------
+// the tile kernel
+// ---------------------------------------------------------------------------------------
+
+template <typename T, int NREG, bool USE_LDS>
+__global__ void __launch_bounds__(TPERM_THREADS)
+tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
+    typedef typename Elem<T>::reg reg_t;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    reg_t* lds = reinterpret_cast<reg_t*>(smem_raw);
+    const uint32_t tid = threadIdx.x;
+    const __amdgpu_buffer_rsrc_t rsrc_in = make_rsrc(in, nbytes);
+    const __amdgpu_buffer_rsrc_t rsrc_out = make_rsrc(out, nbytes);
+
+    // minor positions of this thread's slots; global offsets are kept in BYTES
+    uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
+    uint32_t lds_pos[NREG];  // low half: slot written on the read side; high half: slot
+                             // read on the write side
+#pragma unroll
+    for (int j = 0; j < NREG; ++j) {
+        const uint32_t k = tid + (uint32_t)j * TPERM_THREADS;
+        rd_off[j] = 0;
+        wr_off[j] = 0;
+        lds_pos[j] = 0;
+        rd_mask[j] = 0xFFFFFFFFu;  // coordinates no remaining extent exceeds: slot unused
+        wr_mask[j] = 0xFFFFFFFFu;
+        if (k < d.tile_vol) {
+            const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
+            wr_off[j] = so.goff * (uint32_t)sizeof(T);
+            wr_mask[j] = so.xa | (so.xb << 16);
+            if (USE_LDS) {
+                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
+                rd_off[j] = si.goff * (uint32_t)sizeof(T);
+                rd_mask[j] = si.xa | (si.xb << 16);
+                lds_pos[j] = si.loff | (so.loff << 16);
+            } else {
+                rd_off[j] = so.ooff * (uint32_t)sizeof(T);
+                rd_mask[j] = wr_mask[j];
+            }
+        }
+    }
+
+    const uint32_t lane16 = tid & 15u;
+    MajorLane ml;
+    ml.cum = d.major.cum[lane16];
+    ml.ext_div = d.major.ext_div[lane16];
+    ml.ext = d.major.ext[lane16];
+    ml.stride_in = d.major.stride_in[lane16];
+    ml.stride_out = d.major.stride_out[lane16];
+
+    const uint32_t grid = gridDim.x, block = blockIdx.x;
+    uint32_t it = 0;
+    uint32_t b = tile_of(d, block, grid, it);
+    reg_t v[NREG];
+    MajorPos pos;
+    pos.in = pos.out = 0;
+    pos.rem_a = pos.rem_b = 0;
+    if (b < d.num_tiles) {
+        pos = major_position(d, ml, b);
+        const uint32_t soff = pos.in * (uint32_t)sizeof(T);
+#pragma unroll
+        for (int j = 0; j < NREG; ++j)
+            if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
+                v[j] = Elem<T>::load(rsrc_in, rd_off[j], soff);
+    }
+    while (b < d.num_tiles) {
+        const MajorPos cur = pos;
+        reg_t w[NREG];
+        if (USE_LDS) {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(rd_mask[j], cur.rem_a, cur.rem_b)) lds[lds_pos[j] & 0xFFFFu] = v[j];
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(wr_mask[j], cur.rem_a, cur.rem_b)) w[j] = lds[lds_pos[j] >> 16];
+        } else {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j) w[j] = v[j];
+        }
+        // reads of the next tile go out before the stores of this one
+        ++it;
+        const uint32_t bn = tile_of(d, block, grid, it);
+        if (bn < d.num_tiles) {
+            pos = major_position(d, ml, bn);
+            const uint32_t soff = pos.in * (uint32_t)sizeof(T);
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
+                    v[j] = Elem<T>::load(rsrc_in, rd_off[j], soff);
+        }
+        const uint32_t soff_out = cur.out * (uint32_t)sizeof(T);
+#pragma unroll
+        for (int j = 0; j < NREG; ++j)
+            if (slot_valid(wr_mask[j], cur.rem_a, cur.rem_b))
+                Elem<T>::store(w[j], rsrc_out, wr_off[j], soff_out);
+        if (USE_LDS) __syncthreads();  // every wave has finished reading this LDS image
+        b = bn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// plain copy and naive gather
+// ---------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256)
+copy16_kernel(const uint4* __restrict__ in, uint4* __restrict__ out, uint64_t n16) {
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = in[i], b = in[i + stride], c = in[i + 2 * stride], e = in[i + 3 * stride];
+        out[i] = a;
+        out[i + stride] = b;
+        out[i + 2 * stride] = c;
+        out[i + 3 * stride] = e;
+    }
+    for (; i < n16; i += stride) out[i] = in[i];
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+copy_elem_kernel(const T* __restrict__ in, T* __restrict__ out, uint64_t n) {
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n; i += stride) out[i] = in[i];
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+naive_kernel(const NaiveDesc d, const T* __restrict__ in, T* __restrict__ out) {
+    const uint64_t o = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (o < d.volume) out[o] = in[naive_input_offset(d, (uint32_t)o)];
+}
+
+// ---------------------------------------------------------------------------------------
+// dispatch
+// ---------------------------------------------------------------------------------------
+
+template <typename T, bool USE_LDS>
+static const void* tile_kernel_ptr(int nreg) {
+    switch (nreg) {
+#define TPERM_CASE(N) \
+    case N:           \
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, USE_LDS>);
+        TPERM_CASE(1)
+        TPERM_CASE(2)
+        TPERM_CASE(3)
+        TPERM_CASE(4)
+        TPERM_CASE(6)
+        TPERM_CASE(8)
+        TPERM_CASE(12)
+        TPERM_CASE(16)
+        TPERM_CASE(24)
+        TPERM_CASE(32)
+#undef TPERM_CASE
+        default:
+            return nullptr;
+    }
+}
+
+static const void* tile_kernel_for(const Plan& plan) {
+    if (plan.elem == 8)
+        return plan.use_lds ? tile_kernel_ptr<uint64_t, true>(plan.nreg)
+                            : tile_kernel_ptr<uint64_t, false>(plan.nreg);
+    return plan.use_lds ? tile_kernel_ptr<uint32_t, true>(plan.nreg)
+                        : tile_kernel_ptr<uint32_t, false>(plan.nreg);
+}
+
+hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {
+    const void* f = tile_kernel_for(plan);
+    if (f == nullptr) return hipErrorInvalidValue;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, f, TPERM_THREADS,
+                                                        (size_t)plan.lds_bytes);
+}
+
+hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid) {
+    const void* f = tile_kernel_for(plan);
+    if (f == nullptr || grid < 1) return hipErrorInvalidValue;
+    TileDesc d = plan.tile;
+    uint32_t nbytes = (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
+    void* args[] = {(void*)&d, (void*)&in, (void*)&out, (void*)&nbytes};
+    return hipLaunchKernel(f, dim3((unsigned)grid), dim3(TPERM_THREADS), args,
+                           (size_t)plan.lds_bytes, stream);
+}
+
+hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream) {
+    const uint64_t vol = (uint64_t)plan.c.volume;
+    const unsigned grid = (unsigned)((vol + 255) / 256);
+    if (plan.elem == 8)
+        hipLaunchKernelGGL(naive_kernel<uint64_t>, dim3(grid), dim3(256), 0, stream, plan.naive,
+                           (const uint64_t*)in, (uint64_t*)out);
+    else
+        hipLaunchKernelGGL(naive_kernel<uint32_t>, dim3(grid), dim3(256), 0, stream, plan.naive,
+                           (const uint32_t*)in, (uint32_t*)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(const void* in, void* out, size_t nbytes, int elem, int num_cu,
+                       hipStream_t stream) {
+    if (nbytes == 0) return hipSuccess;
+    const unsigned max_grid = (unsigned)(num_cu > 0 ? num_cu : 256) * 8u;
+    auto grid_for = [&](uint64_t n) {
+        const uint64_t g = (n + 255) / 256;
+        return (unsigned)(g < max_grid ? (g ? g : 1) : max_grid);
+    };
+    const bool aligned16 = (((uintptr_t)in | (uintptr_t)out) & 15u) == 0;
+    if (aligned16 && nbytes >= 16) {
+        const uint64_t n16 = nbytes / 16;
+        hipLaunchKernelGGL(copy16_kernel, dim3(grid_for(n16)), dim3(256), 0, stream,
+                           (const uint4*)in, (uint4*)out, n16);
+        const size_t done = (size_t)n16 * 16, tail = nbytes - done;
+        if (tail) {
+            hipLaunchKernelGGL(copy_elem_kernel<uint32_t>, dim3(1), dim3(256), 0, stream,
+                               (const uint32_t*)((const char*)in + done),
+                               (uint32_t*)((char*)out + done), (uint64_t)(tail / 4));
+        }
+    } else if (elem == 8) {
+        const uint64_t n = nbytes / 8;
+        hipLaunchKernelGGL(copy_elem_kernel<uint64_t>, dim3(grid_for(n)), dim3(256), 0, stream,
+                           (const uint64_t*)in, (uint64_t*)out, n);
+    } else {
+        const uint64_t n = nbytes / 4;
+        hipLaunchKernelGGL(copy_elem_kernel<uint32_t>, dim3(grid_for(n)), dim3(256), 0, stream,
+                           (const uint32_t*)in, (uint32_t*)out, n);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tperm

@@ -1,0 +1,22 @@
+// Launch interface between the C-ABI layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "plan.hpp"
+
+namespace tperm {
+
+// Workgroups of this plan's tile kernel that fit one compute unit (occupancy query).
+hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks);
+
+// Enqueue the tile kernel (ROWCOPY / TILED / PACKED classes) with `grid` workgroups.
+hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid);
+
+// Enqueue the naive one-thread-per-output-element gather.
+hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream);
+
+// Enqueue a plain copy of nbytes; elem is the guaranteed pointer alignment (4 or 8).
+hipError_t launch_copy(const void* in, void* out, size_t nbytes, int elem, int num_cu,
+                       hipStream_t stream);
+
+}  // namespace tperm

@@ -1,0 +1,756 @@
+// Host-side planner.  See plan.hpp.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+namespace tperm {
+
+const int kNregSet[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+const int kNregSetSize = (int)(sizeof(kNregSet) / sizeof(kNregSet[0]));
+
+// ---------------------------------------------------------------------------------------
+// validation and canonical form
+// ---------------------------------------------------------------------------------------
+
+tperm_status_t validate(int rank, const int64_t* dims, const int* perm, size_t elem) {
+    if (dims == nullptr || perm == nullptr) return TPERM_ERR_NULL;
+    if (rank < 1 || rank > TPERM_MAX_RANK) return TPERM_ERR_RANK;
+    if (elem != 4 && elem != 8) return TPERM_ERR_ELEM_SIZE;
+    bool seen[TPERM_MAX_RANK] = {false};
+    for (int j = 0; j < rank; ++j) {
+        if (perm[j] < 0 || perm[j] >= rank || seen[perm[j]]) return TPERM_ERR_PERM;
+        seen[perm[j]] = true;
+    }
+    int64_t vol = 1;
+    for (int z = 0; z < rank; ++z) {
+        if (dims[z] < 1) return TPERM_ERR_DIMS;
+    }
+    for (int z = 0; z < rank; ++z) {
+        if (dims[z] >= ((int64_t)1 << 31)) return TPERM_ERR_TOO_LARGE;
+        vol *= dims[z];
+        if (vol >= ((int64_t)1 << 31)) return TPERM_ERR_TOO_LARGE;
+    }
+    // byte offsets inside the tensor are kept in 32 bits (buffer addressing)
+    if (vol * (int64_t)elem >= ((int64_t)1 << 32) - 256) return TPERM_ERR_TOO_LARGE;
+    return TPERM_OK;
+}
+
+// Drop extent-1 dims, then fuse input dims z, z+1 that sit next to each other and in the
+// same order in the output: such a pair moves as one dimension of extent d(z)*d(z+1).
+// Neither step changes where any element goes.
+void canonicalise(int rank, const int64_t* dims, const int* perm, Canonical* out) {
+    // output order without extent-1 dims
+    int ord[TPERM_MAX_RANK];
+    int n = 0;
+    for (int j = 0; j < rank; ++j)
+        if (dims[perm[j]] > 1) ord[n++] = perm[j];
+    Canonical c;
+    c.volume = 1;
+    for (int z = 0; z < rank; ++z) c.volume *= dims[z];
+    if (n == 0) {
+        c.rank = 1;
+        c.dims[0] = 1;
+        c.perm[0] = 0;
+        *out = c;
+        return;
+    }
+    // groups of output positions whose input dims are consecutive among the kept dims
+    // (kept dims are consecutive if no kept dim lies strictly between them)
+    bool kept[TPERM_MAX_RANK] = {false};
+    for (int j = 0; j < n; ++j) kept[ord[j]] = true;
+    auto next_kept = [&](int z) {
+        for (int t = z + 1; t < rank; ++t)
+            if (kept[t]) return t;
+        return -1;
+    };
+    int group_first[TPERM_MAX_RANK];  // first input dim of each group, in output order
+    int64_t group_ext[TPERM_MAX_RANK];
+    int g = 0;
+    for (int j = 0; j < n;) {
+        int first = ord[j];
+        int64_t ext = dims[first];
+        int last = first;
+        int jj = j + 1;
+        while (jj < n && ord[jj] == next_kept(last)) {
+            last = ord[jj];
+            ext *= dims[last];
+            ++jj;
+        }
+        group_first[g] = first;
+        group_ext[g] = ext;
+        ++g;
+        j = jj;
+    }
+    // new input order = groups sorted by their first input dim
+    int idx[TPERM_MAX_RANK];
+    for (int i = 0; i < g; ++i) idx[i] = i;
+    std::sort(idx, idx + g, [&](int a, int b) { return group_first[a] < group_first[b]; });
+    int new_id[TPERM_MAX_RANK];  // group (output order) -> canonical input dim
+    for (int z = 0; z < g; ++z) {
+        new_id[idx[z]] = z;
+        c.dims[z] = group_ext[idx[z]];
+    }
+    for (int j = 0; j < g; ++j) c.perm[j] = new_id[j];
+    c.rank = g;
+    *out = c;
+}
+
+FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    if (d == 0) d = 1;
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    f.shift = 31 + l;
+    const uint64_t pow = (uint64_t)1 << f.shift;
+    f.magic = (uint32_t)((pow + d - 1) / d);
+    return f;
+}
+
+// ---------------------------------------------------------------------------------------
+// candidate tiles
+// ---------------------------------------------------------------------------------------
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static int64_t gcd64(int64_t a, int64_t b) {
+    while (b) {
+        int64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+
+// Expected number of 128-byte lines touched per useful 128 bytes by runs of run_bytes that
+// start on multiples of `granule` bytes (granule a divisor of 128, or 128 itself).
+static double line_overhead(double run_bytes, double granule) {
+    return (run_bytes + 128.0 - granule) / run_bytes;
+}
+
+// Fill the derived fields of a candidate from its tile extents; false if unusable.
+static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
+    const int r = c.rank;
+    int inv[TPERM_MAX_RANK];
+    for (int j = 0; j < r; ++j) inv[c.perm[j]] = j;
+    int64_t sI[TPERM_MAX_RANK], sO[TPERM_MAX_RANK];
+    sI[0] = 1;
+    for (int z = 1; z < r; ++z) sI[z] = sI[z - 1] * c.dims[z - 1];
+    sO[0] = 1;
+    for (int j = 1; j < r; ++j) sO[j] = sO[j - 1] * c.dims[c.perm[j - 1]];
+
+    int splits = 0;
+    int64_t vol = 1, tiles = 1;
+    double util = 1.0;
+    int n_tile_dims = 0, n_outer = 0;
+    for (int z = 0; z < r; ++z) {
+        const int64_t t = cd->t[z], d = c.dims[z];
+        if (t < 1 || t > d) return false;
+        if (t > 1) {
+            vol *= t;
+            ++n_tile_dims;
+        }
+        if (t < d) {
+            const int64_t n = ceil_div(d, t);
+            tiles *= n;
+            util *= (double)d / (double)(n * t);
+            if (t > 1) ++splits; else ++n_outer;
+        }
+        if (t > 0x7FFF) return false;
+    }
+    if (n_tile_dims == 0) return false;
+    if (splits > 2) return false;
+    if (splits + n_outer > TPERM_DESC_MAX_DIMS) return false;
+    if (vol > kMaxTileVol) return false;
+    if (tiles >= ((int64_t)1 << 31)) return false;
+    // contiguous run on the input side: leading dims, all but the last at full extent
+    int64_t run_in = 1;
+    for (int z = 0; z < r; ++z) {
+        run_in *= cd->t[z];
+        if (cd->t[z] < c.dims[z]) break;
+    }
+    int64_t run_out = 1;
+    for (int j = 0; j < r; ++j) {
+        const int z = c.perm[j];
+        run_out *= cd->t[z];
+        if (cd->t[z] < c.dims[z]) break;
+    }
+    cd->tile_vol = vol;
+    cd->num_tiles = tiles;
+    cd->run_in = run_in;
+    cd->run_out = run_out;
+    cd->utilisation = util;
+    if (cd->use_lds && vol * elem > kMaxLdsBytes) return false;  // unpadded image must fit
+
+    // Alignment granule of run starts on each side: every stride that separates two runs
+    // (the strides of all dims other than the run's own leading dims, and the chunk step
+    // of a split leading dim) is a multiple of it.
+    auto granule = [&](bool input) {
+        int64_t g = 128;
+        bool in_run = true;
+        for (int p = 0; p < r; ++p) {
+            const int z = input ? p : c.perm[p];
+            const int64_t stride = (input ? sI[p] : sO[p]) * elem;
+            if (in_run) {
+                if (cd->t[z] < c.dims[z]) {
+                    // split (or outer) dim ends the run; its chunks start t*stride apart
+                    g = gcd64(g, stride * cd->t[z]);
+                    in_run = false;
+                }
+            } else {
+                g = gcd64(g, stride);
+            }
+        }
+        return (double)g;
+    };
+    const double rin = (double)(cd->use_lds ? run_in : cd->t[0]) * elem;
+    const double rout = (double)run_out * elem;
+    double gin = granule(true), gout = granule(false);
+    if (!cd->use_lds) {
+        // rows are read in output-lane order: contiguous only along dim 0
+        gin = (double)gcd64(128, (r > 1 ? sI[1] : 1) * elem);
+        if (cd->t[0] < c.dims[0]) gin = (double)gcd64((int64_t)gin, cd->t[0] * elem);
+    }
+    // Cost per useful byte: lines touched on the read side plus lines touched on the write
+    // side, where a partially written line costs about twice a full one (cf. Eq. (13)).
+    const double cost_in = line_overhead(rin, gin);
+    const double over_out = line_overhead(rout, gout);
+    const double cost_out = 1.0 + 2.0 * (over_out - 1.0);
+    double cost = (cost_in + cost_out) / util;
+    // Short runs also waste lanes of the 64-wide wavefront's memory instruction.
+    const double bytes = (double)vol * elem;
+    // Small tiles keep too few bytes in flight per workgroup; very large ones cut occupancy.
+    if (bytes < 8192.0) cost *= 1.0 + 0.15 * std::log2(8192.0 / bytes);
+    if (bytes > 32768.0) cost *= 1.0 + 0.10 * std::log2(bytes / 32768.0);
+    // Too few tiles cannot fill 256 compute units.
+    if (tiles < 1024) cost *= 1.0 + 0.5 * std::log2(1024.0 / (double)tiles) / 10.0;
+    // The LDS stage itself is not free.
+    if (cd->use_lds) cost *= 1.03;
+    cd->score = cost;
+    return true;
+}
+
+// Tile extents proposed for one side: take the first `count` dims of `order` whole except
+// the last, which gets extent `last`.
+struct SideChoice {
+    int count;
+    int64_t last;
+};
+
+static std::vector<SideChoice> side_choices(const Canonical& c, const int* order) {
+    static const int64_t targets[] = {4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048};
+    std::vector<SideChoice> v;
+    int64_t prefix = 1;
+    for (int n = 1; n <= c.rank; ++n) {
+        const int64_t d = c.dims[order[n - 1]];
+        for (int64_t target : targets) {
+            if (prefix >= target) continue;
+            int64_t t = std::min(d, ceil_div(target, prefix));
+            const int64_t chunks = ceil_div(d, t);
+            t = ceil_div(d, chunks);  // balance the chunks
+            if (prefix * t > kMaxTileVol) continue;
+            bool dup = false;
+            for (const auto& s : v) dup |= (s.count == n && s.last == t);
+            if (!dup) v.push_back({n, t});
+            // also the unbalanced power-of-two-ish chunk (keeps chunk starts aligned)
+            const int64_t t2 = std::min(d, ceil_div(target, prefix));
+            if (t2 != t && prefix * t2 <= kMaxTileVol) {
+                dup = false;
+                for (const auto& s : v) dup |= (s.count == n && s.last == t2);
+                if (!dup) v.push_back({n, t2});
+            }
+        }
+        if (prefix * d <= kMaxTileVol) {
+            bool dup = false;
+            for (const auto& s : v) dup |= (s.count == n && s.last == d);
+            if (!dup) v.push_back({n, d});
+        }
+        prefix *= d;
+        if (prefix >= 2048) break;
+    }
+    return v;
+}
+
+bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
+                    int64_t tile_out, bool use_lds, Candidate* out) {
+    const int r = c.rank;
+    if (m < 1 || m > r || k < 1 || k > r) return false;
+    Candidate cd;
+    cd.m = m;
+    cd.k = k;
+    cd.use_lds = use_lds;
+    for (int z = 0; z < r; ++z) cd.t[z] = 1;
+    for (int z = 0; z < m - 1; ++z) cd.t[z] = c.dims[z];
+    const int za = m - 1;
+    if (tile_in <= 0 || tile_in > c.dims[za]) tile_in = c.dims[za];
+    cd.t[za] = std::max(cd.t[za], tile_in);
+    for (int j = 0; j < k - 1; ++j) cd.t[c.perm[j]] = c.dims[c.perm[j]];
+    const int zb = c.perm[k - 1];
+    if (tile_out <= 0 || tile_out > c.dims[zb]) tile_out = c.dims[zb];
+    cd.t[zb] = std::max(cd.t[zb], tile_out);
+    if (!use_lds && c.perm[0] != 0) return false;  // LDS-free only when dim 0 stays first
+    if (!finish_candidate(c, elem, &cd)) return false;
+    if (!use_lds)
+        cd.kclass = TPERM_KERNEL_ROWCOPY;
+    else if (m == 1 && k == 1 && c.perm[0] != 0)
+        cd.kclass = TPERM_KERNEL_TILED;
+    else
+        cd.kclass = TPERM_KERNEL_PACKED;
+    *out = cd;
+    return true;
+}
+
+std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem) {
+    std::vector<Candidate> out;
+    if (c.rank < 2) return out;
+    int in_order[TPERM_MAX_RANK];
+    for (int z = 0; z < c.rank; ++z) in_order[z] = z;
+    const auto ins = side_choices(c, in_order);
+    const auto outs = side_choices(c, c.perm);
+    auto push = [&](const Candidate& cd) {
+        for (const auto& o : out) {
+            if (o.use_lds != cd.use_lds) continue;
+            bool same = true;
+            for (int z = 0; z < c.rank; ++z) same &= (o.t[z] == cd.t[z]);
+            if (same) return;
+        }
+        out.push_back(cd);
+    };
+    for (const auto& a : ins)
+        for (const auto& b : outs) {
+            Candidate cd;
+            if (make_candidate(c, elem, a.count, a.last, b.count, b.last, true, &cd)) push(cd);
+        }
+    if (c.perm[0] == 0) {
+        // LDS-free row copy: the tile is taken in output order only
+        for (const auto& b : outs) {
+            Candidate cd;
+            if (make_candidate(c, elem, 1, b.count == 1 ? b.last : 0, b.count, b.last, false, &cd))
+                push(cd);
+        }
+    }
+    std::stable_sort(out.begin(), out.end(),
+                     [](const Candidate& x, const Candidate& y) { return x.score < y.score; });
+    return out;
+}
+
+// ---------------------------------------------------------------------------------------
+// descriptor construction
+// ---------------------------------------------------------------------------------------
+
+static int pick_nreg(int64_t tile_vol) {
+    const int64_t need = ceil_div(tile_vol, TPERM_THREADS);
+    for (int i = 0; i < kNregSetSize; ++i)
+        if (kNregSet[i] >= need) return kNregSet[i];
+    return -1;
+}
+
+// LDS cost of the first slots of each wavefront: for every wavefront-wide access, the
+// largest number of distinct addresses that fall into one bank (64 banks of 4 bytes; an
+// 8-byte access is served per half wavefront and occupies two banks).
+double lds_conflict_cost(const TileDesc& d, int elem, int nreg) {
+    const int kBanks = 64;
+    double total = 0.0;
+    const int slots = std::min(nreg, 4);
+    for (int side = 0; side < 2; ++side) {
+        const TileDim* dims = side == 0 ? d.in_order : d.out_order;
+        for (int w = 0; w < TPERM_THREADS / 64; ++w)
+            for (int j = 0; j < slots; ++j) {
+                const int groups = elem == 8 ? 2 : 1;
+                const int lanes = 64 / groups;
+                for (int gidx = 0; gidx < groups; ++gidx) {
+                    uint32_t addr[64];
+                    int n = 0;
+                    for (int l = 0; l < lanes; ++l) {
+                        const uint32_t k = (uint32_t)(w * 64 + gidx * lanes + l + j * TPERM_THREADS);
+                        if (k >= d.tile_vol) continue;
+                        addr[n++] = tile_slot(dims, d.n_tile_dims, k).loff;
+                    }
+                    int worst = 0;
+                    for (int b = 0; b < kBanks; b += (elem == 8 ? 2 : 1)) {
+                        uint32_t seen[64];
+                        int ns = 0;
+                        for (int i = 0; i < n; ++i) {
+                            const uint32_t word = addr[i] * (uint32_t)(elem / 4);
+                            if ((int)(word % kBanks) != b) continue;
+                            bool dup = false;
+                            for (int s = 0; s < ns; ++s) dup |= (seen[s] == addr[i]);
+                            if (!dup) seen[ns++] = addr[i];
+                        }
+                        worst = std::max(worst, ns);
+                    }
+                    total += worst;
+                }
+            }
+    }
+    return total;
+}
+
+// Fill the LDS strides of both dim lists for a given row padding; returns LDS elements.
+static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* dim_of_out,
+                                int run_dims, uint32_t pad) {
+    uint32_t lstride[TPERM_DESC_MAX_DIMS];
+    uint32_t cum = 1;
+    const uint32_t n = d->n_tile_dims;
+    for (uint32_t i = 0; i < n; ++i) {
+        if ((int)i == run_dims && run_dims > 0 && i < n) cum += pad;  // pitch after the run
+        lstride[i] = cum;
+        cum *= d->in_order[i].ext;
+        d->in_order[i].lstride = lstride[i];
+    }
+    for (uint32_t j = 0; j < n; ++j)
+        for (uint32_t i = 0; i < n; ++i)
+            if (dim_of_out[j] == dim_of_in[i]) d->out_order[j].lstride = lstride[i];
+    return cum;
+}
+
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode) {
+    const Canonical& c = plan->c;
+    const int r = c.rank;
+    const int elem = plan->elem;
+    int inv[TPERM_MAX_RANK];
+    for (int j = 0; j < r; ++j) inv[c.perm[j]] = j;
+    int64_t sI[TPERM_MAX_RANK], sO[TPERM_MAX_RANK];
+    sI[0] = 1;
+    for (int z = 1; z < r; ++z) sI[z] = sI[z - 1] * c.dims[z - 1];
+    sO[0] = 1;
+    for (int j = 1; j < r; ++j) sO[j] = sO[j - 1] * c.dims[c.perm[j - 1]];
+
+    TileDesc d;
+    std::memset(&d, 0, sizeof(d));
+    // split dims: A = first split dim in input order, B = the second
+    int split_dim[2] = {-1, -1};
+    for (int z = 0, s = 0; z < r; ++z)
+        if (cand.t[z] > 1 && cand.t[z] < c.dims[z]) {
+            if (s >= 2) return TPERM_ERR_KERNEL;
+            split_dim[s++] = z;
+        }
+    auto sel_of = [&](int z) -> uint32_t {
+        return z == split_dim[0] ? 1u : (z == split_dim[1] ? 2u : 0u);
+    };
+    // tile dims in input order and in output order
+    int dim_of_in[TPERM_DESC_MAX_DIMS], dim_of_out[TPERM_DESC_MAX_DIMS];
+    uint32_t n = 0;
+    for (int z = 0; z < r; ++z)
+        if (cand.t[z] > 1) {
+            TileDim& td = d.in_order[n];
+            td.ext = (uint32_t)cand.t[z];
+            td.div = make_fastdiv(td.ext);
+            td.gstride = (uint32_t)sI[z];
+            td.ostride = (uint32_t)sO[inv[z]];
+            td.sel = sel_of(z);
+            dim_of_in[n++] = z;
+        }
+    uint32_t n2 = 0;
+    for (int j = 0; j < r; ++j) {
+        const int z = c.perm[j];
+        if (cand.t[z] > 1) {
+            TileDim& td = d.out_order[n2];
+            td.ext = (uint32_t)cand.t[z];
+            td.div = make_fastdiv(td.ext);
+            td.gstride = (uint32_t)sO[j];
+            td.ostride = (uint32_t)sI[z];
+            td.sel = sel_of(z);
+            dim_of_out[n2++] = z;
+        }
+    }
+    d.n_tile_dims = n;
+    d.tile_vol = (uint32_t)cand.tile_vol;
+    d.num_tiles = (uint32_t)cand.num_tiles;
+    for (int s = 0; s < 2; ++s) {
+        d.split_ext[s] = split_dim[s] >= 0 ? (uint32_t)c.dims[split_dim[s]] : 0u;
+        d.split_tile[s] = split_dim[s] >= 0 ? (uint32_t)cand.t[split_dim[s]] : 0u;
+    }
+    // major terms: chunk counters of the split dims first (so that consecutive tiles are
+    // neighbours along the input run), then the outer dims in input order
+    for (int l = 0; l < TPERM_DESC_MAX_DIMS; ++l) {
+        d.major.cum[l] = make_fastdiv(1);
+        d.major.ext_div[l] = make_fastdiv(1);
+        d.major.ext[l] = 1;
+        d.major.stride_in[l] = 0;
+        d.major.stride_out[l] = 0;
+    }
+    uint32_t lane = 0;
+    uint64_t cum = 1;
+    auto add_major = [&](uint32_t ext, uint64_t sin, uint64_t sout) {
+        d.major.cum[lane] = make_fastdiv((uint32_t)cum);
+        d.major.ext_div[lane] = make_fastdiv(ext);
+        d.major.ext[lane] = ext;
+        d.major.stride_in[lane] = (uint32_t)sin;
+        d.major.stride_out[lane] = (uint32_t)sout;
+        cum *= ext;
+        ++lane;
+    };
+    d.lane_a = d.lane_b = 0;
+    for (int s = 0; s < 2; ++s)
+        if (split_dim[s] >= 0) {
+            const int z = split_dim[s];
+            (s == 0 ? d.lane_a : d.lane_b) = lane;
+            add_major((uint32_t)ceil_div(c.dims[z], cand.t[z]), (uint64_t)cand.t[z] * sI[z],
+                      (uint64_t)cand.t[z] * sO[inv[z]]);
+        }
+    for (int z = 0; z < r; ++z)
+        if (cand.t[z] == 1 && c.dims[z] > 1) {
+            if (lane >= TPERM_DESC_MAX_DIMS) return TPERM_ERR_KERNEL;
+            add_major((uint32_t)c.dims[z], (uint64_t)sI[z], (uint64_t)sO[inv[z]]);
+        }
+    d.n_major = lane;
+    if (cum != (uint64_t)cand.num_tiles) return TPERM_ERR_INTERNAL;
+
+    const int nreg = pick_nreg(cand.tile_vol);
+    if (nreg < 0) return TPERM_ERR_KERNEL;
+
+    // LDS image: tile in input order, rows of the contiguous input run separated by a
+    // padded pitch chosen to minimise bank conflicts of the transposed read
+    int run_dims = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        // dims of the run are the leading canonical dims 0,1,..: tile dim i belongs to
+        // the run if it is canonical dim i and all earlier ones were taken whole
+        if (dim_of_in[i] != (int)i) break;
+        ++run_dims;
+        if (cand.t[i] < c.dims[i]) break;
+    }
+    int pad = 0;
+    uint32_t lds_elems = 0;
+    if (cand.use_lds) {
+        if (lds_pad >= 0) {
+            pad = lds_pad;
+            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)pad);
+        } else if (run_dims >= (int)n) {
+            pad = 0;
+            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, 0);
+        } else {
+            double best = 1e300;
+            int best_pad = 0;
+            const int max_pad = elem == 8 ? 16 : 32;
+            for (int p = 0; p <= max_pad; ++p) {
+                const uint32_t le = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)p);
+                if ((int64_t)le * elem > kMaxLdsBytes) break;
+                const double cost = lds_conflict_cost(d, elem, nreg);
+                if (cost < best - 1e-9) {
+                    best = cost;
+                    best_pad = p;
+                }
+            }
+            pad = best_pad;
+            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)pad);
+        }
+        if ((int64_t)lds_elems * elem > kMaxLdsBytes) return TPERM_ERR_KERNEL;
+        if (lds_elems > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
+    }
+    d.lds_elems = lds_elems;
+    d.grid_mode = (uint32_t)grid_mode;
+    d.tiles_per_xcd = (uint32_t)ceil_div(cand.num_tiles, 8);
+
+    plan->tile = d;
+    plan->cand = cand;
+    plan->kclass = cand.kclass;
+    plan->use_lds = cand.use_lds;
+    plan->nreg = nreg;
+    plan->lds_pad = pad;
+    plan->lds_bytes = (int)((int64_t)lds_elems * elem);
+    plan->grid_mode = grid_mode;
+    return TPERM_OK;
+}
+
+void build_naive_desc(Plan* plan) {
+    const Canonical& c = plan->c;
+    NaiveDesc nd;
+    std::memset(&nd, 0, sizeof(nd));
+    nd.rank = (uint32_t)c.rank;
+    nd.volume = (uint32_t)c.volume;
+    int64_t sI[TPERM_MAX_RANK];
+    sI[0] = 1;
+    for (int z = 1; z < c.rank; ++z) sI[z] = sI[z - 1] * c.dims[z - 1];
+    for (int j = 0; j < c.rank; ++j) {
+        nd.out_ext[j] = (uint32_t)c.dims[c.perm[j]];
+        nd.out_ext_div[j] = make_fastdiv(nd.out_ext[j]);
+        nd.in_stride[j] = (uint32_t)sI[c.perm[j]];
+    }
+    plan->naive = nd;
+}
+
+// ---------------------------------------------------------------------------------------
+// plan creation
+// ---------------------------------------------------------------------------------------
+
+tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int* perm,
+                           size_t elem, const tperm_plan_opts_t* opts) {
+    if (out == nullptr) return TPERM_ERR_NULL;
+    *out = nullptr;
+    tperm_status_t st = validate(rank, dims, perm, elem);
+    if (st != TPERM_OK) return st;
+    Plan* p = new (std::nothrow) Plan();
+    if (p == nullptr) return TPERM_ERR_NOMEM;
+    p->rank = rank;
+    for (int z = 0; z < rank; ++z) {
+        p->dims[z] = dims[z];
+        p->perm[z] = perm[z];
+    }
+    p->elem = (int)elem;
+    canonicalise(rank, dims, perm, &p->c);
+    std::memset(&p->tile, 0, sizeof(p->tile));
+    build_naive_desc(p);
+
+    tperm_plan_opts_t o;
+    std::memset(&o, 0, sizeof(o));
+    o.lds_pad = -1;
+    if (opts) o = *opts;
+    const int want = o.kernel_class;
+    const bool identity = (p->c.rank == 1);
+
+    auto fail = [&](tperm_status_t s) {
+        delete p;
+        return s;
+    };
+
+    if (want == TPERM_KERNEL_NAIVE) {
+        p->kclass = TPERM_KERNEL_NAIVE;
+        *out = p;
+        return TPERM_OK;
+    }
+    if (identity) {
+        if (want != TPERM_KERNEL_AUTO && want != TPERM_KERNEL_COPY) return fail(TPERM_ERR_KERNEL);
+        p->kclass = TPERM_KERNEL_COPY;
+        *out = p;
+        return TPERM_OK;
+    }
+    if (want == TPERM_KERNEL_COPY) return fail(TPERM_ERR_KERNEL);
+    if (want < 0 || want > TPERM_KERNEL_NAIVE) return fail(TPERM_ERR_KERNEL);
+
+    Candidate chosen;
+    bool have = false;
+    if (o.m > 0 || o.k > 0) {
+        const int m = o.m > 0 ? o.m : 1, k = o.k > 0 ? o.k : 1;
+        const bool use_lds = (want != TPERM_KERNEL_ROWCOPY);
+        if (!make_candidate(p->c, p->elem, m, o.tile_in, k, o.tile_out, use_lds, &chosen))
+            return fail(TPERM_ERR_KERNEL);
+        if (want != TPERM_KERNEL_AUTO && want != chosen.kclass) {
+            // an explicit tile may be run under the PACKED label whatever its shape
+            if (!(want == TPERM_KERNEL_PACKED && chosen.use_lds)) return fail(TPERM_ERR_KERNEL);
+            chosen.kclass = TPERM_KERNEL_PACKED;
+        }
+        have = true;
+    } else {
+        const auto cands = enumerate_candidates(p->c, p->elem);
+        for (const auto& cd : cands) {
+            if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
+            chosen = cd;
+            have = true;
+            break;
+        }
+    }
+    if (!have) return fail(TPERM_ERR_KERNEL);
+    st = build_tile_plan(p, chosen, o.lds_pad, o.grid_mode);
+    if (st != TPERM_OK) return fail(st);
+    *out = p;
+    return TPERM_OK;
+}
+
+tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* dims,
+                                          const int* perm, size_t elem, const Candidate& cand) {
+    if (out == nullptr) return TPERM_ERR_NULL;
+    *out = nullptr;
+    tperm_status_t st = validate(rank, dims, perm, elem);
+    if (st != TPERM_OK) return st;
+    Plan* p = new (std::nothrow) Plan();
+    if (p == nullptr) return TPERM_ERR_NOMEM;
+    p->rank = rank;
+    for (int z = 0; z < rank; ++z) {
+        p->dims[z] = dims[z];
+        p->perm[z] = perm[z];
+    }
+    p->elem = (int)elem;
+    canonicalise(rank, dims, perm, &p->c);
+    std::memset(&p->tile, 0, sizeof(p->tile));
+    build_naive_desc(p);
+    st = build_tile_plan(p, cand, -1, 0);
+    if (st != TPERM_OK) {
+        delete p;
+        return st;
+    }
+    *out = p;
+    return TPERM_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// host evaluation of a plan's index maps
+// ---------------------------------------------------------------------------------------
+
+tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
+    const int64_t vol = plan.c.volume;
+    for (int64_t i = 0; i < vol; ++i) out_to_in[i] = -1;
+    if (plan.kclass == TPERM_KERNEL_COPY) {
+        for (int64_t i = 0; i < vol; ++i) out_to_in[i] = i;
+        return TPERM_OK;
+    }
+    if (plan.kclass == TPERM_KERNEL_NAIVE) {
+        for (int64_t o = 0; o < vol; ++o)
+            out_to_in[o] = (int64_t)naive_input_offset(plan.naive, (uint32_t)o);
+        return TPERM_OK;
+    }
+    const TileDesc& d = plan.tile;
+    std::vector<int64_t> lds(plan.use_lds ? d.lds_elems : 1, -1);
+    const uint32_t slots = (uint32_t)plan.nreg * TPERM_THREADS;
+    if (slots < d.tile_vol) return TPERM_ERR_INTERNAL;
+    // visit tiles the way a launch with `grid` workgroups would; any grid gives the same
+    // set of tiles, use a small one that still exercises the iteration arithmetic
+    const uint32_t grid = d.grid_mode == 1u ? 16u : 7u;
+    std::vector<char> tile_seen(d.num_tiles, 0);
+    for (uint32_t block = 0; block < grid; ++block)
+        for (uint32_t it = 0;; ++it) {
+            const uint32_t b = tile_of(d, block, grid, it);
+            if (b >= d.num_tiles) break;
+            if (tile_seen[b]) return TPERM_ERR_INTERNAL;
+            tile_seen[b] = 1;
+            // major offsets: sum of the per-lane terms (Eqs. (2),(3))
+            uint64_t maj_in = 0, maj_out = 0;
+            uint32_t coord[TPERM_DESC_MAX_DIMS];
+            for (uint32_t l = 0; l < TPERM_DESC_MAX_DIMS; ++l) {
+                coord[l] = major_coord(d.major, l, b);
+                maj_in += (uint64_t)coord[l] * d.major.stride_in[l];
+                maj_out += (uint64_t)coord[l] * d.major.stride_out[l];
+            }
+            const uint32_t rem_a = split_remaining(d.split_ext[0], d.split_tile[0], coord[d.lane_a]);
+            const uint32_t rem_b = split_remaining(d.split_ext[1], d.split_tile[1], coord[d.lane_b]);
+            if (plan.use_lds) {
+                std::fill(lds.begin(), lds.end(), -1);
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.in_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && s.xb < rem_b)) continue;
+                    const uint64_t gi = maj_in + s.goff;
+                    if (gi >= (uint64_t)vol || s.loff >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                    if (lds[s.loff] != -1) return TPERM_ERR_INTERNAL;
+                    lds[s.loff] = (int64_t)gi;
+                }
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.out_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && s.xb < rem_b)) continue;
+                    const uint64_t go = maj_out + s.goff;
+                    if (go >= (uint64_t)vol || s.loff >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                    if (lds[s.loff] == -1) return TPERM_ERR_INTERNAL;
+                    if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                    out_to_in[go] = lds[s.loff];
+                }
+            } else {
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.out_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && s.xb < rem_b)) continue;
+                    const uint64_t go = maj_out + s.goff, gi = maj_in + s.ooff;
+                    if (go >= (uint64_t)vol || gi >= (uint64_t)vol) return TPERM_ERR_INTERNAL;
+                    if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                    out_to_in[go] = (int64_t)gi;
+                }
+            }
+        }
+    for (uint32_t b = 0; b < d.num_tiles; ++b)
+        if (!tile_seen[b]) return TPERM_ERR_INTERNAL;
+    // The map is in canonical coordinates; canonicalisation leaves scalar positions
+    // unchanged, so it is also the map of the problem as given.
+    return TPERM_OK;
+}
+
+}  // namespace tperm

@@ -1,0 +1,91 @@
+// Host-side planner: validate, canonicalise, enumerate candidate tiles, score them and
+// fill the kernel descriptor.  Pure C++ with no HIP calls, so it runs on a GPU-less host.
+#pragma once
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/tperm.h"
+#include "tperm_desc.h"
+
+namespace tperm {
+
+// Largest tile the tile kernels accept: NREG_MAX slots per thread, and an LDS image that
+// fits the 64 KiB a workgroup may take without opting in to more.
+constexpr int kMaxNreg = 32;
+constexpr int64_t kMaxTileVol = (int64_t)kMaxNreg * TPERM_THREADS;  // 8192 elements
+constexpr int64_t kMaxLdsBytes = 64 * 1024;
+
+// The per-thread slot counts the tile kernel is instantiated for.
+extern const int kNregSet[];
+extern const int kNregSetSize;
+
+struct Canonical {
+    int rank = 0;
+    int64_t dims[TPERM_MAX_RANK] = {0};
+    int perm[TPERM_MAX_RANK] = {0};
+    int64_t volume = 0;
+};
+
+// A candidate tile: extents per canonical dim (1 = dim is enumerated by the tile index).
+struct Candidate {
+    int kclass = 0;   // ROWCOPY / TILED / PACKED
+    bool use_lds = true;
+    int m = 0, k = 0;
+    int64_t t[TPERM_MAX_RANK] = {0};
+    int64_t tile_vol = 0, run_in = 0, run_out = 0, num_tiles = 0;
+    double utilisation = 1.0;  // useful fraction of the slots of all tiles (ragged edges)
+    double score = 0.0;        // relative cost estimate, lower is better
+};
+
+struct Plan {
+    int rank = 0;
+    int64_t dims[TPERM_MAX_RANK] = {0};
+    int perm[TPERM_MAX_RANK] = {0};
+    int elem = 0;
+    Canonical c;
+    int kclass = 0;
+    Candidate cand;
+    bool use_lds = false;
+    int nreg = 0;
+    int lds_pad = 0;
+    int lds_bytes = 0;
+    int grid_mode = 0;
+    TileDesc tile;
+    NaiveDesc naive;
+    // launch geometry, resolved on first execute (needs the device); 0 = not yet
+    int max_blocks = 0;
+};
+
+tperm_status_t validate(int rank, const int64_t* dims, const int* perm, size_t elem);
+void canonicalise(int rank, const int64_t* dims, const int* perm, Canonical* out);
+FastDiv make_fastdiv(uint32_t d);
+
+// All candidate tiles for a canonical problem, each scored; sorted best first.
+std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem);
+
+// Build a candidate from explicit (m, tile_in, k, tile_out); false if it cannot run.
+bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
+                    int64_t tile_out, bool use_lds, Candidate* out);
+
+// Fill plan->tile (and nreg, lds size, padding) from a candidate.
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode);
+void build_naive_desc(Plan* plan);
+
+// Plan creation proper.
+tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int* perm,
+                           size_t elem, const tperm_plan_opts_t* opts);
+
+// Plan for one explicit candidate (measurement-based selection tries them one by one).
+tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* dims,
+                                          const int* perm, size_t elem, const Candidate& cand);
+
+// Host evaluation of the plan's index maps (see tperm_plan_index_map).
+tperm_status_t index_map(const Plan& plan, int64_t* out_to_in);
+
+// Estimated LDS cycles of the first accesses of a workgroup for a given descriptor
+// (bank-conflict count evaluated from the slot positions, as Section 2.3 does for the
+// shared-memory term of its model).
+double lds_conflict_cost(const TileDesc& d, int elem, int nreg);
+
+}  // namespace tperm

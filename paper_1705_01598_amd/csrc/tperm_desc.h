@@ -1,0 +1,149 @@
+// Kernel descriptors: plain structs filled by the host planner and passed BY VALUE as
+// kernel arguments (no device allocation, no host-to-device copy at plan time), plus the
+// index arithmetic that both the kernels and the host-side self check evaluate.
+//
+// Notation follows Section 2 of the paper: a tile is the sub-volume M_mk staged through
+// LDS; the remaining dimensions (M-bar_mk, here together with the chunk counters of split
+// dimensions) are enumerated by the tile index b; "major" offsets depend on b only
+// (Eqs. (2),(3)), "minor" offsets on the position k inside the tile (Eqs. (4)-(6)).
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define TPERM_HD __host__ __device__ inline __attribute__((always_inline))
+#else
+#define TPERM_HD inline
+#endif
+
+#define TPERM_DESC_MAX_DIMS 16   // canonical rank limit = lanes of one DPP row
+#define TPERM_THREADS 256        // threads per workgroup of the tile kernels
+#define TPERM_NO_REM 0xFFFFu     // "no split on this side": every real coordinate is below it
+
+namespace tperm {
+
+// Division of a 31-bit unsigned n by a constant d >= 1 as multiply + shift:
+// with l = ceil(log2 d), magic = ceil(2^(31+l) / d) < 2^32 and
+// floor(n / d) = (n * magic) >> (31 + l) for every n < 2^31 (Granlund-Montgomery).
+struct FastDiv {
+    uint32_t magic;
+    uint32_t shift;
+};
+
+TPERM_HD uint32_t fdiv(uint32_t n, FastDiv f) {
+    return (uint32_t)(((uint64_t)n * (uint64_t)f.magic) >> f.shift);
+}
+
+// One dimension of the tile, as seen from one side (input order or output order).
+struct TileDim {
+    uint32_t ext;      // tile extent t_z (>= 2)
+    FastDiv div;       // division by ext
+    uint32_t gstride;  // element stride of this dim in global memory on this side
+    uint32_t ostride;  // element stride of this dim in global memory on the other side
+    uint32_t lstride;  // element stride of this dim in the LDS image of the tile
+    uint32_t sel;      // 0: whole dim is in the tile; 1: split dim A; 2: split dim B
+};
+
+// One term of the major-offset sums (Eqs. (2),(3)): lane j of every 16-lane row holds
+// term j.  coordinate = (b / cum) % ext.
+struct MajorDims {
+    FastDiv cum[TPERM_DESC_MAX_DIMS];   // division by the cumulative volume c_j
+    FastDiv ext_div[TPERM_DESC_MAX_DIMS];
+    uint32_t ext[TPERM_DESC_MAX_DIMS];
+    uint32_t stride_in[TPERM_DESC_MAX_DIMS];   // elements
+    uint32_t stride_out[TPERM_DESC_MAX_DIMS];  // elements
+};
+
+// Descriptor of the generic tile kernel (Tiled, Packed, PackedSplit and the LDS-free
+// row-copy all reduce to it).
+struct TileDesc {
+    uint32_t num_tiles;     // vol(M-bar_mk) times the chunk counts of the split dims
+    uint32_t tile_vol;      // vol(M_mk) with split dims at their tile extent
+    uint32_t n_tile_dims;
+    uint32_t n_major;       // terms in use in `major` (the rest are neutral)
+    uint32_t split_ext[2];  // full extent d of split dim A / B (0 if none)
+    uint32_t split_tile[2]; // tile extent t of split dim A / B
+    uint32_t lds_elems;     // size of the LDS image (with padding), elements
+    uint32_t grid_mode;     // 0: tile b = block + i*grid;  1: contiguous tile range per XCD
+    uint32_t tiles_per_xcd; // grid_mode 1: ceil(num_tiles / 8)
+    uint32_t lane_a;        // lane of `major` holding the chunk counter of split A (if any)
+    uint32_t lane_b;        // same for split B
+    TileDim in_order[TPERM_DESC_MAX_DIMS];   // tile dims, input order (k enumerates these)
+    TileDim out_order[TPERM_DESC_MAX_DIMS];  // the same dims, output order
+    MajorDims major;
+};
+
+// Per-thread, per-slot minor position for the read side (Eq. (4) and the LDS store slot).
+// k is the position inside the tile in input order.  xa/xb are the coordinates along the
+// split dims, used to mask ragged edge tiles.
+struct Slot {
+    uint32_t goff;   // element offset in global memory relative to the tile's major offset
+    uint32_t ooff;   // the same element's offset on the other side (LDS-free kernels)
+    uint32_t loff;   // element index in the LDS image
+    uint32_t xa, xb;
+};
+
+TPERM_HD Slot tile_slot(const TileDim* dims, uint32_t n, uint32_t k) {
+    Slot s;
+    s.goff = 0; s.ooff = 0; s.loff = 0; s.xa = 0; s.xb = 0;
+    uint32_t rem = k;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t q = fdiv(rem, dims[i].div);
+        const uint32_t x = rem - q * dims[i].ext;
+        rem = q;
+        s.goff += x * dims[i].gstride;
+        s.ooff += x * dims[i].ostride;
+        s.loff += x * dims[i].lstride;
+        if (dims[i].sel == 1u) s.xa = x;
+        if (dims[i].sel == 2u) s.xb = x;
+    }
+    return s;
+}
+
+// Term `lane` of the major sums for tile b: coordinate along that major dim.
+TPERM_HD uint32_t major_coord(const MajorDims& m, uint32_t lane, uint32_t b) {
+    const uint32_t q = fdiv(b, m.cum[lane]);
+    return q - fdiv(q, m.ext_div[lane]) * m.ext[lane];
+}
+
+// Remaining extent of a split dim in the chunk with counter `chunk` (ragged last chunk).
+TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t chunk) {
+    if (full_ext == 0u) return TPERM_NO_REM;
+    const uint32_t left = full_ext - chunk * tile_ext;
+    return left < tile_ext ? left : tile_ext;
+}
+
+// Tile visited by workgroup `block` of `grid` on its i-th iteration, or num_tiles if done.
+TPERM_HD uint32_t tile_of(const TileDesc& d, uint32_t block, uint32_t grid, uint32_t i) {
+    if (d.grid_mode == 1u) {
+        // workgroups are dealt round-robin to the 8 XCDs: give each XCD one contiguous
+        // range of tiles so neighbouring tiles share an L2
+        const uint32_t xcd = block & 7u, slot = block >> 3, per = grid >> 3;
+        const uint32_t local = slot + i * per;
+        if (local >= d.tiles_per_xcd) return d.num_tiles;
+        const uint32_t b = xcd * d.tiles_per_xcd + local;
+        return b < d.num_tiles ? b : d.num_tiles;
+    }
+    const uint64_t b = (uint64_t)block + (uint64_t)i * grid;
+    return b < d.num_tiles ? (uint32_t)b : d.num_tiles;
+}
+
+// Descriptor of the naive gather kernel: one thread per output element.
+struct NaiveDesc {
+    uint32_t rank;
+    uint32_t volume;
+    FastDiv out_ext_div[TPERM_DESC_MAX_DIMS];  // division by output extent j
+    uint32_t out_ext[TPERM_DESC_MAX_DIMS];
+    uint32_t in_stride[TPERM_DESC_MAX_DIMS];   // input stride of the dim at output position j
+};
+
+TPERM_HD uint32_t naive_input_offset(const NaiveDesc& d, uint32_t o) {
+    uint32_t rem = o, p = 0;
+    for (uint32_t j = 0; j < d.rank; ++j) {
+        const uint32_t q = fdiv(rem, d.out_ext_div[j]);
+        p += (rem - q * d.out_ext[j]) * d.in_stride[j];
+        rem = q;
+    }
+    return p;
+}
+
+}  // namespace tperm

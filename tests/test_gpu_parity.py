@@ -1,0 +1,221 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Shapes here are small enough for the oracle to finish in well under a second each, yet span
+several tiles and ragged edge tiles in every kernel class.  Transposes move bits, so the
+bar is exact equality of the raw bytes.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1705_01598_amd import binding as B
+from paper_1705_01598_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from gpu_util import np_uint, run_plan, to_device  # noqa: E402
+
+
+def _check(case, plan, kind="bits", offset=0):
+    if kind == "bits":
+        a = wl.bitpattern_values(case)
+    elif kind == "uniform":
+        a = wl.uniform_values(case)
+    else:
+        a = wl.stamp_values(case)
+    a_dev = to_device(a)
+    got, guards = run_plan(plan, a_dev, case.volume, case.elem_size, offset)
+    ref = np_uint(oracle.transpose(np_uint(a), case.dims, case.perm))
+    assert guards, f"{case.name}: wrote outside the output buffer"
+    bad = np.nonzero(got != ref)[0]
+    assert bad.size == 0, (f"{case.name} dims={case.dims} perm={case.perm}: {bad.size} wrong "
+                           f"elements, first at {bad[:5]}; plan={B.info_dict(plan.describe())}")
+
+
+SHAPES = [
+    # (dims, perm)
+    ((257, 131), (1, 0)),                       # rank-2, ragged both ways
+    ((64, 64), (1, 0)),
+    ((9, 7), (1, 0)),                           # the tile-illustration shape of the paper, tiny
+    ((1000, 3), (1, 0)),                        # long input dim, tiny output dim
+    ((3, 1000), (1, 0)),
+    ((70, 45, 33), (2, 1, 0)),
+    ((70, 45, 33), (1, 2, 0)),
+    ((70, 45, 33), (0, 2, 1)),                  # leading dim kept, long enough for row copy
+    ((5, 45, 33, 7), (0, 2, 1, 3)),             # leading dim kept, short: packed
+    ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4)),
+    ((2, 3, 4, 3, 2, 2, 3, 2, 5, 3), (9, 0, 7, 2, 5, 4, 3, 6, 1, 8)),   # rank 10, tiny extents
+    ((4, 3, 2, 2, 3, 2, 2, 3, 2, 2, 3, 2), (11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1, 0)),  # rank-12 reverse
+    ((96, 96, 24), (1, 0, 2)),
+    ((33, 1, 17, 1, 19), (4, 1, 2, 3, 0)),      # extent-1 dims in the middle
+    ((129, 67, 5), (2, 0, 1)),
+    ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4)),         # contraction-style, power-of-two strides
+    ((16, 16, 16, 16), (2, 3, 0, 1)),           # fuses to a 256 x 256 matrix transpose
+]
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("dims,perm", SHAPES)
+def test_auto_plan_matches_oracle(dims, perm, elem):
+    case = wl.make_case(0, 1, dims, perm, elem)
+    plan = B.tperm_plan_create(dims, perm, elem)
+    _check(case, plan)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("kclass", [B.KERNEL_NAIVE, B.KERNEL_TILED, B.KERNEL_PACKED, B.KERNEL_ROWCOPY])
+@pytest.mark.parametrize("dims,perm", SHAPES)
+def test_forced_class_matches_oracle(dims, perm, kclass, elem):
+    case = wl.make_case(0, 2, dims, perm, elem)
+    try:
+        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=kclass)
+    except B.TpermError as e:
+        assert e.status == B.ERR_KERNEL      # class not legal for this problem
+        pytest.skip("class cannot run this shape")
+    assert plan.describe().kernel_class == kclass
+    _check(case, plan)
+    plan.destroy()
+
+
+TILES = [
+    # dims, perm, m, tile_in, k, tile_out  -> ragged chunks on both split dims
+    ((257, 131), (1, 0), 1, 32, 1, 32),
+    ((257, 131), (1, 0), 1, 64, 1, 48),
+    ((257, 131), (1, 0), 1, 100, 1, 7),
+    ((70, 45, 33), (2, 1, 0), 1, 32, 1, 16),
+    ((70, 45, 33), (2, 1, 0), 1, 16, 2, 9),
+    ((20, 7, 33, 5), (2, 1, 3, 0), 2, 3, 2, 4),
+    ((70, 45, 33), (1, 0, 2), 1, 16, 2, 5),
+    ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 3, 3, 3, 5),
+    ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 2, 4, 2, 4),
+    ((5, 45, 33, 7), (0, 2, 1, 3), 2, 11, 2, 8),
+    ((5, 45, 33, 7), (0, 2, 1, 3), 2, 45, 2, 33),
+    ((1000, 3), (1, 0), 1, 333, 2, 0),
+    ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4), 2, 8, 2, 8),
+]
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("grid_mode", [0, 1])
+@pytest.mark.parametrize("dims,perm,m,tin,k,tout", TILES)
+def test_explicit_tiles_match_oracle(dims, perm, m, tin, k, tout, grid_mode, elem):
+    case = wl.make_case(0, 3, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin,
+                                  k=k, tile_out=tout, grid_mode=grid_mode)
+    _check(case, plan)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("pad", [0, 1, 2, 5])
+def test_forced_lds_padding(pad):
+    dims, perm = (100, 90), (1, 0)
+    case = wl.make_case(0, 4, dims, perm, 8)
+    plan = B.tperm_plan_create_ex(dims, perm, 8, kernel_class=B.KERNEL_PACKED, m=1, tile_in=50, k=1,
+                                  tile_out=30, lds_pad=pad)
+    assert plan.describe().lds_pad == pad
+    _check(case, plan)
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+def test_all_rank4_permutations(elem):
+    dims = (12, 7, 10, 9)
+    for perm in itertools.permutations(range(4)):
+        case = wl.make_case(0, 5, dims, perm, elem)
+        plan = B.tperm_plan_create(dims, perm, elem)
+        _check(case, plan, kind="stamp")
+        plan.destroy()
+
+
+@pytest.mark.parametrize("dims,perm", [((7,), (0,)), ((1,), (0,)), ((1, 1, 1), (2, 0, 1)),
+                                       ((5, 1, 3), (0, 1, 2)), ((1000003,), (0,)),
+                                       ((4, 6, 5), (0, 1, 2)), ((1, 9, 1), (1, 2, 0))])
+@pytest.mark.parametrize("elem", [8, 4])
+def test_degenerate_shapes_are_copies(dims, perm, elem):
+    case = wl.make_case(0, 6, dims, perm, elem)
+    plan = B.tperm_plan_create(dims, perm, elem)
+    assert plan.describe().kernel_class == B.KERNEL_COPY
+    _check(case, plan)
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("offset", [1, 3])
+def test_unaligned_base_pointers(elem, offset):
+    """Pointers aligned to the element size only (not to 16 bytes) must still work."""
+    for dims, perm in [((257, 131), (1, 0)), ((70, 45, 33), (0, 2, 1)), ((1000,), (0,))]:
+        case = wl.make_case(0, 7, dims, perm, elem)
+        a = wl.bitpattern_values(case)
+        a_pad = np.concatenate([np.zeros(offset, dtype=a.dtype), a])
+        a_dev = to_device(a_pad)[offset:]
+        plan = B.tperm_plan_create(dims, perm, elem)
+        got, guards = run_plan(plan, a_dev, case.volume, elem, offset)
+        ref = np_uint(oracle.transpose(a, dims, perm))
+        assert guards and np.array_equal(got, ref), (dims, perm, elem, offset)
+
+
+def test_uniform_values_and_repeat_execution():
+    """Same plan executed several times on different inputs (catches a missing barrier)."""
+    dims, perm = (150, 40, 30), (2, 0, 1)
+    plan = B.tperm_plan_create(dims, perm, 8)
+    for i in range(4):
+        case = wl.make_case(0, 100 + i, dims, perm, 8)
+        _check(case, plan, kind="uniform")
+
+
+def test_execute_argument_errors():
+    dims, perm = (64, 32), (1, 0)
+    plan = B.tperm_plan_create(dims, perm, 8)
+    a = torch.zeros(64 * 32 + 8, dtype=torch.int64, device="cuda")
+    b = torch.zeros(64 * 32 + 8, dtype=torch.int64, device="cuda")
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, a.data_ptr(), a.data_ptr())
+    assert e.value.status == B.ERR_ALIAS
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, a.data_ptr(), a.data_ptr() + 64)       # overlapping ranges
+    assert e.value.status == B.ERR_ALIAS
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, a.data_ptr() + 4, b.data_ptr())        # not 8-byte aligned
+    assert e.value.status == B.ERR_ALIGN
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, 0, b.data_ptr())
+    assert e.value.status == B.ERR_NULL
+    B.tperm_execute(plan, a.data_ptr(), b.data_ptr())
+    torch.cuda.synchronize()
+
+
+def test_non_default_stream():
+    dims, perm = (257, 131), (1, 0)
+    case = wl.make_case(0, 9, dims, perm, 8)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    plan = B.tperm_plan_create(dims, perm, 8)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        got, guards = run_plan(plan, a_dev, case.volume, 8)
+    assert guards and np.array_equal(got, np_uint(oracle.transpose(a, dims, perm)))
+
+
+def test_measured_plan_matches_oracle():
+    dims, perm = (70, 45, 33), (2, 1, 0)
+    case = wl.make_case(0, 10, dims, perm, 8)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    scratch = torch.empty(case.volume, dtype=torch.int64, device="cuda")
+    plan = B.tperm_plan_create_measured(dims, perm, 8, a_dev.data_ptr(), scratch.data_ptr(),
+                                        torch.cuda.current_stream().cuda_stream, 12)
+    got, guards = run_plan(plan, a_dev, case.volume, 8)
+    assert guards and np.array_equal(got, np_uint(oracle.transpose(a, dims, perm)))
+
+
+def test_copy_bytes():
+    n = 1 << 20
+    a = torch.arange(n + 3, dtype=torch.int32, device="cuda")
+    b = torch.zeros(n + 3, dtype=torch.int32, device="cuda")
+    B.tperm_copy_bytes(a.data_ptr(), b.data_ptr(), (n + 3) * 4, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

@@ -1,0 +1,242 @@
+"""Host-only tests of the library: C-ABI exports, argument validation, canonical form, the
+multiply-shift division, and -- for every plan the GPU tests execute and many more -- the
+plan's index maps, evaluated on the CPU with the very arithmetic the kernel runs, against
+the oracle's map.  No GPU is needed: plan creation never touches the device."""
+import ctypes
+import itertools
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1705_01598_amd import binding as B
+from paper_1705_01598_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tperm.h")).read()
+    declared = set(re.findall(r"\b(tperm_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    for s in range(13):
+        assert B.status_string(s) and B.status_string(s) != "unknown status"
+    assert B.status_string(99) == "unknown status"
+
+
+@pytest.mark.parametrize("dims,perm,elem,status", [
+    ((2, 3), (0, 0), 8, B.ERR_PERM),
+    ((2, 3), (0, 2), 8, B.ERR_PERM),
+    ((2, 3), (-1, 0), 8, B.ERR_PERM),
+    ((2, 0), (0, 1), 8, B.ERR_DIMS),
+    ((2, -5), (0, 1), 8, B.ERR_DIMS),
+    ((2, 3), (0, 1), 2, B.ERR_ELEM_SIZE),
+    ((2, 3), (0, 1), 16, B.ERR_ELEM_SIZE),
+    ((1 << 16, 1 << 16), (1, 0), 4, B.ERR_TOO_LARGE),
+    ((1 << 15, 1 << 15), (1, 0), 8, B.ERR_TOO_LARGE),     # 8 GiB: byte offsets exceed 32 bits
+    ((2,) * 17, tuple(range(17)), 8, B.ERR_RANK),
+    ((), (), 8, B.ERR_RANK),
+])
+def test_plan_create_rejects_bad_arguments(dims, perm, elem, status):
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create(dims, perm, elem)
+    assert e.value.status == status
+
+
+def test_null_arguments():
+    L = B.lib()
+    h = ctypes.c_void_p()
+    d = (ctypes.c_int64 * 2)(2, 3)
+    p = (ctypes.c_int * 2)(1, 0)
+    assert L.tperm_plan_create(None, 2, d, p, 8) == B.ERR_NULL
+    assert L.tperm_plan_create(ctypes.byref(h), 2, None, p, 8) == B.ERR_NULL
+    assert L.tperm_plan_create(ctypes.byref(h), 2, d, None, 8) == B.ERR_NULL
+    assert L.tperm_plan_destroy(None) == B.ERR_NULL
+    assert L.tperm_plan_describe(None, None) == B.ERR_NULL
+    assert L.tperm_execute(None, None, None, None) == B.ERR_NULL
+
+
+def test_execute_without_device_reports_hip_error():
+    """On a host with no GPU, execute must fail with a status, not crash or fall back."""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    plan = B.tperm_plan_create((64, 64), (1, 0), 8)
+    a = np.zeros(64 * 64, dtype=np.int64)
+    b = np.zeros(64 * 64, dtype=np.int64)
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, a.ctypes.data, b.ctypes.data)
+    assert e.value.status == B.ERR_HIP
+    assert not b.any()
+
+
+@pytest.mark.parametrize("dims,perm,cdims,cperm", [
+    ((2, 3, 4), (0, 1, 2), (24,), (0,)),
+    ((2, 3, 4), (1, 2, 0), (2, 12), (1, 0)),
+    ((2, 3, 4, 5), (2, 3, 0, 1), (6, 20), (1, 0)),
+    ((2, 1, 3, 4, 1, 5), (3, 4, 5, 1, 0, 2), (6, 20), (1, 0)),
+    ((1, 1, 1), (2, 0, 1), (1,), (0,)),
+    ((96, 96, 96, 96), (0, 1, 3, 2), (9216, 96, 96), (0, 2, 1)),
+    ((96, 96, 96, 96), (3, 0, 1, 2), (884736, 96), (1, 0)),
+    ((96, 96, 96, 96), (2, 3, 0, 1), (9216, 9216), (1, 0)),
+    ((96, 96, 96, 96), (3, 2, 1, 0), (96, 96, 96, 96), (3, 2, 1, 0)),
+    ((5, 1, 7), (2, 1, 0), (5, 7), (1, 0)),
+])
+def test_canonical_form(dims, perm, cdims, cperm):
+    info = B.tperm_plan_create(dims, perm, 8).describe()
+    r = info.canon_rank
+    assert tuple(info.canon_dims[:r]) == cdims
+    assert tuple(info.canon_perm[:r]) == cperm
+    assert info.volume == math.prod(dims)
+
+
+def test_canonical_form_preserves_the_oracle_result():
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        r = int(rng.integers(2, 8))
+        dims = tuple(int(x) for x in rng.integers(1, 6, size=r))
+        perm = tuple(int(x) for x in rng.permutation(r))
+        info = B.tperm_plan_create(dims, perm, 4).describe()
+        cr = info.canon_rank
+        a = np.arange(math.prod(dims), dtype=np.int32)
+        assert np.array_equal(oracle.transpose(a, dims, perm),
+                              oracle.transpose(a, tuple(info.canon_dims[:cr]), tuple(info.canon_perm[:cr])))
+
+
+def test_class_selection_basics():
+    k = lambda d, p, e=8: B.tperm_plan_create(d, p, e).describe().kernel_class
+    assert k((1000,), (0,)) == B.KERNEL_COPY
+    assert k((10, 20, 30), (0, 1, 2)) == B.KERNEL_COPY
+    assert k((2048, 2048), (1, 0)) == B.KERNEL_TILED
+    assert k((4, 4, 4, 4, 4, 4, 4, 4, 4), (8, 7, 6, 5, 4, 3, 2, 1, 0)) == B.KERNEL_PACKED
+    assert k((4096, 64, 64), (0, 2, 1)) == B.KERNEL_ROWCOPY
+    assert k((2, 64, 64, 64), (0, 2, 1, 3)) == B.KERNEL_PACKED
+
+
+def test_forced_class_that_cannot_run_is_an_error():
+    for kc in (B.KERNEL_TILED, B.KERNEL_COPY):
+        with pytest.raises(B.TpermError) as e:
+            B.tperm_plan_create_ex((8, 9, 10), (0, 2, 1), 8, kernel_class=kc)
+        assert e.value.status == B.ERR_KERNEL
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_ex((8, 9, 10), (2, 1, 0), 8, kernel_class=B.KERNEL_ROWCOPY)
+    assert e.value.status == B.ERR_KERNEL
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_ex((8, 9, 10), (0, 1, 2), 8, kernel_class=B.KERNEL_PACKED)
+    assert e.value.status == B.ERR_KERNEL
+
+
+# -- index maps ---------------------------------------------------------------------------
+
+def _map_ok(dims, perm, elem, **kw):
+    plan = B.tperm_plan_create_ex(dims, perm, elem, **kw)
+    m = B.tperm_plan_index_map(plan)           # raises on overlap / out-of-range / LDS misuse
+    vol = math.prod(dims)
+    ref = oracle.transpose(np.arange(vol, dtype=np.int64), dims, perm)
+    assert np.array_equal(m, ref), (dims, perm, elem, kw, B.info_dict(plan.describe()))
+    return plan
+
+
+def test_fig2_tile_shape():
+    """The paper's tile illustration: a 9 x 7 slab cut by width-4 tiles gives 3 x 2 = 6
+    tiles, two of them whole, the others ragged (Section 2.1, Figure 2)."""
+    plan = _map_ok((9, 7), (1, 0), 8, kernel_class=B.KERNEL_PACKED, m=1, tile_in=4, k=1, tile_out=4)
+    info = plan.describe()
+    assert info.num_tiles == 6 and info.tile_volume == 16
+    assert list(info.tile_extent[:2]) == [4, 4]
+
+
+def test_index_maps_of_every_gpu_test_plan():
+    import test_gpu_parity as G
+    for elem in (8, 4):
+        for dims, perm in G.SHAPES:
+            _map_ok(dims, perm, elem)
+            for kc in (B.KERNEL_NAIVE, B.KERNEL_TILED, B.KERNEL_PACKED, B.KERNEL_ROWCOPY):
+                try:
+                    _map_ok(dims, perm, elem, kernel_class=kc)
+                except B.TpermError as e:
+                    assert e.status == B.ERR_KERNEL
+        for dims, perm, m, tin, k, tout in G.TILES:
+            for gm in (0, 1):
+                _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
+                        tile_out=tout, grid_mode=gm)
+
+
+def test_index_maps_all_perms_small_grid():
+    n = 0
+    for dims in [(5, 4, 3), (2, 7, 3, 2), (3, 3, 3, 3), (2, 2, 3, 2, 2), (6, 1, 5, 2), (37, 11),
+                 (2, 3, 2, 3, 2, 3)]:
+        for perm in itertools.permutations(range(len(dims))):
+            _map_ok(dims, perm, 8)
+            n += 1
+    assert n > 900
+
+
+def test_index_maps_random_shapes_and_tiles():
+    rng = np.random.default_rng(11)
+    done = 0
+    while done < 150:
+        r = int(rng.integers(2, 9))
+        dims = tuple(int(x) for x in rng.integers(1, 40, size=r))
+        if math.prod(dims) > 150_000 or math.prod(dims) < 2:
+            continue
+        perm = tuple(int(x) for x in rng.permutation(r))
+        elem = int(rng.choice([4, 8]))
+        _map_ok(dims, perm, elem)
+        info = B.tperm_plan_create(dims, perm, elem).describe()
+        cr = info.canon_rank
+        if cr >= 2:
+            m = int(rng.integers(1, cr + 1))
+            k = int(rng.integers(1, cr + 1))
+            tin = int(rng.integers(1, info.canon_dims[m - 1] + 1))
+            tout = int(rng.integers(1, info.canon_dims[info.canon_perm[k - 1]] + 1))
+            try:
+                _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
+                        tile_out=tout, grid_mode=int(rng.integers(0, 2)))
+            except B.TpermError as e:
+                assert e.status == B.ERR_KERNEL     # tile too large for LDS / registers
+        done += 1
+
+
+def test_index_maps_scaled_workload_shapes():
+    """The benchmark families, shrunk so the maps can be enumerated on the host."""
+    for case in wl.config5()[::5]:
+        dims = tuple(4 if d == 8 else 6 for d in case.dims)
+        _map_ok(dims, case.perm, 4)
+    for case in wl.config4()[::11]:
+        scale = (300_000 / case.volume) ** (1.0 / case.rank)
+        dims = tuple(max(2, int(d * scale)) for d in case.dims)
+        _map_ok(dims, case.perm, 8)
+    for p in itertools.permutations(range(4)):
+        _map_ok((24, 20, 18, 22), p, 8)
+
+
+def test_fastdiv_through_naive_descriptor():
+    """The multiply-shift division is exercised on extents up to 2^31 through the naive
+    kernel's map (which divides by every output extent)."""
+    for dims in [(46341, 3), (3, 46337), (65536, 2), (7, 11, 13, 17), (2, 99991)]:
+        perm = tuple(reversed(range(len(dims))))
+        _map_ok(dims, perm, 4, kernel_class=B.KERNEL_NAIVE)
+
+
+def test_selected_tiles_are_sane_for_the_benchmark_shapes():
+    """Every benchmark case gets a plan; staged plans have runs of at least 128 bytes on
+    both sides unless the tensor itself forbids it, and fit the LDS budget."""
+    cases = wl.config1() + wl.config2() + wl.config3() + wl.config4()[::7] + wl.config5()[::4]
+    for case in cases:
+        info = B.tperm_plan_create(case.dims, case.perm, case.elem_size).describe()
+        assert info.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
+        assert info.lds_bytes <= 64 * 1024
+        assert info.tile_volume <= info.nreg * info.threads
+        assert info.run_out * case.elem_size >= 128, B.info_dict(info)
+        if info.kernel_class != B.KERNEL_ROWCOPY:
+            assert info.run_in * case.elem_size >= 128, B.info_dict(info)
