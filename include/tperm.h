@@ -72,8 +72,14 @@ typedef struct {
     int k;              /* number of leading OUTPUT dims (canonical) taken into the tile     */
     int64_t tile_out;   /* tile extent of the last of those k dims (0 = full extent)         */
     int lds_pad;        /* -1 = search; >= 0 forces the LDS row padding (elements)           */
-    int grid_mode;      /* 0 = default tile order; 1 = one contiguous tile range per XCD     */
-    int reserved[8];
+    int grid_mode;      /* 0 = tiles in launch order; 1 = one contiguous tile range per XCD;  */
+                        /* 2 + g = groups of 2^g consecutive tiles dealt to the XCDs in turn  */
+    int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
+    int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal global access */
+    int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
+    int window_out;     /* on the input / output side; 0 = default, 1 = plain input order     */
+    int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
+    int reserved[3];
 } tperm_plan_opts_t;
 
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
@@ -97,7 +103,9 @@ typedef struct {
     int lds_bytes;
     int lds_pad;
     double score;                          /* selector's estimate (relative, lower = better)*/
-    int reserved[8];
+    int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
+    int cache_policy;                      /* 1 = cached, 2 = nontemporal                   */
+    int reserved[6];
 } tperm_plan_info_t;
 
 /* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is

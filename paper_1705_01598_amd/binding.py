@@ -31,7 +31,10 @@ EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measu
 class PlanOpts(ctypes.Structure):
     _fields_ = [("kernel_class", ctypes.c_int), ("m", ctypes.c_int), ("tile_in", ctypes.c_int64),
                 ("k", ctypes.c_int), ("tile_out", ctypes.c_int64), ("lds_pad", ctypes.c_int),
-                ("grid_mode", ctypes.c_int), ("reserved", ctypes.c_int * 8)]
+                ("grid_mode", ctypes.c_int), ("blocks_per_cu", ctypes.c_int),
+                ("cache_policy", ctypes.c_int), ("window_in", ctypes.c_int),
+                ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
+                ("reserved", ctypes.c_int * 3)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -43,7 +46,8 @@ class PlanInfo(ctypes.Structure):
                 ("num_tiles", ctypes.c_int64), ("m", ctypes.c_int), ("k", ctypes.c_int),
                 ("nreg", ctypes.c_int), ("threads", ctypes.c_int), ("lds_bytes", ctypes.c_int),
                 ("lds_pad", ctypes.c_int), ("score", ctypes.c_double),
-                ("reserved", ctypes.c_int * 8)]
+                ("blocks_per_cu", ctypes.c_int), ("cache_policy", ctypes.c_int),
+                ("reserved", ctypes.c_int * 6)]
 
 
 class TpermError(RuntimeError):
@@ -135,10 +139,14 @@ def tperm_plan_create(dims: Sequence[int], perm: Sequence[int], elem_size: int) 
 
 def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: int,
                          kernel_class: int = KERNEL_AUTO, m: int = 0, tile_in: int = 0, k: int = 0,
-                         tile_out: int = 0, lds_pad: int = -1, grid_mode: int = 0) -> Plan:
+                         tile_out: int = 0, lds_pad: int = -1, grid_mode: int = 0,
+                         blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
+                         window_out: int = 0, threads: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
-                    tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode))
+                    tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
+                    blocks_per_cu=int(blocks_per_cu), cache_policy=int(cache_policy),
+                    window_in=int(window_in), window_out=int(window_out), threads=int(threads))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:
@@ -201,5 +209,6 @@ def info_dict(info: PlanInfo) -> dict:
     return {"kernel": KERNEL_NAMES.get(info.kernel_class, "?"), "canon_dims": list(info.canon_dims[:r]),
             "canon_perm": list(info.canon_perm[:r]), "tile": list(info.tile_extent[:r]),
             "tile_volume": info.tile_volume, "run_in": info.run_in, "run_out": info.run_out,
-            "num_tiles": info.num_tiles, "nreg": info.nreg, "lds_bytes": info.lds_bytes,
-            "lds_pad": info.lds_pad, "score": round(info.score, 4)}
+            "num_tiles": info.num_tiles, "nreg": info.nreg, "threads": info.threads, "lds_bytes": info.lds_bytes,
+            "lds_pad": info.lds_pad, "score": round(info.score, 4),
+            "blocks_per_cu": info.blocks_per_cu, "cache_policy": info.cache_policy}

@@ -42,13 +42,14 @@ tperm_status_t resolve_grid(tperm_plan_s* h, int* grid) {
             (void)hipGetLastError();
             return TPERM_ERR_HIP;
         }
+        if (h->p->blocks_per_cu > 0 && per_cu > h->p->blocks_per_cu) per_cu = h->p->blocks_per_cu;
         mb = per_cu * num_cu;
         h->num_cu.store(num_cu, std::memory_order_release);
         h->max_blocks.store(mb, std::memory_order_release);
     }
     int64_t g = h->p->tile.num_tiles;
     if (g > mb) g = mb;
-    if (h->p->tile.grid_mode == 1u) {
+    if (h->p->tile.grid_mode != 0u) {
         g = (g + 7) / 8 * 8;  // whole rounds over the 8 XCDs
     }
     *grid = (int)g;
@@ -161,10 +162,12 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
         info->m = p.cand.m;
         info->k = p.cand.k;
         info->nreg = p.nreg;
-        info->threads = TPERM_THREADS;
+        info->threads = p.threads;
         info->lds_bytes = p.lds_bytes;
         info->lds_pad = p.lds_pad;
         info->score = p.cand.score;
+        info->blocks_per_cu = p.blocks_per_cu;
+        info->cache_policy = p.cache_policy;
     } else {
         info->threads = 256;
     }

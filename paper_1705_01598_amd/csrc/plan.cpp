@@ -9,8 +9,19 @@
 
 namespace tperm {
 
-const int kNregSet[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
-const int kNregSetSize = (int)(sizeof(kNregSet) / sizeof(kNregSet[0]));
+// keep in step with the instantiation lists in kernels.hip
+static const int kNregSet256[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+static const int kNregSet64[] = {4, 8, 12, 16, 24, 32};
+
+int pick_nreg(int64_t tile_vol, int threads) {
+    const int64_t need = (tile_vol + threads - 1) / threads;
+    const int* set = threads == 64 ? kNregSet64 : kNregSet256;
+    const int n = threads == 64 ? (int)(sizeof(kNregSet64) / sizeof(int))
+                                : (int)(sizeof(kNregSet256) / sizeof(int));
+    for (int i = 0; i < n; ++i)
+        if (set[i] >= need) return set[i];
+    return -1;
+}
 
 // ---------------------------------------------------------------------------------------
 // validation and canonical form
@@ -125,11 +136,6 @@ static int64_t gcd64(int64_t a, int64_t b) {
     return a;
 }
 
-// Expected number of 128-byte lines touched per useful 128 bytes by runs of run_bytes that
-// start on multiples of `granule` bytes (granule a divisor of 128, or 128 itself).
-static double line_overhead(double run_bytes, double granule) {
-    return (run_bytes + 128.0 - granule) / run_bytes;
-}
 
 // Fill the derived fields of a candidate from its tile extents; false if unusable.
 static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
@@ -214,21 +220,27 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
         gin = (double)gcd64(128, (r > 1 ? sI[1] : 1) * elem);
         if (cd->t[0] < c.dims[0]) gin = (double)gcd64((int64_t)gin, cd->t[0] * elem);
     }
-    // Cost per useful byte: lines touched on the read side plus lines touched on the write
-    // side, where a partially written line costs about twice a full one (cf. Eq. (13)).
-    const double cost_in = line_overhead(rin, gin);
-    const double over_out = line_overhead(rout, gout);
-    const double cost_out = 1.0 + 2.0 * (over_out - 1.0);
+    // Cost per useful byte on each side: 128-byte lines touched per line's worth of useful
+    // data, plus a fixed per-run overhead worth about 64 bytes (short runs leave lanes of a
+    // 64-wide memory instruction straddling several rows).  A partially written line costs
+    // about twice a full one (cf. Eq. (13)).
+    const double cost_in = (rin + 64.0 + (128.0 - gin)) / rin;
+    const double cost_out = (rout + 64.0 + 2.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
-    // Short runs also waste lanes of the 64-wide wavefront's memory instruction.
+    // Measured on MI355X: throughput peaks when a compute unit keeps about 16-24 KiB of
+    // reads in flight, which two to three workgroups with 8-12 KiB tiles provide; smaller
+    // tiles pay more per-tile overhead, larger ones overshoot.
     const double bytes = (double)vol * elem;
-    // Small tiles keep too few bytes in flight per workgroup; very large ones cut occupancy.
-    if (bytes < 8192.0) cost *= 1.0 + 0.15 * std::log2(8192.0 / bytes);
-    if (bytes > 32768.0) cost *= 1.0 + 0.10 * std::log2(bytes / 32768.0);
+    if (bytes < 6144.0) cost *= 1.0 + 0.08 * std::log2(6144.0 / bytes);
+    if (bytes > 8192.0) cost *= 1.0 + 0.10 * std::log2(bytes / 8192.0);
     // Too few tiles cannot fill 256 compute units.
     if (tiles < 1024) cost *= 1.0 + 0.5 * std::log2(1024.0 / (double)tiles) / 10.0;
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.03;
+    // Nontemporal accesses pay off when every run starts and ends on a line boundary; with
+    // ragged runs neighbouring tiles share lines and want them kept in L2.
+    cd->aligned = (gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
+                   std::fmod(rout, 128.0) == 0.0);
     cd->score = cost;
     return true;
 }
@@ -341,23 +353,17 @@ std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem) {
 // descriptor construction
 // ---------------------------------------------------------------------------------------
 
-static int pick_nreg(int64_t tile_vol) {
-    const int64_t need = ceil_div(tile_vol, TPERM_THREADS);
-    for (int i = 0; i < kNregSetSize; ++i)
-        if (kNregSet[i] >= need) return kNregSet[i];
-    return -1;
-}
 
 // LDS cost of the first slots of each wavefront: for every wavefront-wide access, the
 // largest number of distinct addresses that fall into one bank (64 banks of 4 bytes; an
 // 8-byte access is served per half wavefront and occupies two banks).
-double lds_conflict_cost(const TileDesc& d, int elem, int nreg) {
+double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads) {
     const int kBanks = 64;
     double total = 0.0;
     const int slots = std::min(nreg, 4);
     for (int side = 0; side < 2; ++side) {
         const TileDim* dims = side == 0 ? d.in_order : d.out_order;
-        for (int w = 0; w < TPERM_THREADS / 64; ++w)
+        for (int w = 0; w < threads / 64; ++w)
             for (int j = 0; j < slots; ++j) {
                 const int groups = elem == 8 ? 2 : 1;
                 const int lanes = 64 / groups;
@@ -365,7 +371,7 @@ double lds_conflict_cost(const TileDesc& d, int elem, int nreg) {
                     uint32_t addr[64];
                     int n = 0;
                     for (int l = 0; l < lanes; ++l) {
-                        const uint32_t k = (uint32_t)(w * 64 + gidx * lanes + l + j * TPERM_THREADS);
+                        const uint32_t k = (uint32_t)(w * 64 + gidx * lanes + l + j * threads);
                         if (k >= d.tile_vol) continue;
                         addr[n++] = tile_slot(dims, d.n_tile_dims, k).loff;
                     }
@@ -407,7 +413,9 @@ static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* di
     return cum;
 }
 
-tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode) {
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
+                               int window_in, int window_out, int threads) {
+    if (threads != 64 && threads != 256) return TPERM_ERR_KERNEL;
     const Canonical& c = plan->c;
     const int r = c.rank;
     const int elem = plan->elem;
@@ -459,13 +467,16 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
     }
     d.n_tile_dims = n;
     d.tile_vol = (uint32_t)cand.tile_vol;
-    d.num_tiles = (uint32_t)cand.num_tiles;
     for (int s = 0; s < 2; ++s) {
         d.split_ext[s] = split_dim[s] >= 0 ? (uint32_t)c.dims[split_dim[s]] : 0u;
         d.split_tile[s] = split_dim[s] >= 0 ? (uint32_t)cand.t[split_dim[s]] : 0u;
     }
-    // major terms: chunk counters of the split dims first (so that consecutive tiles are
-    // neighbours along the input run), then the outer dims in input order
+    // Major terms.  The order of the lanes is the order in which the tile index b walks the
+    // tiles, and with it which tiles run at the same time.  A "window" of up to window_in
+    // tiles that are neighbours on the input side (smallest input strides) comes first,
+    // then a window of up to window_out tiles that are neighbours on the output side, then
+    // everything else in input order: the few hundred tiles in flight at any moment then
+    // cover a compact region of both tensors instead of a thin slab of one.
     for (int l = 0; l < TPERM_DESC_MAX_DIMS; ++l) {
         d.major.cum[l] = make_fastdiv(1);
         d.major.ext_div[l] = make_fastdiv(1);
@@ -473,6 +484,54 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         d.major.stride_in[l] = 0;
         d.major.stride_out[l] = 0;
     }
+    struct MDim {
+        int z;             // canonical dim
+        uint32_t count;    // chunks (split dim) or extent (outer dim)
+        uint64_t sin, sout;
+        int split;         // 0 / 1: chunk counter of split A / B; -1: outer dim
+        uint32_t lo = 0;   // > 0: counter split into lo (window) and hi parts
+        int window = -1;   // 0: in the input window, 1: in the output window, -1: neither
+    };
+    std::vector<MDim> md;
+    for (int z = 0; z < r; ++z) {
+        if (cand.t[z] >= c.dims[z]) continue;
+        MDim m;
+        m.z = z;
+        m.count = (uint32_t)ceil_div(c.dims[z], cand.t[z]);
+        m.sin = (uint64_t)cand.t[z] * sI[z];
+        m.sout = (uint64_t)cand.t[z] * sO[inv[z]];
+        m.split = z == split_dim[0] ? 0 : (z == split_dim[1] ? 1 : -1);
+        md.push_back(m);
+    }
+    if (md.size() > TPERM_DESC_MAX_DIMS) return TPERM_ERR_KERNEL;
+    int n_pairs = 0;
+    auto take_window = [&](int side, uint32_t budget) {
+        // walk the major dims by increasing stride on this side
+        std::vector<int> order(md.size());
+        for (size_t i = 0; i < md.size(); ++i) order[i] = (int)i;
+        std::sort(order.begin(), order.end(), [&](int a, int b) {
+            return side == 0 ? md[a].sin < md[b].sin : md[a].sout < md[b].sout;
+        });
+        for (int i : order) {
+            if (budget < 2) break;
+            MDim& m = md[i];
+            if (m.window >= 0) continue;  // already taken by the other window
+            if (m.count <= budget) {
+                m.window = side;
+                budget /= m.count;
+            } else {
+                if (n_pairs >= 2 || md.size() + (size_t)n_pairs + 1 > TPERM_DESC_MAX_DIMS) break;
+                const uint32_t hi = (uint32_t)ceil_div(m.count, budget);
+                m.lo = (uint32_t)ceil_div(m.count, hi);  // balanced: few non-existent tiles
+                m.window = side;
+                ++n_pairs;
+                break;
+            }
+        }
+    };
+    if (window_in > 1) take_window(0, (uint32_t)window_in);
+    if (window_out > 1) take_window(1, (uint32_t)window_out);
+
     uint32_t lane = 0;
     uint64_t cum = 1;
     auto add_major = [&](uint32_t ext, uint64_t sin, uint64_t sout) {
@@ -482,25 +541,48 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         d.major.stride_in[lane] = (uint32_t)sin;
         d.major.stride_out[lane] = (uint32_t)sout;
         cum *= ext;
-        ++lane;
+        return lane++;
     };
     d.lane_a = d.lane_b = 0;
-    for (int s = 0; s < 2; ++s)
-        if (split_dim[s] >= 0) {
-            const int z = split_dim[s];
-            (s == 0 ? d.lane_a : d.lane_b) = lane;
-            add_major((uint32_t)ceil_div(c.dims[z], cand.t[z]), (uint64_t)cand.t[z] * sI[z],
-                      (uint64_t)cand.t[z] * sO[inv[z]]);
-        }
-    for (int z = 0; z < r; ++z)
-        if (cand.t[z] == 1 && c.dims[z] > 1) {
-            if (lane >= TPERM_DESC_MAX_DIMS) return TPERM_ERR_KERNEL;
-            add_major((uint32_t)c.dims[z], (uint64_t)sI[z], (uint64_t)sO[inv[z]]);
+    d.chunk_pair[0] = d.chunk_pair[1] = 2;
+    for (int p = 0; p < 2; ++p) d.pair[p] = SplitPair{0, 0, 0, 0};
+    int pair_of[TPERM_DESC_MAX_DIMS];
+    int next_pair = 0;
+    // pass 0: input window, pass 1: output window (low parts), pass 2: the rest
+    for (int pass = 0; pass < 3; ++pass)
+        for (size_t i = 0; i < md.size(); ++i) {
+            MDim& m = md[i];
+            if (pass < 2) {
+                if (m.window != pass) continue;
+                if (m.lo > 0) {
+                    pair_of[i] = next_pair++;
+                    SplitPair& sp = d.pair[pair_of[i]];
+                    sp.width = m.lo;
+                    sp.count = m.count;
+                    sp.lane_lo = add_major(m.lo, m.sin, m.sout);
+                    if (m.split >= 0) d.chunk_pair[m.split] = (uint32_t)pair_of[i];
+                } else {
+                    const uint32_t l = add_major(m.count, m.sin, m.sout);
+                    if (m.split == 0) d.lane_a = l;
+                    if (m.split == 1) d.lane_b = l;
+                }
+            } else {
+                if (m.window >= 0 && m.lo == 0) continue;  // placed whole in a window
+                if (m.lo > 0) {
+                    d.pair[pair_of[i]].lane_hi = add_major((uint32_t)ceil_div(m.count, m.lo),
+                                                           m.sin * m.lo, m.sout * m.lo);
+                } else {
+                    const uint32_t l = add_major(m.count, m.sin, m.sout);
+                    if (m.split == 0) d.lane_a = l;
+                    if (m.split == 1) d.lane_b = l;
+                }
+            }
         }
     d.n_major = lane;
-    if (cum != (uint64_t)cand.num_tiles) return TPERM_ERR_INTERNAL;
+    if (cum >= ((uint64_t)1 << 31)) return TPERM_ERR_KERNEL;
+    d.num_tiles = (uint32_t)cum;  // includes the non-existent combinations of split counters
 
-    const int nreg = pick_nreg(cand.tile_vol);
+    const int nreg = pick_nreg(cand.tile_vol, threads);
     if (nreg < 0) return TPERM_ERR_KERNEL;
 
     // LDS image: tile in input order, rows of the contiguous input run separated by a
@@ -529,7 +611,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
             for (int p = 0; p <= max_pad; ++p) {
                 const uint32_t le = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)p);
                 if ((int64_t)le * elem > kMaxLdsBytes) break;
-                const double cost = lds_conflict_cost(d, elem, nreg);
+                const double cost = lds_conflict_cost(d, elem, nreg, threads);
                 if (cost < best - 1e-9) {
                     best = cost;
                     best_pad = p;
@@ -542,14 +624,25 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         if (lds_elems > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
     }
     d.lds_elems = lds_elems;
-    d.grid_mode = (uint32_t)grid_mode;
-    d.tiles_per_xcd = (uint32_t)ceil_div(cand.num_tiles, 8);
+    // grid_mode values >= 2 carry the group size: mode 2 + log2(group) (2 -> groups of 1)
+    d.grid_mode = grid_mode >= 2 ? 2u : (uint32_t)grid_mode;
+    d.group_log2 = grid_mode >= 2 ? (uint32_t)(grid_mode - 2) : 0u;
+    if (d.group_log2 > 20u) return TPERM_ERR_KERNEL;
+    d.tiles_per_xcd = (uint32_t)ceil_div((int64_t)d.num_tiles, 8);
 
     plan->tile = d;
     plan->cand = cand;
     plan->kclass = cand.kclass;
     plan->use_lds = cand.use_lds;
     plan->nreg = nreg;
+    plan->threads = threads;
+    {
+        // resident workgroups per compute unit: aim at ~20 KiB of tile data per CU
+        const double tile_bytes = (double)cand.tile_vol * elem;
+        int bpc = (int)std::lround(20480.0 / tile_bytes);
+        plan->blocks_per_cu = std::max(2, std::min(8, bpc));
+        plan->cache_policy = cand.aligned ? 2 : 1;
+    }
     plan->lds_pad = pad;
     plan->lds_bytes = (int)((int64_t)lds_elems * elem);
     plan->grid_mode = grid_mode;
@@ -644,8 +737,13 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
         }
     }
     if (!have) return fail(TPERM_ERR_KERNEL);
-    st = build_tile_plan(p, chosen, o.lds_pad, o.grid_mode);
+    st = build_tile_plan(p, chosen, o.lds_pad, o.grid_mode,
+                         o.window_in > 0 ? o.window_in : kDefaultWindow,
+                         o.window_out > 0 ? o.window_out : kDefaultWindow,
+                         o.threads > 0 ? o.threads : kDefaultThreads);
     if (st != TPERM_OK) return fail(st);
+    if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
+    if (o.cache_policy == 1 || o.cache_policy == 2) p->cache_policy = o.cache_policy;
     *out = p;
     return TPERM_OK;
 }
@@ -667,7 +765,7 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
     canonicalise(rank, dims, perm, &p->c);
     std::memset(&p->tile, 0, sizeof(p->tile));
     build_naive_desc(p);
-    st = build_tile_plan(p, cand, -1, 0);
+    st = build_tile_plan(p, cand, -1, 0, kDefaultWindow, kDefaultWindow, kDefaultThreads);
     if (st != TPERM_OK) {
         delete p;
         return st;
@@ -694,11 +792,11 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
     }
     const TileDesc& d = plan.tile;
     std::vector<int64_t> lds(plan.use_lds ? d.lds_elems : 1, -1);
-    const uint32_t slots = (uint32_t)plan.nreg * TPERM_THREADS;
+    const uint32_t slots = (uint32_t)plan.nreg * (uint32_t)plan.threads;
     if (slots < d.tile_vol) return TPERM_ERR_INTERNAL;
     // visit tiles the way a launch with `grid` workgroups would; any grid gives the same
     // set of tiles, use a small one that still exercises the iteration arithmetic
-    const uint32_t grid = d.grid_mode == 1u ? 16u : 7u;
+    const uint32_t grid = d.grid_mode != 0u ? 16u : 7u;
     std::vector<char> tile_seen(d.num_tiles, 0);
     for (uint32_t block = 0; block < grid; ++block)
         for (uint32_t it = 0;; ++it) {
@@ -714,8 +812,8 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
                 maj_in += (uint64_t)coord[l] * d.major.stride_in[l];
                 maj_out += (uint64_t)coord[l] * d.major.stride_out[l];
             }
-            const uint32_t rem_a = split_remaining(d.split_ext[0], d.split_tile[0], coord[d.lane_a]);
-            const uint32_t rem_b = split_remaining(d.split_ext[1], d.split_tile[1], coord[d.lane_b]);
+            uint32_t rem_a = 0, rem_b = 0;
+            tile_remaining(d, [&](uint32_t l) { return coord[l]; }, &rem_a, &rem_b);
             if (plan.use_lds) {
                 std::fill(lds.begin(), lds.end(), -1);
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {

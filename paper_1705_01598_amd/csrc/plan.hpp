@@ -13,12 +13,16 @@ namespace tperm {
 // Largest tile the tile kernels accept: NREG_MAX slots per thread, and an LDS image that
 // fits the 64 KiB a workgroup may take without opting in to more.
 constexpr int kMaxNreg = 32;
-constexpr int64_t kMaxTileVol = (int64_t)kMaxNreg * TPERM_THREADS;  // 8192 elements
+constexpr int64_t kMaxTileVol = (int64_t)kMaxNreg * TPERM_MAX_THREADS;  // 8192 elements
 constexpr int64_t kMaxLdsBytes = 64 * 1024;
+// Tiles that run at the same time are grouped into windows of this many neighbours along
+// the input side and along the output side (1 = plain input order).
+constexpr int kDefaultWindow = 8;
+constexpr int kDefaultThreads = 256;
 
-// The per-thread slot counts the tile kernel is instantiated for.
-extern const int kNregSet[];
-extern const int kNregSetSize;
+// The per-thread slot counts the tile kernel is instantiated for, by workgroup size.
+// Returns the smallest instantiated count >= need, or -1.
+int pick_nreg(int64_t tile_vol, int threads);
 
 struct Canonical {
     int rank = 0;
@@ -34,6 +38,7 @@ struct Candidate {
     int m = 0, k = 0;
     int64_t t[TPERM_MAX_RANK] = {0};
     int64_t tile_vol = 0, run_in = 0, run_out = 0, num_tiles = 0;
+    bool aligned = false;      // every run starts and ends on a 128-byte line boundary
     double utilisation = 1.0;  // useful fraction of the slots of all tiles (ragged edges)
     double score = 0.0;        // relative cost estimate, lower is better
 };
@@ -48,9 +53,12 @@ struct Plan {
     Candidate cand;
     bool use_lds = false;
     int nreg = 0;
+    int threads = TPERM_MAX_THREADS;  // workgroup size: 256 (four wavefronts) or 64 (one)
     int lds_pad = 0;
     int lds_bytes = 0;
     int grid_mode = 0;
+    int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
+    int cache_policy = 1;    // 1 = cached, 2 = nontemporal global loads and stores
     TileDesc tile;
     NaiveDesc naive;
     // launch geometry, resolved on first execute (needs the device); 0 = not yet
@@ -69,7 +77,8 @@ bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
                     int64_t tile_out, bool use_lds, Candidate* out);
 
 // Fill plan->tile (and nreg, lds size, padding) from a candidate.
-tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode);
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
+                               int window_in, int window_out, int threads);
 void build_naive_desc(Plan* plan);
 
 // Plan creation proper.
@@ -86,6 +95,6 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in);
 // Estimated LDS cycles of the first accesses of a workgroup for a given descriptor
 // (bank-conflict count evaluated from the slot positions, as Section 2.3 does for the
 // shared-memory term of its model).
-double lds_conflict_cost(const TileDesc& d, int elem, int nreg);
+double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads);
 
 }  // namespace tperm

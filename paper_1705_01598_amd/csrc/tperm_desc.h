@@ -16,7 +16,7 @@
 #endif
 
 #define TPERM_DESC_MAX_DIMS 16   // canonical rank limit = lanes of one DPP row
-#define TPERM_THREADS 256        // threads per workgroup of the tile kernels
+#define TPERM_MAX_THREADS 256    // largest workgroup of the tile kernels (4 wavefronts)
 #define TPERM_NO_REM 0xFFFFu     // "no split on this side": every real coordinate is below it
 
 namespace tperm {
@@ -53,6 +53,14 @@ struct MajorDims {
     uint32_t stride_out[TPERM_DESC_MAX_DIMS];  // elements
 };
 
+// A major dimension whose counter is split into a low part of `width` values (placed early
+// in the tile order, so that tiles running at the same time are neighbours along that
+// dimension) and a high part: counter = c[lane_lo] + width * c[lane_hi].  Combinations with
+// counter >= count do not exist and are skipped.  count == 0: pair unused.
+struct SplitPair {
+    uint32_t lane_lo, lane_hi, width, count;
+};
+
 // Descriptor of the generic tile kernel (Tiled, Packed, PackedSplit and the LDS-free
 // row-copy all reduce to it).
 struct TileDesc {
@@ -63,10 +71,14 @@ struct TileDesc {
     uint32_t split_ext[2];  // full extent d of split dim A / B (0 if none)
     uint32_t split_tile[2]; // tile extent t of split dim A / B
     uint32_t lds_elems;     // size of the LDS image (with padding), elements
-    uint32_t grid_mode;     // 0: tile b = block + i*grid;  1: contiguous tile range per XCD
+    uint32_t grid_mode;     // how workgroups walk the tiles, see tile_of()
     uint32_t tiles_per_xcd; // grid_mode 1: ceil(num_tiles / 8)
+    uint32_t group_log2;    // grid_mode 2: log2 of the tile group dealt to one XCD
     uint32_t lane_a;        // lane of `major` holding the chunk counter of split A (if any)
     uint32_t lane_b;        // same for split B
+    uint32_t chunk_pair[2]; // index of the SplitPair that carries the chunk counter of split
+                            // A / B instead of a single lane; >= 2: none
+    SplitPair pair[2];
     TileDim in_order[TPERM_DESC_MAX_DIMS];   // tile dims, input order (k enumerates these)
     TileDim out_order[TPERM_DESC_MAX_DIMS];  // the same dims, output order
     MajorDims major;
@@ -108,20 +120,51 @@ TPERM_HD uint32_t major_coord(const MajorDims& m, uint32_t lane, uint32_t b) {
 // Remaining extent of a split dim in the chunk with counter `chunk` (ragged last chunk).
 TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t chunk) {
     if (full_ext == 0u) return TPERM_NO_REM;
-    const uint32_t left = full_ext - chunk * tile_ext;
+    const uint32_t start = chunk * tile_ext;
+    if (start >= full_ext) return 0u;
+    const uint32_t left = full_ext - start;
     return left < tile_ext ? left : tile_ext;
 }
 
+// From the per-lane coordinates of a tile (coord(l) returns lane l's coordinate): does the
+// tile exist, and what is left of the split dims in it.  A tile that does not exist gets
+// remaining extents of 0, which masks every slot.
+template <typename CoordFn>
+TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, uint32_t* rem_b) {
+    bool exists = true;
+    uint32_t counter[2] = {0u, 0u};
+    for (int p = 0; p < 2; ++p)
+        if (d.pair[p].count != 0u) {
+            counter[p] = coord(d.pair[p].lane_lo) + d.pair[p].width * coord(d.pair[p].lane_hi);
+            exists = exists && counter[p] < d.pair[p].count;
+        }
+    const uint32_t chunk_a = d.chunk_pair[0] < 2u ? counter[d.chunk_pair[0]] : coord(d.lane_a);
+    const uint32_t chunk_b = d.chunk_pair[1] < 2u ? counter[d.chunk_pair[1]] : coord(d.lane_b);
+    *rem_a = exists ? split_remaining(d.split_ext[0], d.split_tile[0], chunk_a) : 0u;
+    *rem_b = exists ? split_remaining(d.split_ext[1], d.split_tile[1], chunk_b) : 0u;
+}
+
 // Tile visited by workgroup `block` of `grid` on its i-th iteration, or num_tiles if done.
+// Workgroups are dealt round-robin to the 8 XCDs (workgroup w runs on XCD w % 8), each with
+// its own L2.  grid_mode 0 walks the tiles in launch order, so neighbouring tiles run on
+// different XCDs.  grid_mode 1 gives each XCD one contiguous eighth of the tiles.
+// grid_mode 2 deals groups of 2^group_log2 consecutive tiles to the XCDs in turn: tiles
+// that share cache lines at their edges meet in one L2, while all XCDs still work on the
+// same neighbourhood of the tensors.  Modes 1 and 2 need grid % 8 == 0.
 TPERM_HD uint32_t tile_of(const TileDesc& d, uint32_t block, uint32_t grid, uint32_t i) {
     if (d.grid_mode == 1u) {
-        // workgroups are dealt round-robin to the 8 XCDs: give each XCD one contiguous
-        // range of tiles so neighbouring tiles share an L2
         const uint32_t xcd = block & 7u, slot = block >> 3, per = grid >> 3;
         const uint32_t local = slot + i * per;
         if (local >= d.tiles_per_xcd) return d.num_tiles;
         const uint32_t b = xcd * d.tiles_per_xcd + local;
         return b < d.num_tiles ? b : d.num_tiles;
+    }
+    if (d.grid_mode == 2u) {
+        const uint32_t xcd = block & 7u, slot = block >> 3, per = grid >> 3;
+        const uint64_t local = (uint64_t)slot + (uint64_t)i * per;
+        const uint64_t group = local >> d.group_log2;
+        const uint64_t b = (((group << 3) + xcd) << d.group_log2) + (local & ((1u << d.group_log2) - 1u));
+        return b < d.num_tiles ? (uint32_t)b : d.num_tiles;
     }
     const uint64_t b = (uint64_t)block + (uint64_t)i * grid;
     return b < d.num_tiles ? (uint32_t)b : d.num_tiles;

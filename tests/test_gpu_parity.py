@@ -101,7 +101,7 @@ TILES = [
 
 
 @pytest.mark.parametrize("elem", [8, 4])
-@pytest.mark.parametrize("grid_mode", [0, 1])
+@pytest.mark.parametrize("grid_mode", [0, 1, 2, 6])
 @pytest.mark.parametrize("dims,perm,m,tin,k,tout", TILES)
 def test_explicit_tiles_match_oracle(dims, perm, m, tin, k, tout, grid_mode, elem):
     case = wl.make_case(0, 3, dims, perm, elem)

@@ -166,7 +166,7 @@ def test_index_maps_of_every_gpu_test_plan():
                 except B.TpermError as e:
                     assert e.status == B.ERR_KERNEL
         for dims, perm, m, tin, k, tout in G.TILES:
-            for gm in (0, 1):
+            for gm in (0, 1, 2, 5):
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
                         tile_out=tout, grid_mode=gm)
 
@@ -201,7 +201,9 @@ def test_index_maps_random_shapes_and_tiles():
             tout = int(rng.integers(1, info.canon_dims[info.canon_perm[k - 1]] + 1))
             try:
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
-                        tile_out=tout, grid_mode=int(rng.integers(0, 2)))
+                        tile_out=tout, grid_mode=int(rng.integers(0, 8)),
+                        window_in=int(rng.choice([0, 1, 4, 16])), window_out=int(rng.choice([0, 1, 3, 16])),
+                        threads=int(rng.choice([64, 256])))
             except B.TpermError as e:
                 assert e.status == B.ERR_KERNEL     # tile too large for LDS / registers
         done += 1
