@@ -1,0 +1,131 @@
+"""GPU parity at the full benchmark sizes, with the plans the benchmark times.
+
+Where the CPU oracle finishes a whole tensor in about a second the comparison is element by
+element; for the 330-case rank sweep the output is checked on seeded sampled positions that
+the oracle computes one by one, plus properties that hold at any size: every element is
+written (a sentinel pre-fill is gone), nothing is written outside the tensor (guard bands),
+and the result is a permutation of the input (index-stamp input: the sum of the output
+equals the sum of 0..vol-1; on a subset, the sorted output is exactly 0..vol-1).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1705_01598_amd import binding as B
+from paper_1705_01598_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+from gpu_util import GUARD, np_uint, to_device  # noqa: E402
+
+N_SAMPLES = 4096
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _full_compare(case, values="uniform"):
+    a = wl.uniform_values(case) if values == "uniform" else wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    out = torch.full((case.volume + 2 * GUARD,), -1, dtype=a_dev.dtype, device="cuda")
+    plan = B.tperm_plan_create(case.dims, case.perm, case.elem_size)
+    B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr() + GUARD * case.elem_size, _stream())
+    torch.cuda.synchronize()
+    got = np_uint(out[GUARD:GUARD + case.volume].cpu().numpy())
+    ref = np_uint(oracle.transpose(np_uint(a), case.dims, case.perm))
+    assert bool((out[:GUARD] == -1).all()) and bool((out[GUARD + case.volume:] == -1).all()), case.name
+    bad = np.nonzero(got != ref)[0]
+    assert bad.size == 0, f"{case.name}: {bad.size} wrong elements, first {bad[:4]}, plan {B.info_dict(plan.describe())}"
+
+
+def _stamp_check(case, stamp, out, sort_check=False):
+    """Index-stamp input already on the device in `stamp`; `out` is a guarded scratch."""
+    vol = case.volume
+    out.fill_(-1)
+    plan = B.tperm_plan_create(case.dims, case.perm, case.elem_size)
+    B.tperm_execute(plan, stamp.data_ptr(), out.data_ptr() + GUARD * case.elem_size, _stream())
+    torch.cuda.synchronize()
+    body = out[GUARD:GUARD + vol]
+    desc = f"{case.name} dims={case.dims} perm={case.perm} plan={B.info_dict(plan.describe())}"
+    assert bool((out[:GUARD] == -1).all()) and bool((out[GUARD + vol:GUARD + vol + GUARD] == -1).all()), desc
+    assert bool((body >= 0).all()), "unwritten elements: " + desc
+    assert int(body.sum(dtype=torch.int64)) == vol * (vol - 1) // 2, "not a permutation: " + desc
+    pos = wl.sample_positions(case, N_SAMPLES)
+    got = body[torch.from_numpy(pos).cuda()].cpu().numpy().astype(np.int64)
+    # the stamp at output position o is the input position the oracle assigns to o
+    expect = oracle.sample(np.arange(vol, dtype=np.int64), case.dims, case.perm, pos) \
+        if vol <= (1 << 24) else np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
+    assert np.array_equal(got, expect), "sampled positions differ: " + desc
+    if sort_check:
+        srt = torch.sort(body).values
+        assert bool((srt == torch.arange(vol, dtype=body.dtype, device="cuda")).all()), desc
+
+
+def test_config1_full():
+    _full_compare(wl.config1()[0])
+
+
+@pytest.mark.parametrize("idx", [0, 1, 8, 15, 22])
+def test_config2_full_compare(idx):
+    _full_compare(wl.config2()[idx])
+
+
+def test_config2_all_permutations_sampled():
+    cases = wl.config2()
+    vol = cases[0].volume
+    stamp = torch.arange(vol, dtype=torch.int64, device="cuda")
+    out = torch.empty(vol + 2 * GUARD, dtype=torch.int64, device="cuda")
+    for i, case in enumerate(cases):
+        _stamp_check(case, stamp, out, sort_check=(i % 8 == 0))
+
+
+@pytest.mark.parametrize("idx", [1, 16])
+def test_config3_full_compare(idx):
+    _full_compare(wl.config3()[idx], values="bits")
+
+
+def test_config3_all_cases_sampled():
+    cases = wl.config3()
+    big = max(c.volume for c in cases)
+    stamp = torch.arange(big, dtype=torch.int64, device="cuda")
+    out = torch.empty(big + 2 * GUARD, dtype=torch.int64, device="cuda")
+    for case in cases:
+        _stamp_check(case, stamp[:case.volume], out[:case.volume + 2 * GUARD])
+
+
+@pytest.mark.parametrize("rank", list(range(2, 13)))
+def test_config4_rank_sweep_sampled(rank):
+    cases = wl.config4(ranks=(rank,))
+    big = max(c.volume for c in cases)
+    stamp = torch.arange(big, dtype=torch.int64, device="cuda")
+    out = torch.empty(big + 2 * GUARD, dtype=torch.int64, device="cuda")
+    for i, case in enumerate(cases):
+        _stamp_check(case, stamp[:case.volume], out[:case.volume + 2 * GUARD], sort_check=(i == 7))
+
+
+@pytest.mark.parametrize("idx", [40, 171, 300, 329])
+def test_config4_full_compare(idx):
+    _full_compare(wl.config4()[idx])
+
+
+def test_config5_all_cases_full_compare():
+    for case in wl.config5():
+        _full_compare(case, values="uniform" if case.index % 2 else "bits")
+
+
+def test_measured_plans_on_config2_subset():
+    """Measurement-based selection (Section 2.3) returns a plan that is still exact."""
+    for case in wl.config2()[::11]:
+        a = wl.stamp_values(case)
+        a_dev = torch.from_numpy(a).cuda()
+        out = torch.full((case.volume,), -1, dtype=torch.int64, device="cuda")
+        plan = B.tperm_plan_create_measured(case.dims, case.perm, 8, a_dev.data_ptr(), out.data_ptr(),
+                                            _stream(), 16)
+        out.fill_(-1)
+        B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr(), _stream())
+        torch.cuda.synchronize()
+        pos = wl.sample_positions(case, N_SAMPLES)
+        got = out[torch.from_numpy(pos).cuda()].cpu().numpy()
+        expect = np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
+        assert np.array_equal(got, expect) and int(out.sum()) == case.volume * (case.volume - 1) // 2
