@@ -79,7 +79,8 @@ typedef struct {
     int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
     int window_out;     /* on the input / output side; 0 = default, 1 = plain input order     */
     int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
-    int reserved[3];
+    int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
+    int reserved[2];
 } tperm_plan_opts_t;
 
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
@@ -118,6 +119,16 @@ tperm_status_t tperm_plan_create(tperm_plan_t *plan, int rank, const int64_t *di
 tperm_status_t tperm_plan_create_ex(tperm_plan_t *plan, int rank, const int64_t *dims,
                                     const int *perm, size_t elem_size,
                                     const tperm_plan_opts_t *opts);
+
+/* Enumeration of the feasible staged plans (Section 2.3: every plan that can run is
+ * created, then one is kept).  tperm_plan_candidate_count returns how many tile candidates
+ * the selector sees for the problem, best estimate first; tperm_plan_create_candidate
+ * builds the plan for candidate `index`.  Host only.  Problems whose canonical form is a
+ * copy have no candidates. */
+tperm_status_t tperm_plan_candidate_count(int rank, const int64_t *dims, const int *perm,
+                                          size_t elem_size, int *count);
+tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                           const int *perm, size_t elem_size, int index);
 
 /* Measurement-based plan selection (Section 2.3): every candidate plan the selector
  * enumerates is executed on (in, out) on `hip_stream` and timed with HIP events; the

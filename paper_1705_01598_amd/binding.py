@@ -24,6 +24,7 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
                 KERNEL_TILED: "tiled", KERNEL_PACKED: "packed", KERNEL_NAIVE: "naive"}
 
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
+           "tperm_plan_candidate_count", "tperm_plan_create_candidate",
            "tperm_execute", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes"]
 
@@ -34,7 +35,7 @@ class PlanOpts(ctypes.Structure):
                 ("grid_mode", ctypes.c_int), ("blocks_per_cu", ctypes.c_int),
                 ("cache_policy", ctypes.c_int), ("window_in", ctypes.c_int),
                 ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
-                ("reserved", ctypes.c_int * 3)]
+                ("lds_buffers", ctypes.c_int), ("reserved", ctypes.c_int * 2)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -75,6 +76,9 @@ def lib() -> ctypes.CDLL:
                                            ctypes.c_size_t, ctypes.POINTER(PlanOpts)]
         L.tperm_plan_create_measured.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
                                                  ctypes.c_size_t, vp, vp, vp, ctypes.c_int]
+        L.tperm_plan_candidate_count.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, ip]
+        L.tperm_plan_create_candidate.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
+                                                  ctypes.c_size_t, ctypes.c_int]
         L.tperm_execute.argtypes = [vp, vp, vp, vp]
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
@@ -141,12 +145,13 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                          kernel_class: int = KERNEL_AUTO, m: int = 0, tile_in: int = 0, k: int = 0,
                          tile_out: int = 0, lds_pad: int = -1, grid_mode: int = 0,
                          blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
-                         window_out: int = 0, threads: int = 0) -> Plan:
+                         window_out: int = 0, threads: int = 0, lds_buffers: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
                     tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
                     blocks_per_cu=int(blocks_per_cu), cache_policy=int(cache_policy),
-                    window_in=int(window_in), window_out=int(window_out), threads=int(threads))
+                    window_in=int(window_in), window_out=int(window_out), threads=int(threads),
+                    lds_buffers=int(lds_buffers))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:
@@ -164,6 +169,25 @@ def tperm_plan_create_measured(dims: Sequence[int], perm: Sequence[int], elem_si
                                           ctypes.c_void_p(stream), int(max_candidates))
     if st != OK:
         raise TpermError(st, "tperm_plan_create_measured")
+    return Plan(h)
+
+
+def tperm_plan_candidate_count(dims: Sequence[int], perm: Sequence[int], elem_size: int) -> int:
+    rank, cd, cp = _marshal(dims, perm)
+    n = ctypes.c_int(0)
+    st = lib().tperm_plan_candidate_count(rank, cd, cp, int(elem_size), ctypes.byref(n))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_candidate_count")
+    return int(n.value)
+
+
+def tperm_plan_create_candidate(dims: Sequence[int], perm: Sequence[int], elem_size: int,
+                                index: int) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create_candidate(ctypes.byref(h), rank, cd, cp, int(elem_size), int(index))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create_candidate")
     return Plan(h)
 
 

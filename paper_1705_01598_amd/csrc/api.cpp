@@ -179,6 +179,34 @@ tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t* out_to_in) {
     return tperm::index_map(*plan->p, out_to_in);
 }
 
+tperm_status_t tperm_plan_candidate_count(int rank, const int64_t* dims, const int* perm,
+                                          size_t elem_size, int* count) {
+    if (count == nullptr) return TPERM_ERR_NULL;
+    *count = 0;
+    tperm_status_t st = tperm::validate(rank, dims, perm, elem_size);
+    if (st != TPERM_OK) return st;
+    tperm::Canonical c;
+    tperm::canonicalise(rank, dims, perm, &c);
+    *count = (int)tperm::enumerate_candidates(c, (int)elem_size).size();
+    return TPERM_OK;
+}
+
+tperm_status_t tperm_plan_create_candidate(tperm_plan_t* plan, int rank, const int64_t* dims,
+                                           const int* perm, size_t elem_size, int index) {
+    if (plan == nullptr) return TPERM_ERR_NULL;
+    *plan = nullptr;
+    tperm_status_t st = tperm::validate(rank, dims, perm, elem_size);
+    if (st != TPERM_OK) return st;
+    tperm::Canonical c;
+    tperm::canonicalise(rank, dims, perm, &c);
+    const std::vector<tperm::Candidate> cands = tperm::enumerate_candidates(c, (int)elem_size);
+    if (index < 0 || index >= (int)cands.size()) return TPERM_ERR_KERNEL;
+    Plan* p = nullptr;
+    st = tperm::create_plan_with_candidate(&p, rank, dims, perm, elem_size, cands[index]);
+    if (st != TPERM_OK) return st;
+    return wrap(p, plan);
+}
+
 tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const int64_t* dims,
                                           const int* perm, size_t elem_size, const void* in,
                                           void* out, void* hip_stream, int max_candidates) {

@@ -158,9 +158,9 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     uint32_t it = 0;
     uint32_t b = tile_of(d, block, grid, it);
     reg_t v[NREG];
-    MajorPos pos;
-    pos.in = pos.out = 0;
-    pos.rem_a = pos.rem_b = 0;
+    MajorPos pos, nxt;
+    pos.in = pos.out = pos.rem_a = pos.rem_b = 0;
+    nxt = pos;
     if (b < d.num_tiles) {
         pos = major_position(d, ml, b);
         const uint32_t soff = pos.in * (uint32_t)sizeof(T);
@@ -169,39 +169,47 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
                 v[j] = io::load(rsrc_in, rd_off[j], soff);
     }
+    // the position of the tile after this one is worked out while the loads are in flight
+    uint32_t bn = tile_of(d, block, grid, it + 1);
+    if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
+    const bool two_buffers = d.lds_buffers == 2u;
     while (b < d.num_tiles) {
-        const MajorPos cur = pos;
         reg_t w[NREG];
         if (USE_LDS) {
+            // with two LDS images the tiles alternate between them and one barrier per
+            // tile is enough: a wave can only overwrite an image two tiles later, after
+            // the barrier of the tile in between
+            reg_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], cur.rem_a, cur.rem_b)) lds[lds_pos[j] & 0xFFFFu] = v[j];
+                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) img[lds_pos[j] & 0xFFFFu] = v[j];
             __syncthreads();
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], cur.rem_a, cur.rem_b)) w[j] = lds[lds_pos[j] >> 16];
+                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
         } else {
 #pragma unroll
             for (int j = 0; j < NREG; ++j) w[j] = v[j];
         }
         // reads of the next tile go out before the stores of this one
-        ++it;
-        const uint32_t bn = tile_of(d, block, grid, it);
         if (bn < d.num_tiles) {
-            pos = major_position(d, ml, bn);
-            const uint32_t soff = pos.in * (uint32_t)sizeof(T);
+            const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
+                if (slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b))
                     v[j] = io::load(rsrc_in, rd_off[j], soff);
         }
-        const uint32_t soff_out = cur.out * (uint32_t)sizeof(T);
+        const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
 #pragma unroll
         for (int j = 0; j < NREG; ++j)
-            if (slot_valid(wr_mask[j], cur.rem_a, cur.rem_b))
+            if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
                 io::store(w[j], rsrc_out, wr_off[j], soff_out);
-        if (USE_LDS) __syncthreads();  // every wave has finished reading this LDS image
         b = bn;
+        pos = nxt;
+        ++it;
+        bn = tile_of(d, block, grid, it + 1);
+        if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
+        if (USE_LDS && !two_buffers) __syncthreads();  // all waves are done reading the image
     }
 }
 
@@ -302,7 +310,7 @@ hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {
     const void* f = tile_kernel_for(plan);
     if (f == nullptr) return hipErrorInvalidValue;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, f, plan.threads,
-                                                        (size_t)plan.lds_bytes);
+                                                        (size_t)plan.lds_bytes * plan.tile.lds_buffers);
 }
 
 hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid) {
@@ -312,7 +320,7 @@ hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t 
     uint32_t nbytes = (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
     void* args[] = {(void*)&d, (void*)&in, (void*)&out, (void*)&nbytes};
     return hipLaunchKernel(f, dim3((unsigned)grid), dim3((unsigned)plan.threads), args,
-                           (size_t)plan.lds_bytes, stream);
+                           (size_t)plan.lds_bytes * plan.tile.lds_buffers, stream);
 }
 
 hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream) {

@@ -189,7 +189,8 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     cd->run_in = run_in;
     cd->run_out = run_out;
     cd->utilisation = util;
-    if (cd->use_lds && vol * elem > kMaxLdsBytes) return false;  // unpadded image must fit
+    // the LDS image must fit with room left for the bank-conflict padding
+    if (cd->use_lds && vol * elem > kMaxLdsBytes - 8192) return false;
 
     // Alignment granule of run starts on each side: every stride that separates two runs
     // (the strides of all dims other than the run's own leading dims, and the chunk step
@@ -221,22 +222,25 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
         if (cd->t[0] < c.dims[0]) gin = (double)gcd64((int64_t)gin, cd->t[0] * elem);
     }
     // Cost per useful byte on each side: 128-byte lines touched per line's worth of useful
-    // data, plus a fixed per-run overhead worth about 64 bytes (short runs leave lanes of a
-    // 64-wide memory instruction straddling several rows).  A partially written line costs
-    // about twice a full one (cf. Eq. (13)).
-    const double cost_in = (rin + 64.0 + (128.0 - gin)) / rin;
-    const double cost_out = (rout + 64.0 + 2.0 * (128.0 - gout)) / rout;
+    // data, plus a fixed per-run overhead.  The constants were fitted on MI355X to the
+    // measured times of every candidate of 115 benchmark cases: output runs keep paying off
+    // up to about 2 KiB (overhead worth 64 bytes, misalignment weighted 4x: a partially
+    // written line costs far more than a partially read one, cf. Eq. (13)), input runs are
+    // flat from 128 bytes on (overhead worth 16 bytes).
+    double cost_in = (rin + 16.0 + (128.0 - gin)) / rin;
+    if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
+    const double cost_out = (rout + 64.0 + 4.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
-    // Measured on MI355X: throughput peaks when a compute unit keeps about 16-24 KiB of
-    // reads in flight, which two to three workgroups with 8-12 KiB tiles provide; smaller
-    // tiles pay more per-tile overhead, larger ones overshoot.
+    // Tile size: throughput is flat between 8 and 16 KiB tiles (two or three workgroups per
+    // compute unit then keep 16-24 KiB of reads in flight), falls slowly below, and falls
+    // above as fewer workgroups fit and LDS padding runs out of room.
     const double bytes = (double)vol * elem;
-    if (bytes < 6144.0) cost *= 1.0 + 0.08 * std::log2(6144.0 / bytes);
-    if (bytes > 8192.0) cost *= 1.0 + 0.10 * std::log2(bytes / 8192.0);
+    if (bytes < 8192.0) cost *= 1.0 + 0.08 * std::log2(8192.0 / bytes);
+    if (bytes > 16384.0) cost *= 1.0 + 0.15 * std::log2(bytes / 16384.0);
     // Too few tiles cannot fill 256 compute units.
-    if (tiles < 1024) cost *= 1.0 + 0.5 * std::log2(1024.0 / (double)tiles) / 10.0;
+    if (tiles < 1024) cost *= 1.0 + 0.05 * std::log2(1024.0 / (double)tiles);
     // The LDS stage itself is not free.
-    if (cd->use_lds) cost *= 1.03;
+    if (cd->use_lds) cost *= 1.05;
     // Nontemporal accesses pay off when every run starts and ends on a line boundary; with
     // ragged runs neighbouring tiles share lines and want them kept in L2.
     cd->aligned = (gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
@@ -414,7 +418,7 @@ static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* di
 }
 
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
-                               int window_in, int window_out, int threads) {
+                               int window_in, int window_out, int threads, int lds_buffers) {
     if (threads != 64 && threads != 256) return TPERM_ERR_KERNEL;
     const Canonical& c = plan->c;
     const int r = c.rank;
@@ -624,6 +628,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         if (lds_elems > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
     }
     d.lds_elems = lds_elems;
+    d.lds_buffers = (cand.use_lds && lds_buffers == 2 && (int64_t)lds_elems * elem * 2 <= kMaxLdsBytes) ? 2u : 1u;
     // grid_mode values >= 2 carry the group size: mode 2 + log2(group) (2 -> groups of 1)
     d.grid_mode = grid_mode >= 2 ? 2u : (uint32_t)grid_mode;
     d.group_log2 = grid_mode >= 2 ? (uint32_t)(grid_mode - 2) : 0u;
@@ -740,7 +745,8 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     st = build_tile_plan(p, chosen, o.lds_pad, o.grid_mode,
                          o.window_in > 0 ? o.window_in : kDefaultWindow,
                          o.window_out > 0 ? o.window_out : kDefaultWindow,
-                         o.threads > 0 ? o.threads : kDefaultThreads);
+                         o.threads > 0 ? o.threads : kDefaultThreads,
+                         o.lds_buffers > 0 ? o.lds_buffers : kDefaultLdsBuffers);
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy == 1 || o.cache_policy == 2) p->cache_policy = o.cache_policy;
@@ -765,7 +771,8 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
     canonicalise(rank, dims, perm, &p->c);
     std::memset(&p->tile, 0, sizeof(p->tile));
     build_naive_desc(p);
-    st = build_tile_plan(p, cand, -1, 0, kDefaultWindow, kDefaultWindow, kDefaultThreads);
+    st = build_tile_plan(p, cand, -1, 0, kDefaultWindow, kDefaultWindow, kDefaultThreads,
+                         kDefaultLdsBuffers);
     if (st != TPERM_OK) {
         delete p;
         return st;

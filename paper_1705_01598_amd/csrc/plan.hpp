@@ -19,6 +19,7 @@ constexpr int64_t kMaxLdsBytes = 64 * 1024;
 // the input side and along the output side (1 = plain input order).
 constexpr int kDefaultWindow = 8;
 constexpr int kDefaultThreads = 256;
+constexpr int kDefaultLdsBuffers = 1;
 
 // The per-thread slot counts the tile kernel is instantiated for, by workgroup size.
 // Returns the smallest instantiated count >= need, or -1.
@@ -78,7 +79,7 @@ bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
 
 // Fill plan->tile (and nreg, lds size, padding) from a candidate.
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
-                               int window_in, int window_out, int threads);
+                               int window_in, int window_out, int threads, int lds_buffers);
 void build_naive_desc(Plan* plan);
 
 // Plan creation proper.

@@ -70,7 +70,8 @@ struct TileDesc {
     uint32_t n_major;       // terms in use in `major` (the rest are neutral)
     uint32_t split_ext[2];  // full extent d of split dim A / B (0 if none)
     uint32_t split_tile[2]; // tile extent t of split dim A / B
-    uint32_t lds_elems;     // size of the LDS image (with padding), elements
+    uint32_t lds_elems;     // size of one LDS image (with padding), elements
+    uint32_t lds_buffers;   // 1, or 2: tiles alternate between two images (one barrier per tile)
     uint32_t grid_mode;     // how workgroups walk the tiles, see tile_of()
     uint32_t tiles_per_xcd; // grid_mode 1: ceil(num_tiles / 8)
     uint32_t group_log2;    // grid_mode 2: log2 of the tile group dealt to one XCD

@@ -94,7 +94,7 @@ TILES = [
     ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 3, 3, 3, 5),
     ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 2, 4, 2, 4),
     ((5, 45, 33, 7), (0, 2, 1, 3), 2, 11, 2, 8),
-    ((5, 45, 33, 7), (0, 2, 1, 3), 2, 45, 2, 33),
+    ((5, 45, 33, 7), (0, 2, 1, 3), 2, 45, 2, 30),
     ((1000, 3), (1, 0), 1, 333, 2, 0),
     ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4), 2, 8, 2, 8),
 ]
@@ -109,6 +109,22 @@ def test_explicit_tiles_match_oracle(dims, perm, m, tin, k, tout, grid_mode, ele
                                   k=k, tile_out=tout, grid_mode=grid_mode)
     _check(case, plan)
     plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("threads", [64, 256])
+@pytest.mark.parametrize("lds_buffers", [1, 2])
+@pytest.mark.parametrize("dims,perm,m,tin,k,tout", TILES[:8])
+def test_workgroup_size_and_lds_buffering(dims, perm, m, tin, k, tout, lds_buffers, threads, elem):
+    case = wl.make_case(0, 11, dims, perm, elem)
+    try:
+        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin,
+                                      k=k, tile_out=tout, threads=threads, lds_buffers=lds_buffers,
+                                      cache_policy=1 + (lds_buffers % 2), window_in=4, window_out=3)
+    except B.TpermError as e:
+        assert e.status == B.ERR_KERNEL and threads == 64     # tile too large for one wavefront
+        pytest.skip("tile does not fit a single-wavefront workgroup")
+    _check(case, plan)
 
 
 @pytest.mark.parametrize("pad", [0, 1, 2, 5])
