@@ -40,6 +40,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload family 1..5 (default 2)")
     ap.add_argument("--stride", type=int, default=1, help="take every n-th case of the family")
     ap.add_argument("--plan", choices=["heuristic", "measured"], default="heuristic")
+    ap.add_argument("--also-measured", action="store_true",
+                    help="after the main pass, time the same step with measurement-selected plans")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cases-out", default="", help="write per-case results (JSON lines) here")
     return ap.parse_args()
@@ -220,6 +222,21 @@ def main():
                      "traffic": traffic, "kernel": "tperm::tile_kernel",
                      "avg_launch_us": round(float(tile_ms.mean()) * 1e3, 2) if tile_mask.any() else None},
     }
+    if args.also_measured and args.plan == "heuristic":
+        # Section 2.3's other selection scheme, for comparison: plans chosen by timing every
+        # candidate once at plan creation (outside any timed region)
+        a, b = pairs[0]
+        mplans = [B.tperm_plan_create_measured(c.dims, c.perm, c.elem_size, a.data_ptr(), b.data_ptr(),
+                                               stream, 64) for c in cases]
+        plans[:] = mplans
+        for w in range(args.warmup):
+            one_step(w)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            one_step(s)
+        torch.cuda.synchronize()
+        result["measured_plans_value"] = round(step_bytes * args.steps / (time.perf_counter() - t0) / 1e9, 1)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cases)
     print(json.dumps(result))

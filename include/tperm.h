@@ -80,7 +80,8 @@ typedef struct {
     int window_out;     /* on the input / output side; 0 = default, 1 = plain input order     */
     int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
-    int reserved[2];
+    int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */
+    int reserved[1];
 } tperm_plan_opts_t;
 
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
@@ -106,7 +107,8 @@ typedef struct {
     double score;                          /* selector's estimate (relative, lower = better)*/
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
     int cache_policy;                      /* 1 = cached, 2 = nontemporal                   */
-    int reserved[6];
+    int align_out;                         /* 1 if stores are issued line-aligned           */
+    int reserved[5];
 } tperm_plan_info_t;
 
 /* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is

@@ -107,7 +107,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // the tile kernel
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int NREG, int THREADS, bool USE_LDS, bool NT>
+template <typename T, int NREG, int THREADS, bool USE_LDS, bool NT, bool ALIGN>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
     typedef Elem<T, NT> io;
@@ -122,6 +122,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
     uint32_t lds_pos[NREG];  // low half: slot written on the read side; high half: slot
                              // read on the write side
+    uint32_t wr_aux[NREG];   // line-aligned stores: position in the padded row | row phase << 16
 #pragma unroll
     for (int j = 0; j < NREG; ++j) {
         const uint32_t k = tid + (uint32_t)j * THREADS;
@@ -130,7 +131,23 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         lds_pos[j] = 0;
         rd_mask[j] = 0xFFFFFFFFu;  // coordinates no remaining extent exceeds: slot unused
         wr_mask[j] = 0xFFFFFFFFu;
-        if (k < d.tile_vol) {
+        wr_aux[j] = 0xFFFFu;       // a row position beyond every run: slot unused
+        if (ALIGN) {
+            // write side: slot = (output row, position in the padded row)
+            if (k < d.oa.total_slots) {
+                const OutSlot o = out_slot(d.oa, k);
+                wr_off[j] = o.goff * (uint32_t)sizeof(T);
+                wr_mask[j] = o.xo;
+                wr_aux[j] = o.s | (o.rho << 16);
+                lds_pos[j] = o.lpos << 16;
+            }
+            if (k < d.tile_vol) {
+                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
+                rd_off[j] = si.goff * (uint32_t)sizeof(T);
+                rd_mask[j] = si.xa | (si.xb << 16);
+                lds_pos[j] |= si.loff;
+            }
+        } else if (k < d.tile_vol) {
             const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
             wr_off[j] = so.goff * (uint32_t)sizeof(T);
             wr_mask[j] = so.xa | (so.xb << 16);
@@ -173,8 +190,22 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     uint32_t bn = tile_of(d, block, grid, it + 1);
     if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
     const bool two_buffers = d.lds_buffers == 2u;
+    // line-aligned stores: phase of the output base pointer within a 128-byte line
+    const uint32_t line_mask = ALIGN ? d.oa.line_elems - 1u : 0u;
+    const uint32_t out_phase =
+        ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
     while (b < d.num_tiles) {
         reg_t w[NREG];
+        uint32_t shift[NREG];     // ALIGN: this tile's lane shift of each slot's row
+        uint32_t lout_rem = 0, rem_other = 0, phi = 0;
+        if (ALIGN) {
+            const bool exists = pos.rem_a != 0u && pos.rem_b != 0u;
+            const uint32_t run_rem = d.oa.run_split == 0u ? pos.rem_a : pos.rem_b;
+            lout_rem = !exists ? 0u : (d.oa.run_split < 2u ? run_rem * d.oa.run_prefix : d.oa.run_len);
+            rem_other = d.oa.other_split == 0u ? pos.rem_a
+                                               : (d.oa.other_split == 1u ? pos.rem_b : TPERM_NO_REM);
+            phi = (out_phase + pos.out) & line_mask;
+        }
         if (USE_LDS) {
             // with two LDS images the tiles alternate between them and one barrier per
             // tile is enough: a wave can only overwrite an image two tiles later, after
@@ -184,9 +215,19 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             for (int j = 0; j < NREG; ++j)
                 if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) img[lds_pos[j] & 0xFFFFu] = v[j];
             __syncthreads();
+            if (ALIGN) {
 #pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
+                for (int j = 0; j < NREG; ++j) {
+                    shift[j] = (phi + (wr_aux[j] >> 16)) & line_mask;
+                    const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
+                    if (x < lout_rem && wr_mask[j] < rem_other)
+                        w[j] = img[(lds_pos[j] >> 16) - shift[j]];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NREG; ++j)
+                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < NREG; ++j) w[j] = v[j];
@@ -200,10 +241,19 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                     v[j] = io::load(rsrc_in, rd_off[j], soff);
         }
         const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
+        if (ALIGN) {
 #pragma unroll
-        for (int j = 0; j < NREG; ++j)
-            if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
-                io::store(w[j], rsrc_out, wr_off[j], soff_out);
+            for (int j = 0; j < NREG; ++j) {
+                const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
+                if (x < lout_rem && wr_mask[j] < rem_other)
+                    io::store(w[j], rsrc_out, wr_off[j] - shift[j] * (uint32_t)sizeof(T), soff_out);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
+                    io::store(w[j], rsrc_out, wr_off[j], soff_out);
+        }
         b = bn;
         pos = nxt;
         ++it;
@@ -257,12 +307,12 @@ naive_kernel(const NaiveDesc d, const T* __restrict__ in, T* __restrict__ out) {
 // dispatch
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int THREADS, bool USE_LDS, bool NT>
+template <typename T, int THREADS, bool USE_LDS, bool NT, bool ALIGN>
 static const void* tile_kernel_ptr(int nreg) {
     switch (nreg) {
 #define TPERM_CASE(N) \
     case N:           \
-        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT>);
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN>);
         TPERM_CASE(4)
         TPERM_CASE(8)
         TPERM_CASE(12)
@@ -289,11 +339,17 @@ static const void* tile_kernel_ptr(int nreg) {
 template <typename T, int THREADS>
 static const void* tile_kernel_for_threads(const Plan& plan) {
     const bool nt = plan.cache_policy == 2;
-    if (plan.use_lds)
-        return nt ? tile_kernel_ptr<T, THREADS, true, true>(plan.nreg)
-                  : tile_kernel_ptr<T, THREADS, true, false>(plan.nreg);
-    return nt ? tile_kernel_ptr<T, THREADS, false, true>(plan.nreg)
-              : tile_kernel_ptr<T, THREADS, false, false>(plan.nreg);
+    if (plan.use_lds) {
+        if constexpr (THREADS == 256) {
+            if (plan.align_out)
+                return nt ? tile_kernel_ptr<T, THREADS, true, true, true>(plan.nreg)
+                          : tile_kernel_ptr<T, THREADS, true, false, true>(plan.nreg);
+        }
+        return nt ? tile_kernel_ptr<T, THREADS, true, true, false>(plan.nreg)
+                  : tile_kernel_ptr<T, THREADS, true, false, false>(plan.nreg);
+    }
+    return nt ? tile_kernel_ptr<T, THREADS, false, true, false>(plan.nreg)
+              : tile_kernel_ptr<T, THREADS, false, false, false>(plan.nreg);
 }
 
 template <typename T>

@@ -223,28 +223,32 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     }
     // Cost per useful byte on each side: 128-byte lines touched per line's worth of useful
     // data, plus a fixed per-run overhead.  The constants were fitted on MI355X to the
-    // measured times of every candidate of 115 benchmark cases: output runs keep paying off
+    // measured times of every candidate of ~160 benchmark cases: output runs keep paying off
     // up to about 2 KiB (overhead worth 64 bytes, misalignment weighted 4x: a partially
     // written line costs far more than a partially read one, cf. Eq. (13)), input runs are
-    // flat from 128 bytes on (overhead worth 16 bytes).
-    double cost_in = (rin + 16.0 + (128.0 - gin)) / rin;
+    // flat from 128 bytes on (overhead worth 32 bytes).
+    double cost_in = (rin + 32.0 + (128.0 - gin)) / rin;
     if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
     const double cost_out = (rout + 64.0 + 4.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
-    // Tile size: throughput is flat between 8 and 16 KiB tiles (two or three workgroups per
-    // compute unit then keep 16-24 KiB of reads in flight), falls slowly below, and falls
-    // above as fewer workgroups fit and LDS padding runs out of room.
+    // Tile size.  Throughput is flat up to 16 KiB tiles and falls above (fewer workgroups
+    // fit, LDS padding runs out of room); tiles of less than two slots per thread cannot
+    // keep enough bytes in flight.
     const double bytes = (double)vol * elem;
-    if (bytes < 8192.0) cost *= 1.0 + 0.08 * std::log2(8192.0 / bytes);
-    if (bytes > 16384.0) cost *= 1.0 + 0.15 * std::log2(bytes / 16384.0);
-    // Too few tiles cannot fill 256 compute units.
-    if (tiles < 1024) cost *= 1.0 + 0.05 * std::log2(1024.0 / (double)tiles);
+    if (bytes > 16384.0) cost *= 1.0 + 0.10 * std::log2(bytes / 16384.0);
+    if (vol < 2 * TPERM_MAX_THREADS) cost *= 1.4;
+    // Pipeline fill and drain: a persistent workgroup spends about two tile times without
+    // overlap, which matters when it only gets a few tiles (small tensors).
+    const double wg_per_cu = std::max(2.0, std::min(8.0, std::round(20480.0 / bytes)));
+    const double iters = (double)tiles / (256.0 * wg_per_cu);
+    cost *= 1.0 + 2.0 / std::max(iters, 0.25);
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.05;
     // Nontemporal accesses pay off when every run starts and ends on a line boundary; with
     // ragged runs neighbouring tiles share lines and want them kept in L2.
     cd->aligned = (gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
                    std::fmod(rout, 128.0) == 0.0);
+    cd->out_aligned = (gout >= 128.0 && std::fmod(rout, 128.0) == 0.0);
     cd->score = cost;
     return true;
 }
@@ -417,8 +421,29 @@ static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* di
     return cum;
 }
 
-tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
-                               int window_in, int window_out, int threads, int lds_buffers) {
+// Same for an LDS image kept in OUTPUT order: the first `run_dims` output dims of the tile
+// (one output run) are contiguous, the remaining dims ("rows") follow with a padded pitch.
+static uint32_t set_lds_strides_out(TileDesc* d, const int* dim_of_in, const int* dim_of_out,
+                                    int run_dims, uint32_t pad) {
+    uint32_t lstride[TPERM_DESC_MAX_DIMS];
+    uint32_t cum = 1;
+    const uint32_t n = d->n_tile_dims;
+    for (uint32_t j = 0; j < n; ++j) {
+        if ((int)j == run_dims && run_dims > 0) cum += pad;
+        lstride[j] = cum;
+        cum *= d->out_order[j].ext;
+        d->out_order[j].lstride = lstride[j];
+        if ((int)j >= run_dims) d->oa.rows[j - run_dims].lstride = lstride[j];
+    }
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t j = 0; j < n; ++j)
+            if (dim_of_out[j] == dim_of_in[i]) d->in_order[i].lstride = lstride[j];
+    return cum;
+}
+
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts) {
+    const int lds_pad = opts.lds_pad, grid_mode = opts.grid_mode, window_in = opts.window_in,
+              window_out = opts.window_out, threads = opts.threads, lds_buffers = opts.lds_buffers;
     if (threads != 64 && threads != 256) return TPERM_ERR_KERNEL;
     const Canonical& c = plan->c;
     const int r = c.rank;
@@ -586,11 +611,55 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
     if (cum >= ((uint64_t)1 << 31)) return TPERM_ERR_KERNEL;
     d.num_tiles = (uint32_t)cum;  // includes the non-existent combinations of split counters
 
-    const int nreg = pick_nreg(cand.tile_vol, threads);
+    // Line-aligned stores: worth it when output runs do not sit on line boundaries.
+    int orun_dims = 0;
+    for (uint32_t j = 0; j < n; ++j) {
+        if (dim_of_out[j] != c.perm[j]) break;
+        ++orun_dims;
+        if (cand.t[dim_of_out[j]] < c.dims[dim_of_out[j]]) break;
+    }
+    bool align_out = false;
+    std::memset(&d.oa, 0, sizeof(d.oa));
+    d.oa.run_split = d.oa.other_split = 2;
+    // Measured on MI355X this mode gains 1-3 % when output runs are long and loses up to
+    // 20 % when the padded rows push the slot count up, so it is only used on request.
+    if (cand.use_lds && orun_dims > 0 && opts.align_out == 2 && threads == 256) {
+        OutAlign& oa = d.oa;
+        oa.line_elems = 128u / (uint32_t)elem;
+        uint32_t run_len = 1;
+        for (int j = 0; j < orun_dims; ++j) run_len *= d.out_order[j].ext;
+        oa.run_len = run_len;
+        oa.slots_per_row = (run_len + 2 * oa.line_elems - 2) / oa.line_elems * oa.line_elems;
+        oa.slots_div = make_fastdiv(oa.slots_per_row);
+        const int z_last = dim_of_out[orun_dims - 1];
+        if (cand.t[z_last] < c.dims[z_last]) {
+            oa.run_split = z_last == split_dim[0] ? 0u : 1u;
+            oa.run_prefix = run_len / (uint32_t)cand.t[z_last];
+        }
+        for (int sidx = 0; sidx < 2; ++sidx)
+            if (split_dim[sidx] >= 0 && (uint32_t)sidx != oa.run_split) oa.other_split = (uint32_t)sidx;
+        uint32_t rows = 1;
+        oa.n_row_dims = n - (uint32_t)orun_dims;
+        for (uint32_t j = (uint32_t)orun_dims; j < n; ++j) {
+            TileDim td = d.out_order[j];
+            td.sel = (oa.other_split < 2u && dim_of_out[j] == split_dim[oa.other_split]) ? 1u : 0u;
+            oa.rows[j - orun_dims] = td;
+            rows *= td.ext;
+        }
+        oa.total_slots = rows * oa.slots_per_row;
+        if ((int64_t)oa.total_slots <= (int64_t)kMaxNreg * threads &&
+            pick_nreg(std::max<int64_t>(cand.tile_vol, oa.total_slots), threads) > 0) {
+            oa.enabled = 1;
+            align_out = true;
+        }
+    }
+    const int nreg = pick_nreg(align_out ? std::max<int64_t>(cand.tile_vol, d.oa.total_slots)
+                                         : cand.tile_vol, threads);
     if (nreg < 0) return TPERM_ERR_KERNEL;
 
-    // LDS image: tile in input order, rows of the contiguous input run separated by a
-    // padded pitch chosen to minimise bank conflicts of the transposed read
+    // LDS image.  Default: tile in input order, rows of the contiguous input run separated
+    // by a padded pitch.  With line-aligned stores: output order, rows = output runs.  The
+    // pad is chosen to minimise the bank conflicts of the strided side.
     int run_dims = 0;
     for (uint32_t i = 0; i < n; ++i) {
         // dims of the run are the leading canonical dims 0,1,..: tile dim i belongs to
@@ -599,21 +668,26 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         ++run_dims;
         if (cand.t[i] < c.dims[i]) break;
     }
+    auto lay = [&](uint32_t p) {
+        return align_out ? set_lds_strides_out(&d, dim_of_in, dim_of_out, orun_dims, p)
+                         : set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, p);
+    };
+    const int layout_run_dims = align_out ? orun_dims : run_dims;
     int pad = 0;
     uint32_t lds_elems = 0;
     if (cand.use_lds) {
         if (lds_pad >= 0) {
             pad = lds_pad;
-            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)pad);
-        } else if (run_dims >= (int)n) {
+            lds_elems = lay((uint32_t)pad);
+        } else if (layout_run_dims >= (int)n) {
             pad = 0;
-            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, 0);
+            lds_elems = lay(0);
         } else {
             double best = 1e300;
             int best_pad = 0;
             const int max_pad = elem == 8 ? 16 : 32;
             for (int p = 0; p <= max_pad; ++p) {
-                const uint32_t le = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)p);
+                const uint32_t le = lay((uint32_t)p);
                 if ((int64_t)le * elem > kMaxLdsBytes) break;
                 const double cost = lds_conflict_cost(d, elem, nreg, threads);
                 if (cost < best - 1e-9) {
@@ -622,10 +696,10 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
                 }
             }
             pad = best_pad;
-            lds_elems = set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, (uint32_t)pad);
+            lds_elems = lay((uint32_t)pad);
         }
         if ((int64_t)lds_elems * elem > kMaxLdsBytes) return TPERM_ERR_KERNEL;
-        if (lds_elems > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
+        if (lds_elems + 64u > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
     }
     d.lds_elems = lds_elems;
     d.lds_buffers = (cand.use_lds && lds_buffers == 2 && (int64_t)lds_elems * elem * 2 <= kMaxLdsBytes) ? 2u : 1u;
@@ -649,6 +723,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, i
         plan->cache_policy = cand.aligned ? 2 : 1;
     }
     plan->lds_pad = pad;
+    plan->align_out = align_out;
     plan->lds_bytes = (int)((int64_t)lds_elems * elem);
     plan->grid_mode = grid_mode;
     return TPERM_OK;
@@ -742,11 +817,15 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
         }
     }
     if (!have) return fail(TPERM_ERR_KERNEL);
-    st = build_tile_plan(p, chosen, o.lds_pad, o.grid_mode,
-                         o.window_in > 0 ? o.window_in : kDefaultWindow,
-                         o.window_out > 0 ? o.window_out : kDefaultWindow,
-                         o.threads > 0 ? o.threads : kDefaultThreads,
-                         o.lds_buffers > 0 ? o.lds_buffers : kDefaultLdsBuffers);
+    TileBuildOpts bo;
+    bo.lds_pad = o.lds_pad;
+    bo.grid_mode = o.grid_mode;
+    if (o.window_in > 0) bo.window_in = o.window_in;
+    if (o.window_out > 0) bo.window_out = o.window_out;
+    if (o.threads > 0) bo.threads = o.threads;
+    if (o.lds_buffers > 0) bo.lds_buffers = o.lds_buffers;
+    bo.align_out = o.align_out;
+    st = build_tile_plan(p, chosen, bo);
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy == 1 || o.cache_policy == 2) p->cache_policy = o.cache_policy;
@@ -771,8 +850,7 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
     canonicalise(rank, dims, perm, &p->c);
     std::memset(&p->tile, 0, sizeof(p->tile));
     build_naive_desc(p);
-    st = build_tile_plan(p, cand, -1, 0, kDefaultWindow, kDefaultWindow, kDefaultThreads,
-                         kDefaultLdsBuffers);
+    st = build_tile_plan(p, cand, TileBuildOpts());
     if (st != TPERM_OK) {
         delete p;
         return st;
@@ -831,6 +909,36 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
                     if (lds[s.loff] != -1) return TPERM_ERR_INTERNAL;
                     lds[s.loff] = (int64_t)gi;
                 }
+                if (d.oa.enabled) {
+                    // line-aligned stores: the phase the kernel derives from the output
+                    // pointer is taken as 0 here (any phase gives the same element map)
+                    const OutAlign& oa = d.oa;
+                    const uint32_t rems[2] = {rem_a, rem_b};
+                    const bool exists = rem_a != 0u && rem_b != 0u;
+                    const uint32_t lout_rem = !exists ? 0u
+                                              : (oa.run_split < 2u ? rems[oa.run_split] * oa.run_prefix
+                                                                   : oa.run_len);
+                    const uint32_t rem_other = oa.other_split < 2u ? rems[oa.other_split] : TPERM_NO_REM;
+                    for (uint32_t phase_try = 0; phase_try < 2; ++phase_try) {
+                        const uint32_t phi = (uint32_t)((maj_out + (phase_try ? 5u : 0u)) & (oa.line_elems - 1u));
+                        for (uint32_t k = 0; k < oa.total_slots; ++k) {
+                            const OutSlot o = out_slot(oa, k);
+                            const uint32_t q = (phi + o.rho) & (oa.line_elems - 1u);
+                            const uint32_t x = o.s - q;
+                            if (!(x < lout_rem && o.xo < rem_other)) continue;
+                            const uint64_t go = maj_out + o.goff - q;
+                            const uint32_t li = o.lpos - q;
+                            if (go >= (uint64_t)vol || li >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                            if (lds[li] == -1) return TPERM_ERR_INTERNAL;
+                            if (phase_try == 0) {
+                                if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                                out_to_in[go] = lds[li];
+                            } else if (out_to_in[go] != lds[li]) {
+                                return TPERM_ERR_INTERNAL;  // a different phase must not change the map
+                            }
+                        }
+                    }
+                } else
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {
                     const Slot s = tile_slot(d.out_order, d.n_tile_dims, k);
                     if (!(s.xa < rem_a && s.xb < rem_b)) continue;

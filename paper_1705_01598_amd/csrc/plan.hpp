@@ -40,6 +40,7 @@ struct Candidate {
     int64_t t[TPERM_MAX_RANK] = {0};
     int64_t tile_vol = 0, run_in = 0, run_out = 0, num_tiles = 0;
     bool aligned = false;      // every run starts and ends on a 128-byte line boundary
+    bool out_aligned = false;  // output runs start and end on line boundaries
     double utilisation = 1.0;  // useful fraction of the slots of all tiles (ragged edges)
     double score = 0.0;        // relative cost estimate, lower is better
 };
@@ -57,6 +58,7 @@ struct Plan {
     int threads = TPERM_MAX_THREADS;  // workgroup size: 256 (four wavefronts) or 64 (one)
     int lds_pad = 0;
     int lds_bytes = 0;
+    bool align_out = false;  // line-aligned store mode in use
     int grid_mode = 0;
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
     int cache_policy = 1;    // 1 = cached, 2 = nontemporal global loads and stores
@@ -78,8 +80,15 @@ bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
                     int64_t tile_out, bool use_lds, Candidate* out);
 
 // Fill plan->tile (and nreg, lds size, padding) from a candidate.
-tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, int lds_pad, int grid_mode,
-                               int window_in, int window_out, int threads, int lds_buffers);
+struct TileBuildOpts {
+    int lds_pad = -1;       // -1: search
+    int grid_mode = 0;
+    int window_in = kDefaultWindow, window_out = kDefaultWindow;
+    int threads = kDefaultThreads;
+    int lds_buffers = kDefaultLdsBuffers;
+    int align_out = 0;      // 0: selector decides, 1: off, 2: on where possible
+};
+tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts);
 void build_naive_desc(Plan* plan);
 
 // Plan creation proper.

@@ -61,6 +61,54 @@ struct SplitPair {
     uint32_t lane_lo, lane_hi, width, count;
 };
 
+// Line-aligned stores.  When output runs do not start on 128-byte lines, the write side can
+// enumerate its slots as (output row, position in a padded row) and shift every row by its
+// own phase so that lane l always stores to an address congruent to l modulo one line: each
+// group of 16 lanes (fp64; 32 for fp32) then writes exactly one line.  The LDS image is kept
+// in OUTPUT order in this mode, so a row's elements are consecutive in LDS as well.
+struct OutAlign {
+    uint32_t enabled;
+    uint32_t line_elems;     // elements per 128-byte line
+    uint32_t run_len;        // elements of one output run inside a full tile
+    uint32_t slots_per_row;  // run_len + line_elems - 1, rounded up to whole lines
+    FastDiv slots_div;
+    uint32_t n_row_dims;
+    uint32_t total_slots;    // rows * slots_per_row
+    uint32_t run_split;      // 0 / 1: split dim A / B is the last dim of the run; 2: none
+    uint32_t run_prefix;     // run elements per unit of that split dim's coordinate
+    uint32_t other_split;    // 0 / 1: split dim that is a row dim; 2: none
+    TileDim rows[TPERM_DESC_MAX_DIMS];  // row dims, output order (gstride = output stride)
+};
+
+// One write-side slot in line-aligned mode.
+struct OutSlot {
+    uint32_t goff;   // output element offset of (row start + s), relative to the major offset
+    uint32_t lpos;   // LDS index of (row start + s)
+    uint32_t s;      // position in the padded row
+    uint32_t rho;    // (row start offset) mod line_elems
+    uint32_t xo;     // coordinate along the split dim that is a row dim (0 if none)
+};
+
+TPERM_HD OutSlot out_slot(const OutAlign& a, uint32_t k) {
+    OutSlot o;
+    const uint32_t r = fdiv(k, a.slots_div);
+    o.s = k - r * a.slots_per_row;
+    uint32_t rem = r, g = 0, l = 0;
+    o.xo = 0;
+    for (uint32_t i = 0; i < a.n_row_dims; ++i) {
+        const uint32_t q = fdiv(rem, a.rows[i].div);
+        const uint32_t x = rem - q * a.rows[i].ext;
+        rem = q;
+        g += x * a.rows[i].gstride;
+        l += x * a.rows[i].lstride;
+        if (a.rows[i].sel != 0u) o.xo = x;
+    }
+    o.rho = g & (a.line_elems - 1u);
+    o.goff = g + o.s;
+    o.lpos = l + o.s;
+    return o;
+}
+
 // Descriptor of the generic tile kernel (Tiled, Packed, PackedSplit and the LDS-free
 // row-copy all reduce to it).
 struct TileDesc {
@@ -83,6 +131,7 @@ struct TileDesc {
     TileDim in_order[TPERM_DESC_MAX_DIMS];   // tile dims, input order (k enumerates these)
     TileDim out_order[TPERM_DESC_MAX_DIMS];  // the same dims, output order
     MajorDims major;
+    OutAlign oa;
 };
 
 // Per-thread, per-slot minor position for the read side (Eq. (4) and the LDS store slot).

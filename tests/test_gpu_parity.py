@@ -106,9 +106,25 @@ TILES = [
 def test_explicit_tiles_match_oracle(dims, perm, m, tin, k, tout, grid_mode, elem):
     case = wl.make_case(0, 3, dims, perm, elem)
     plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin,
-                                  k=k, tile_out=tout, grid_mode=grid_mode)
+                                  k=k, tile_out=tout, grid_mode=grid_mode, align_out=1 + grid_mode % 2)
     _check(case, plan)
     plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("align_out", [1, 2])
+@pytest.mark.parametrize("offset", [0, 1, 5])
+@pytest.mark.parametrize("dims,perm", SHAPES)
+def test_line_aligned_stores_match_oracle(dims, perm, offset, align_out, elem):
+    """Both store modes, with output base pointers at several phases inside a cache line."""
+    case = wl.make_case(0, 12, dims, perm, elem)
+    try:
+        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, align_out=align_out,
+                                      cache_policy=1 + offset % 2)
+    except B.TpermError as e:
+        assert e.status == B.ERR_KERNEL
+        pytest.skip("no LDS-staged plan for this shape")
+    _check(case, plan, offset=offset)
 
 
 @pytest.mark.parametrize("elem", [8, 4])

@@ -161,10 +161,11 @@ def test_index_maps_of_every_gpu_test_plan():
         for dims, perm in G.SHAPES:
             _map_ok(dims, perm, elem)
             for kc in (B.KERNEL_NAIVE, B.KERNEL_TILED, B.KERNEL_PACKED, B.KERNEL_ROWCOPY):
-                try:
-                    _map_ok(dims, perm, elem, kernel_class=kc)
-                except B.TpermError as e:
-                    assert e.status == B.ERR_KERNEL
+                for ao in (1, 2):
+                    try:
+                        _map_ok(dims, perm, elem, kernel_class=kc, align_out=ao)
+                    except B.TpermError as e:
+                        assert e.status == B.ERR_KERNEL
         for dims, perm, m, tin, k, tout in G.TILES:
             for gm in (0, 1, 2, 5):
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
@@ -203,7 +204,7 @@ def test_index_maps_random_shapes_and_tiles():
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
                         tile_out=tout, grid_mode=int(rng.integers(0, 8)),
                         window_in=int(rng.choice([0, 1, 4, 16])), window_out=int(rng.choice([0, 1, 3, 16])),
-                        threads=int(rng.choice([64, 256])))
+                        threads=int(rng.choice([64, 256])), align_out=int(rng.integers(0, 3)))
             except B.TpermError as e:
                 assert e.status == B.ERR_KERNEL     # tile too large for LDS / registers
         done += 1
