@@ -37,7 +37,12 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload family 1..5 (default 2)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload family 1..5 (default 2); 6 = the paper's printed rank-8/rank-12 "
+                         "shapes (Section 3.2), 7 = its square fp32 matrices of side 13952..13968")
+    ap.add_argument("--accumulate", action="store_true",
+                    help="time out = out + transpose(in) (Section 3.3); bytes = 3 * vol * E")
+    ap.add_argument("--set2-perms", type=int, default=30, help="random permutations per shape for --config 6")
     ap.add_argument("--stride", type=int, default=1, help="take every n-th case of the family")
     ap.add_argument("--plan", choices=["heuristic", "measured"], default="heuristic")
     ap.add_argument("--also-measured", action="store_true",
@@ -98,7 +103,14 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    cases = wl.all_configs()[args.config][:: args.stride]
+    if args.config == 6:
+        cases = wl.set2(args.set2_perms)[:: args.stride]
+    elif args.config == 7:
+        cases = wl.square_sweep()[:: args.stride]
+    else:
+        cases = wl.all_configs()[args.config][:: args.stride]
+    mem_ops = 3 if args.accumulate else 2
+    run = B.tperm_execute_accumulate if args.accumulate else B.tperm_execute
     elem = cases[0].elem_size
     max_vol = max(c.volume for c in cases)
     stream = torch.cuda.current_stream().cuda_stream
@@ -131,7 +143,7 @@ def main():
             a, b = pairs[(step_idx * len(plans) + i) % n_pairs]
             if events is not None:
                 events[i].record()
-            B.tperm_execute(plan, a.data_ptr(), b.data_ptr(), stream)
+            run(plan, a.data_ptr(), b.data_ptr(), stream)
         if events is not None:
             events[len(plans)].record()
 
@@ -152,13 +164,14 @@ def main():
     dur_ms = np.array([[ev[s][i].elapsed_time(ev[s][i + 1]) for i in range(len(plans))]
                        for s in range(args.steps)])
     case_ms = np.median(dur_ms, axis=0)
-    case_gbs = np.array([c.bytes_moved for c in cases]) / case_ms / 1e6
-    step_bytes = sum(c.bytes_moved for c in cases)
+    case_bytes = np.array([c.bytes_moved // 2 * mem_ops for c in cases], dtype=np.float64)
+    case_gbs = case_bytes / case_ms / 1e6
+    step_bytes = int(case_bytes.sum())
     value = step_bytes * args.steps / elapsed / 1e9
 
     tile_mask = np.array([i.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
                           for i in infos])
-    tile_bytes = np.array([c.bytes_moved for c in cases], dtype=np.float64)[tile_mask]
+    tile_bytes = case_bytes[tile_mask]
     tile_ms = dur_ms[:, tile_mask]
     achieved = float(tile_bytes.mean() / tile_ms.mean() / 1e6) if tile_mask.any() else 0.0
     traffic = TRAFFIC_BYTES_PER_LAUNCH.get(f"c{args.config}")
@@ -192,7 +205,9 @@ def main():
 
     workload_names = {1: "rank-2 fp64 2048x2048 transpose", 2: "rank-4 fp64 96^4, all 23 non-identity permutations",
                       3: "rank-6 fp64 ~2^26 elements, 20 seeded cases", 4: "rank sweep 2..12 fp64 ~2^26 elements, 330 seeded cases",
-                      5: "fp32 contraction-feeding transposes 8^8 and 16^6, 80 seeded permutations"}
+                      5: "fp32 contraction-feeding transposes 8^8 and 16^6, 80 seeded permutations",
+                      6: "the paper's rank-8 (205M el) and rank-12 (328M el) fp64 shapes, seeded permutations + trivial + reverse",
+                      7: "square fp32 matrices, side 13952..13968"}
     result = {
         "metric": "transpose GB/s (read+write bytes / time) and % of MI355X HBM peak, median/rank",
         "value": round(value, 1),
@@ -207,7 +222,8 @@ def main():
         "dtype": "f64" if elem == 8 else "f32",
         "data": "synthetic",
         "config": {"workload": workload_names[args.config], "cases": len(cases),
-                   "bytes_per_step": step_bytes, "plan": args.plan, "buffer_pairs": n_pairs},
+                   "bytes_per_step": step_bytes, "plan": args.plan, "buffer_pairs": n_pairs,
+                   "mode": "accumulate (3 memory ops per element)" if args.accumulate else "transpose"},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "case_median_GBs": round(float(np.median(case_gbs)), 1),
         "case_min_GBs": round(float(case_gbs.min()), 1),

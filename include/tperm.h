@@ -146,6 +146,14 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t *plan, int rank, const in
  * overlap in.  A plan is immutable: concurrent executes on several streams are allowed. */
 tperm_status_t tperm_execute(tperm_plan_t plan, const void *in, void *out, void *hip_stream);
 
+/* Accumulating variant (the mode the paper uses for its third benchmark set, Section 3.3:
+ * read input, read output, add, write output): out = out + transpose(in), where the
+ * elements are IEEE binary32 (elem_size 4) or binary64 (elem_size 8) numbers and each output
+ * element receives exactly one addition.  Same argument rules as tperm_execute; three
+ * memory operations per element instead of two. */
+tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void *in, void *out,
+                                        void *hip_stream);
+
 /* Fill *info from the plan (host only). */
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);
 

@@ -17,6 +17,7 @@ Four independent forms of the same definition live here:
 ``transpose_numpy``      the library special case: ``numpy.transpose`` on a
                          Fortran-ordered view
 ``transpose_bruteforce`` pure-Python nested loops over every multi-index
+``transpose_accumulate`` C, out + transposed in (the paper's accumulate mode)
 
 All forms move raw bytes (arrays are viewed as unsigned integers of the element
 size), so results are compared bit for bit.
@@ -59,6 +60,9 @@ def _load():
         lib.tto_transpose_scatter.argtypes = [ctypes.c_int, i64p, i32p, ctypes.c_size_t,
                                               ctypes.c_void_p, ctypes.c_void_p]
         lib.tto_transpose_scatter.restype = ctypes.c_int
+        lib.tto_transpose_accumulate.argtypes = [ctypes.c_int, i64p, i32p, ctypes.c_size_t,
+                                                 ctypes.c_void_p, ctypes.c_void_p]
+        lib.tto_transpose_accumulate.restype = ctypes.c_int
         lib.tto_input_position.argtypes = [ctypes.c_int, i64p, i32p, ctypes.c_int64]
         lib.tto_input_position.restype = ctypes.c_int64
         lib.tto_sample.argtypes = [ctypes.c_int, i64p, i32p, ctypes.c_size_t, ctypes.c_void_p,
@@ -126,6 +130,25 @@ def transpose_scatter(a: np.ndarray, dims: Sequence[int], perm: Sequence[int]) -
         raise ValueError("buffer size does not match dims")
     out = np.empty_like(a)
     rc = lib.tto_transpose_scatter(rank, cd, cp, a.dtype.itemsize, a.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return out
+
+
+def transpose_accumulate(a: np.ndarray, b: np.ndarray, dims: Sequence[int],
+                         perm: Sequence[int]) -> np.ndarray:
+    """Accumulating form in C: returns b + transpose(a) with one IEEE addition per element.
+    ``a`` and ``b`` are float32 or float64 flat buffers of the same dtype; ``b`` is not
+    modified."""
+    lib = _load()
+    a = np.ascontiguousarray(a).reshape(-1)
+    out = np.array(b, copy=True).reshape(-1)
+    if a.dtype != out.dtype or a.dtype not in (np.float32, np.float64):
+        raise ValueError("accumulate needs float32 or float64 buffers of one dtype")
+    rank, cd, cp = _marshal(dims, perm)
+    if a.size != out.size or a.size != int(np.prod([int(d) for d in dims], dtype=object)):
+        raise ValueError("buffer size does not match dims")
+    rc = lib.tto_transpose_accumulate(rank, cd, cp, a.dtype.itemsize, a.ctypes.data, out.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle rejected the arguments (code {rc})")
     return out

@@ -123,6 +123,38 @@ int tto_transpose_gather(int rank, const int64_t *dims, const int *perm, size_t 
 }
 
 /*
+ * Accumulating form (the mode of the paper's third benchmark set, Section 3.3: read input,
+ * read output, accumulate, write output): out[o] = out[o] + in[p(o)], one IEEE addition
+ * per output element, in binary32 for 4-byte and binary64 for 8-byte elements.
+ */
+int tto_transpose_accumulate(int rank, const int64_t *dims, const int *perm, size_t elem,
+                             const void *in, void *out)
+{
+    int64_t sI[TTO_MAX_RANK], sO[TTO_MAX_RANK];
+    int rc = tto_check(rank, dims, perm, elem);
+    if (rc != TTO_OK) return rc;
+    if (elem != 4 && elem != 8) return TTO_BAD_ELEM;
+    tto_strides(rank, dims, perm, sI, sO);
+    const int64_t vol = tto_volume(rank, dims);
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < vol; ++o) {
+        int64_t p = 0;
+        for (int j = 0; j < rank; ++j) {
+            int64_t x = (o / sO[j]) % dims[perm[j]];
+            p += x * sI[perm[j]];
+        }
+        if (elem == 8) {
+            volatile double s = ((double *)out)[o] + ((const double *)in)[p];
+            ((double *)out)[o] = s;
+        } else {
+            volatile float s = ((float *)out)[o] + ((const float *)in)[p];
+            ((float *)out)[o] = s;
+        }
+    }
+    return TTO_OK;
+}
+
+/*
  * Scatter form, Eq. (1): walk the input linearly; recover the input
  * coordinate y_z of every dimension z from the input scalar position and
  * multiply it by the cumulative volume of that same dimension z in the output

@@ -25,7 +25,7 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
 
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
            "tperm_plan_candidate_count", "tperm_plan_create_candidate",
-           "tperm_execute", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
+           "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes"]
 
 
@@ -81,6 +81,7 @@ def lib() -> ctypes.CDLL:
         L.tperm_plan_create_candidate.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
                                                   ctypes.c_size_t, ctypes.c_int]
         L.tperm_execute.argtypes = [vp, vp, vp, vp]
+        L.tperm_execute_accumulate.argtypes = [vp, vp, vp, vp]
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
         L.tperm_plan_destroy.argtypes = [vp]
@@ -198,6 +199,13 @@ def tperm_execute(plan: Plan, in_ptr: int, out_ptr: int, stream: int = 0) -> Non
                              ctypes.c_void_p(stream))
     if st != OK:
         raise TpermError(st, "tperm_execute")
+
+
+def tperm_execute_accumulate(plan: Plan, in_ptr: int, out_ptr: int, stream: int = 0) -> None:
+    st = lib().tperm_execute_accumulate(plan.handle, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                        ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_execute_accumulate")
 
 
 def tperm_plan_describe(plan: Plan) -> PlanInfo:

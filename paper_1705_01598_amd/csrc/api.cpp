@@ -94,7 +94,8 @@ tperm_status_t tperm_plan_destroy(tperm_plan_t plan) {
     return TPERM_OK;
 }
 
-tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void* hip_stream) {
+static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out, void* hip_stream,
+                                   bool accumulate) {
     if (plan == nullptr || in == nullptr || out == nullptr) return TPERM_ERR_NULL;
     if (in == out) return TPERM_ERR_ALIAS;
     const Plan& p = *plan->p;
@@ -102,6 +103,10 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void*
     if ((a % (uintptr_t)p.elem) != 0 || (b % (uintptr_t)p.elem) != 0) return TPERM_ERR_ALIGN;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;
+    // accumulating kernels exist for the default workgroup size and store mode only
+    if (accumulate && (p.align_out || (p.threads != 256 && p.kclass != TPERM_KERNEL_COPY &&
+                                       p.kclass != TPERM_KERNEL_NAIVE)))
+        return TPERM_ERR_KERNEL;
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t err = hipSuccess;
     switch (p.kclass) {
@@ -112,11 +117,12 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void*
                 if (st != TPERM_OK) return st;
                 plan->num_cu.store(num_cu, std::memory_order_release);
             }
-            err = tperm::launch_copy(in, out, nbytes, p.elem, num_cu, stream);
+            err = accumulate ? tperm::launch_accumulate_copy(in, out, nbytes, p.elem, num_cu, stream)
+                             : tperm::launch_copy(in, out, nbytes, p.elem, num_cu, stream);
             break;
         }
         case TPERM_KERNEL_NAIVE:
-            err = tperm::launch_naive(p, in, out, stream);
+            err = tperm::launch_naive(p, in, out, stream, accumulate);
             break;
         case TPERM_KERNEL_ROWCOPY:
         case TPERM_KERNEL_TILED:
@@ -124,7 +130,7 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void*
             int grid = 0;
             tperm_status_t st = resolve_grid(plan, &grid);
             if (st != TPERM_OK) return st;
-            err = tperm::launch_tile(p, in, out, stream, grid);
+            err = tperm::launch_tile(p, in, out, stream, grid, accumulate);
             break;
         }
         default:
@@ -135,6 +141,15 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void*
         return TPERM_ERR_HIP;
     }
     return TPERM_OK;
+}
+
+tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void* hip_stream) {
+    return execute_impl(plan, in, out, hip_stream, false);
+}
+
+tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void* in, void* out,
+                                        void* hip_stream) {
+    return execute_impl(plan, in, out, hip_stream, true);
 }
 
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {

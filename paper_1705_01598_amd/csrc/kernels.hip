@@ -1,15 +1,5 @@
-// HIP kernels for gfx950 (MI355X): the tile kernel that every staged transpose class runs
-// through, the plain copy and the naive gather.
-//
-// Tile kernel, per workgroup (256 threads = 4 wavefronts of 64):
-//   prologue  every thread evaluates, once, the minor positions (Eqs. (4)-(6)) of the
-//             NREG tile slots it owns and keeps them in registers;
-//   per tile  the major offsets (Eqs. (2),(3)) are evaluated lane-parallel: lane j of a
-//             16-lane DPP row holds term j, a row_shr scan adds them, v_readlane moves the
-//             sum into scalar registers (the wave64 form of the paper's Algorithm 1);
-//             global -> registers -> LDS (input order), barrier, LDS (output order) ->
-//             registers -> global.  The loads of the next tile are issued before the
-//             stores of the current one so reads stay in flight all the time.
+// Plain copy / accumulate and naive gather kernels, and the launch functions.  The tile
+// kernel lives in tile_kernel.hpp and is instantiated in tile_inst_*.hip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -18,250 +8,11 @@
 
 namespace tperm {
 
-// ---------------------------------------------------------------------------------------
-// wave-level helpers
-// ---------------------------------------------------------------------------------------
+const void* tile_kernel_u64_256(int nreg, bool use_lds, bool nt, bool align, bool acc);
+const void* tile_kernel_u32_256(int nreg, bool use_lds, bool nt, bool align, bool acc);
+const void* tile_kernel_u64_64(int nreg, bool use_lds, bool nt, bool align, bool acc);
+const void* tile_kernel_u32_64(int nreg, bool use_lds, bool nt, bool align, bool acc);
 
-// Inclusive add-scan inside each row of 16 lanes with DPP row shifts; lane 15 of a row
-// ends up with the sum of the row.  Lanes shifted in from outside the row read 0.
-__device__ __forceinline__ uint32_t row_scan_add(uint32_t v) {
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);  // row_shr:1
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);  // row_shr:2
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);  // row_shr:4
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);  // row_shr:8
-    return v;
-}
-
-__device__ __forceinline__ uint32_t read_lane(uint32_t v, uint32_t lane) {
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
-}
-
-struct MajorPos {
-    uint32_t in, out;        // element offsets of the tile (wave-uniform)
-    uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
-};
-
-// One lane's term of the major sums, kept in registers for the whole kernel.
-struct MajorLane {
-    FastDiv cum, ext_div;
-    uint32_t ext, stride_in, stride_out;
-};
-
-__device__ __forceinline__ MajorPos major_position(const TileDesc& d, const MajorLane& ml,
-                                                   uint32_t b) {
-    const uint32_t q = fdiv(b, ml.cum);
-    const uint32_t c = q - fdiv(q, ml.ext_div) * ml.ext;
-    const uint32_t sum_in = row_scan_add(c * ml.stride_in);
-    const uint32_t sum_out = row_scan_add(c * ml.stride_out);
-    MajorPos p;
-    p.in = read_lane(sum_in, 15);
-    p.out = read_lane(sum_out, 15);
-    tile_remaining(d, [&](uint32_t lane) { return read_lane(c, lane); }, &p.rem_a, &p.rem_b);
-    return p;
-}
-
-__device__ __forceinline__ bool slot_valid(uint32_t packed, uint32_t rem_a, uint32_t rem_b) {
-    return ((packed & 0xFFFFu) < rem_a) && ((packed >> 16) < rem_b);
-}
-
-// ---------------------------------------------------------------------------------------
-// buffer addressing
-// ---------------------------------------------------------------------------------------
-// Global accesses of the tile kernel go through buffer instructions: a 128-bit resource in
-// scalar registers describes the whole tensor, the tile's major offset rides in the scalar
-// offset operand and each lane supplies only its 32-bit minor byte offset.  One VGPR per
-// address instead of two, no 64-bit vector adds, and the hardware drops any access past
-// the end of the tensor.  NT selects the nontemporal cache policy (every byte is touched
-// exactly once, so nothing is worth keeping in the caches).
-
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <typename T, bool NT> struct Elem;
-template <bool NT> struct Elem<uint32_t, NT> {
-    typedef uint32_t reg;
-    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, NT ? 2 : 0);
-    }
-    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
-                                                 uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, NT ? 2 : 0);
-    }
-};
-template <bool NT> struct Elem<uint64_t, NT> {
-    typedef u32x2 reg;
-    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, NT ? 2 : 0);
-    }
-    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
-                                                 uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, NT ? 2 : 0);
-    }
-};
-
-// Raw (untyped, unstrided) buffer resource over `bytes` bytes starting at p.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
-// ---------------------------------------------------------------------------------------
-// the tile kernel
-// ---------------------------------------------------------------------------------------
-
-template <typename T, int NREG, int THREADS, bool USE_LDS, bool NT, bool ALIGN>
-__global__ void __launch_bounds__(THREADS)
-tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
-    typedef Elem<T, NT> io;
-    typedef typename io::reg reg_t;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    reg_t* lds = reinterpret_cast<reg_t*>(smem_raw);
-    const uint32_t tid = threadIdx.x;
-    const __amdgpu_buffer_rsrc_t rsrc_in = make_rsrc(in, nbytes);
-    const __amdgpu_buffer_rsrc_t rsrc_out = make_rsrc(out, nbytes);
-
-    // minor positions of this thread's slots; global offsets are kept in BYTES
-    uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
-    uint32_t lds_pos[NREG];  // low half: slot written on the read side; high half: slot
-                             // read on the write side
-    uint32_t wr_aux[NREG];   // line-aligned stores: position in the padded row | row phase << 16
-#pragma unroll
-    for (int j = 0; j < NREG; ++j) {
-        const uint32_t k = tid + (uint32_t)j * THREADS;
-        rd_off[j] = 0;
-        wr_off[j] = 0;
-        lds_pos[j] = 0;
-        rd_mask[j] = 0xFFFFFFFFu;  // coordinates no remaining extent exceeds: slot unused
-        wr_mask[j] = 0xFFFFFFFFu;
-        wr_aux[j] = 0xFFFFu;       // a row position beyond every run: slot unused
-        if (ALIGN) {
-            // write side: slot = (output row, position in the padded row)
-            if (k < d.oa.total_slots) {
-                const OutSlot o = out_slot(d.oa, k);
-                wr_off[j] = o.goff * (uint32_t)sizeof(T);
-                wr_mask[j] = o.xo;
-                wr_aux[j] = o.s | (o.rho << 16);
-                lds_pos[j] = o.lpos << 16;
-            }
-            if (k < d.tile_vol) {
-                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
-                rd_off[j] = si.goff * (uint32_t)sizeof(T);
-                rd_mask[j] = si.xa | (si.xb << 16);
-                lds_pos[j] |= si.loff;
-            }
-        } else if (k < d.tile_vol) {
-            const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
-            wr_off[j] = so.goff * (uint32_t)sizeof(T);
-            wr_mask[j] = so.xa | (so.xb << 16);
-            if (USE_LDS) {
-                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
-                rd_off[j] = si.goff * (uint32_t)sizeof(T);
-                rd_mask[j] = si.xa | (si.xb << 16);
-                lds_pos[j] = si.loff | (so.loff << 16);
-            } else {
-                rd_off[j] = so.ooff * (uint32_t)sizeof(T);
-                rd_mask[j] = wr_mask[j];
-            }
-        }
-    }
-
-    const uint32_t lane16 = tid & 15u;
-    MajorLane ml;
-    ml.cum = d.major.cum[lane16];
-    ml.ext_div = d.major.ext_div[lane16];
-    ml.ext = d.major.ext[lane16];
-    ml.stride_in = d.major.stride_in[lane16];
-    ml.stride_out = d.major.stride_out[lane16];
-
-    const uint32_t grid = gridDim.x, block = blockIdx.x;
-    uint32_t it = 0;
-    uint32_t b = tile_of(d, block, grid, it);
-    reg_t v[NREG];
-    MajorPos pos, nxt;
-    pos.in = pos.out = pos.rem_a = pos.rem_b = 0;
-    nxt = pos;
-    if (b < d.num_tiles) {
-        pos = major_position(d, ml, b);
-        const uint32_t soff = pos.in * (uint32_t)sizeof(T);
-#pragma unroll
-        for (int j = 0; j < NREG; ++j)
-            if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
-                v[j] = io::load(rsrc_in, rd_off[j], soff);
-    }
-    // the position of the tile after this one is worked out while the loads are in flight
-    uint32_t bn = tile_of(d, block, grid, it + 1);
-    if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
-    const bool two_buffers = d.lds_buffers == 2u;
-    // line-aligned stores: phase of the output base pointer within a 128-byte line
-    const uint32_t line_mask = ALIGN ? d.oa.line_elems - 1u : 0u;
-    const uint32_t out_phase =
-        ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
-    while (b < d.num_tiles) {
-        reg_t w[NREG];
-        uint32_t shift[NREG];     // ALIGN: this tile's lane shift of each slot's row
-        uint32_t lout_rem = 0, rem_other = 0, phi = 0;
-        if (ALIGN) {
-            const bool exists = pos.rem_a != 0u && pos.rem_b != 0u;
-            const uint32_t run_rem = d.oa.run_split == 0u ? pos.rem_a : pos.rem_b;
-            lout_rem = !exists ? 0u : (d.oa.run_split < 2u ? run_rem * d.oa.run_prefix : d.oa.run_len);
-            rem_other = d.oa.other_split == 0u ? pos.rem_a
-                                               : (d.oa.other_split == 1u ? pos.rem_b : TPERM_NO_REM);
-            phi = (out_phase + pos.out) & line_mask;
-        }
-        if (USE_LDS) {
-            // with two LDS images the tiles alternate between them and one barrier per
-            // tile is enough: a wave can only overwrite an image two tiles later, after
-            // the barrier of the tile in between
-            reg_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
-#pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) img[lds_pos[j] & 0xFFFFu] = v[j];
-            __syncthreads();
-            if (ALIGN) {
-#pragma unroll
-                for (int j = 0; j < NREG; ++j) {
-                    shift[j] = (phi + (wr_aux[j] >> 16)) & line_mask;
-                    const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                    if (x < lout_rem && wr_mask[j] < rem_other)
-                        w[j] = img[(lds_pos[j] >> 16) - shift[j]];
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < NREG; ++j)
-                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NREG; ++j) w[j] = v[j];
-        }
-        // reads of the next tile go out before the stores of this one
-        if (bn < d.num_tiles) {
-            const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
-#pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b))
-                    v[j] = io::load(rsrc_in, rd_off[j], soff);
-        }
-        const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
-        if (ALIGN) {
-#pragma unroll
-            for (int j = 0; j < NREG; ++j) {
-                const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                if (x < lout_rem && wr_mask[j] < rem_other)
-                    io::store(w[j], rsrc_out, wr_off[j] - shift[j] * (uint32_t)sizeof(T), soff_out);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
-                    io::store(w[j], rsrc_out, wr_off[j], soff_out);
-        }
-        b = bn;
-        pos = nxt;
-        ++it;
-        bn = tile_of(d, block, grid, it + 1);
-        if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
-        if (USE_LDS && !two_buffers) __syncthreads();  // all waves are done reading the image
-    }
-}
 
 // ---------------------------------------------------------------------------------------
 // plain copy and naive gather
@@ -296,81 +47,59 @@ copy_elem_kernel(const T* __restrict__ in, T* __restrict__ out, uint64_t n) {
     for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n; i += stride) out[i] = in[i];
 }
 
-template <typename T>
+// F is the arithmetic type when accumulating (float / double), else an unsigned integer.
+template <typename F, bool ACC>
 __global__ void __launch_bounds__(256)
-naive_kernel(const NaiveDesc d, const T* __restrict__ in, T* __restrict__ out) {
+naive_kernel(const NaiveDesc d, const F* __restrict__ in, F* __restrict__ out) {
     const uint64_t o = (uint64_t)blockIdx.x * 256u + threadIdx.x;
-    if (o < d.volume) out[o] = in[naive_input_offset(d, (uint32_t)o)];
+    if (o < d.volume) {
+        const F v = in[naive_input_offset(d, (uint32_t)o)];
+        out[o] = ACC ? (F)(out[o] + v) : v;
+    }
+}
+
+// out[i] = out[i] + in[i] (identity permutation in accumulate mode), four elements in
+// flight per lane.
+template <typename F>
+__global__ void __launch_bounds__(256)
+accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const F a0 = in[i], a1 = in[i + stride], a2 = in[i + 2 * stride], a3 = in[i + 3 * stride];
+        const F b0 = out[i], b1 = out[i + stride], b2 = out[i + 2 * stride], b3 = out[i + 3 * stride];
+        out[i] = b0 + a0;
+        out[i + stride] = b1 + a1;
+        out[i + 2 * stride] = b2 + a2;
+        out[i + 3 * stride] = b3 + a3;
+    }
+    for (; i < n; i += stride) out[i] = out[i] + in[i];
 }
 
 // ---------------------------------------------------------------------------------------
 // dispatch
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int THREADS, bool USE_LDS, bool NT, bool ALIGN>
-static const void* tile_kernel_ptr(int nreg) {
-    switch (nreg) {
-#define TPERM_CASE(N) \
-    case N:           \
-        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN>);
-        TPERM_CASE(4)
-        TPERM_CASE(8)
-        TPERM_CASE(12)
-        TPERM_CASE(16)
-        TPERM_CASE(24)
-        TPERM_CASE(32)
-        default:
-            break;
-    }
-    if constexpr (THREADS == 256) {
-        switch (nreg) {
-            TPERM_CASE(1)
-            TPERM_CASE(2)
-            TPERM_CASE(3)
-            TPERM_CASE(6)
-            default:
-                break;
-        }
-    }
-#undef TPERM_CASE
-    return nullptr;
-}
-
-template <typename T, int THREADS>
-static const void* tile_kernel_for_threads(const Plan& plan) {
-    const bool nt = plan.cache_policy == 2;
-    if (plan.use_lds) {
-        if constexpr (THREADS == 256) {
-            if (plan.align_out)
-                return nt ? tile_kernel_ptr<T, THREADS, true, true, true>(plan.nreg)
-                          : tile_kernel_ptr<T, THREADS, true, false, true>(plan.nreg);
-        }
-        return nt ? tile_kernel_ptr<T, THREADS, true, true, false>(plan.nreg)
-                  : tile_kernel_ptr<T, THREADS, true, false, false>(plan.nreg);
-    }
-    return nt ? tile_kernel_ptr<T, THREADS, false, true, false>(plan.nreg)
-              : tile_kernel_ptr<T, THREADS, false, false, false>(plan.nreg);
-}
-
-template <typename T>
-static const void* tile_kernel_for_type(const Plan& plan) {
-    return plan.threads == 64 ? tile_kernel_for_threads<T, 64>(plan)
-                              : tile_kernel_for_threads<T, 256>(plan);
-}
-
-static const void* tile_kernel_for(const Plan& plan) {
-    return plan.elem == 8 ? tile_kernel_for_type<uint64_t>(plan) : tile_kernel_for_type<uint32_t>(plan);
+static const void* tile_kernel_for(const Plan& plan, bool acc) {
+    const bool nt = plan.cache_policy == 2 && !acc;
+    const bool align = plan.align_out;
+    if (plan.elem == 8)
+        return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc)
+                                  : tile_kernel_u64_256(plan.nreg, plan.use_lds, nt, align, acc);
+    return plan.threads == 64 ? tile_kernel_u32_64(plan.nreg, plan.use_lds, nt, align, acc)
+                              : tile_kernel_u32_256(plan.nreg, plan.use_lds, nt, align, acc);
 }
 
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {
-    const void* f = tile_kernel_for(plan);
+    const void* f = tile_kernel_for(plan, false);
     if (f == nullptr) return hipErrorInvalidValue;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, f, plan.threads,
                                                         (size_t)plan.lds_bytes * plan.tile.lds_buffers);
 }
 
-hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid) {
-    const void* f = tile_kernel_for(plan);
+hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid,
+                       bool accumulate) {
+    const void* f = tile_kernel_for(plan, accumulate);
     if (f == nullptr || grid < 1) return hipErrorInvalidValue;
     TileDesc d = plan.tile;
     uint32_t nbytes = (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
@@ -379,15 +108,39 @@ hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t 
                            (size_t)plan.lds_bytes * plan.tile.lds_buffers, stream);
 }
 
-hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream) {
+hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream,
+                        bool accumulate) {
     const uint64_t vol = (uint64_t)plan.c.volume;
     const unsigned grid = (unsigned)((vol + 255) / 256);
-    if (plan.elem == 8)
-        hipLaunchKernelGGL(naive_kernel<uint64_t>, dim3(grid), dim3(256), 0, stream, plan.naive,
-                           (const uint64_t*)in, (uint64_t*)out);
+    if (accumulate) {
+        if (plan.elem == 8)
+            hipLaunchKernelGGL((naive_kernel<double, true>), dim3(grid), dim3(256), 0, stream,
+                               plan.naive, (const double*)in, (double*)out);
+        else
+            hipLaunchKernelGGL((naive_kernel<float, true>), dim3(grid), dim3(256), 0, stream,
+                               plan.naive, (const float*)in, (float*)out);
+    } else if (plan.elem == 8) {
+        hipLaunchKernelGGL((naive_kernel<uint64_t, false>), dim3(grid), dim3(256), 0, stream,
+                           plan.naive, (const uint64_t*)in, (uint64_t*)out);
+    } else {
+        hipLaunchKernelGGL((naive_kernel<uint32_t, false>), dim3(grid), dim3(256), 0, stream,
+                           plan.naive, (const uint32_t*)in, (uint32_t*)out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate_copy(const void* in, void* out, size_t nbytes, int elem, int num_cu,
+                                  hipStream_t stream) {
+    if (nbytes == 0) return hipSuccess;
+    const uint64_t n = nbytes / (size_t)elem;
+    const uint64_t cap = (uint64_t)(num_cu > 0 ? num_cu : 256) * 4u, g = (n + 255) / 256;
+    const unsigned grid = (unsigned)(g < cap ? (g ? g : 1) : cap);
+    if (elem == 8)
+        hipLaunchKernelGGL(accumulate_kernel<double>, dim3(grid), dim3(256), 0, stream,
+                           (const double*)in, (double*)out, n);
     else
-        hipLaunchKernelGGL(naive_kernel<uint32_t>, dim3(grid), dim3(256), 0, stream, plan.naive,
-                           (const uint32_t*)in, (uint32_t*)out);
+        hipLaunchKernelGGL(accumulate_kernel<float>, dim3(grid), dim3(256), 0, stream,
+                           (const float*)in, (float*)out, n);
     return hipGetLastError();
 }
 

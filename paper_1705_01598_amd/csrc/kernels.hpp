@@ -10,10 +10,17 @@ namespace tperm {
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks);
 
 // Enqueue the tile kernel (ROWCOPY / TILED / PACKED classes) with `grid` workgroups.
-hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid);
+// accumulate: out = out + transposed in (elements are IEEE floats of the element size).
+hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid,
+                       bool accumulate);
 
 // Enqueue the naive one-thread-per-output-element gather.
-hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream);
+hipError_t launch_naive(const Plan& plan, const void* in, void* out, hipStream_t stream,
+                        bool accumulate);
+
+// Enqueue out[i] = out[i] + in[i] over nbytes of `elem`-byte IEEE floats.
+hipError_t launch_accumulate_copy(const void* in, void* out, size_t nbytes, int elem, int num_cu,
+                                  hipStream_t stream);
 
 // Enqueue a plain copy of nbytes; elem is the guaranteed pointer alignment (4 or 8).
 hipError_t launch_copy(const void* in, void* out, size_t nbytes, int elem, int num_cu,

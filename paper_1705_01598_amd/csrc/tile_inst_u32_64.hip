@@ -1,0 +1,10 @@
+// Instantiations of the tile kernel for uint32_t elements, 64-thread workgroups.
+#include "tile_kernel.hpp"
+
+namespace tperm {
+
+const void* tile_kernel_u32_64(int nreg, bool use_lds, bool nt, bool align, bool acc) {
+    return tile_kernel_select<uint32_t, 64>(nreg, use_lds, nt, align, acc);
+}
+
+}  // namespace tperm

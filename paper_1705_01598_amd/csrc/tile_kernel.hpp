@@ -1,0 +1,343 @@
+// HIP kernels for gfx950 (MI355X): the tile kernel that every staged transpose class runs
+// through, the plain copy and the naive gather.
+//
+// Tile kernel, per workgroup (256 threads = 4 wavefronts of 64):
+//   prologue  every thread evaluates, once, the minor positions (Eqs. (4)-(6)) of the
+//             NREG tile slots it owns and keeps them in registers;
+//   per tile  the major offsets (Eqs. (2),(3)) are evaluated lane-parallel: lane j of a
+//             16-lane DPP row holds term j, a row_shr scan adds them, v_readlane moves the
+//             sum into scalar registers (the wave64 form of the paper's Algorithm 1);
+//             global -> registers -> LDS (input order), barrier, LDS (output order) ->
+//             registers -> global.  The loads of the next tile are issued before the
+//             stores of the current one so reads stay in flight all the time.
+// This header holds the device code; tile_inst_*.hip instantiate it per element type and
+// workgroup size so that the units compile in parallel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tperm_desc.h"
+
+namespace tperm {
+
+// ---------------------------------------------------------------------------------------
+// wave-level helpers
+// ---------------------------------------------------------------------------------------
+
+// Inclusive add-scan inside each row of 16 lanes with DPP row shifts; lane 15 of a row
+// ends up with the sum of the row.  Lanes shifted in from outside the row read 0.
+__device__ __forceinline__ uint32_t row_scan_add(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);  // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);  // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);  // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);  // row_shr:8
+    return v;
+}
+
+__device__ __forceinline__ uint32_t read_lane(uint32_t v, uint32_t lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
+}
+
+struct MajorPos {
+    uint32_t in, out;        // element offsets of the tile (wave-uniform)
+    uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
+};
+
+// One lane's term of the major sums, kept in registers for the whole kernel.
+struct MajorLane {
+    FastDiv cum, ext_div;
+    uint32_t ext, stride_in, stride_out;
+};
+
+__device__ __forceinline__ MajorPos major_position(const TileDesc& d, const MajorLane& ml,
+                                                   uint32_t b) {
+    const uint32_t q = fdiv(b, ml.cum);
+    const uint32_t c = q - fdiv(q, ml.ext_div) * ml.ext;
+    const uint32_t sum_in = row_scan_add(c * ml.stride_in);
+    const uint32_t sum_out = row_scan_add(c * ml.stride_out);
+    MajorPos p;
+    p.in = read_lane(sum_in, 15);
+    p.out = read_lane(sum_out, 15);
+    tile_remaining(d, [&](uint32_t lane) { return read_lane(c, lane); }, &p.rem_a, &p.rem_b);
+    return p;
+}
+
+__device__ __forceinline__ bool slot_valid(uint32_t packed, uint32_t rem_a, uint32_t rem_b) {
+    return ((packed & 0xFFFFu) < rem_a) && ((packed >> 16) < rem_b);
+}
+
+// ---------------------------------------------------------------------------------------
+// buffer addressing
+// ---------------------------------------------------------------------------------------
+// Global accesses of the tile kernel go through buffer instructions: a 128-bit resource in
+// scalar registers describes the whole tensor, the tile's major offset rides in the scalar
+// offset operand and each lane supplies only its 32-bit minor byte offset.  One VGPR per
+// address instead of two, no 64-bit vector adds, and the hardware drops any access past
+// the end of the tensor.  NT selects the nontemporal cache policy (every byte is touched
+// exactly once, so nothing is worth keeping in the caches).
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T, bool NT> struct Elem;
+template <bool NT> struct Elem<uint32_t, NT> {
+    typedef uint32_t reg;
+    // accumulate: the 4-byte element is an IEEE binary32 number
+    static __device__ __forceinline__ reg add(reg a, reg b) {
+        return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+    }
+    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, NT ? 2 : 0);
+    }
+    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
+                                                 uint32_t soff) {
+        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, NT ? 2 : 0);
+    }
+};
+template <bool NT> struct Elem<uint64_t, NT> {
+    typedef u32x2 reg;
+    // accumulate: the 8-byte element is an IEEE binary64 number
+    static __device__ __forceinline__ reg add(reg a, reg b) {
+        const double s = __hiloint2double((int)a.y, (int)a.x) + __hiloint2double((int)b.y, (int)b.x);
+        reg r;
+        r.x = (uint32_t)__double2loint(s);
+        r.y = (uint32_t)__double2hiint(s);
+        return r;
+    }
+    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, NT ? 2 : 0);
+    }
+    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
+                                                 uint32_t soff) {
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, NT ? 2 : 0);
+    }
+};
+
+// Raw (untyped, unstrided) buffer resource over `bytes` bytes starting at p.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// ---------------------------------------------------------------------------------------
+// the tile kernel
+// ---------------------------------------------------------------------------------------
+
+template <typename T, int NREG, int THREADS, bool USE_LDS, bool NT, bool ALIGN, bool ACC>
+__global__ void __launch_bounds__(THREADS)
+tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
+    typedef Elem<T, NT> io;
+    typedef typename io::reg reg_t;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    reg_t* lds = reinterpret_cast<reg_t*>(smem_raw);
+    const uint32_t tid = threadIdx.x;
+    const __amdgpu_buffer_rsrc_t rsrc_in = make_rsrc(in, nbytes);
+    const __amdgpu_buffer_rsrc_t rsrc_out = make_rsrc(out, nbytes);
+
+    // minor positions of this thread's slots; global offsets are kept in BYTES
+    uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
+    uint32_t lds_pos[NREG];  // low half: slot written on the read side; high half: slot
+                             // read on the write side
+    uint32_t wr_aux[NREG];   // line-aligned stores: position in the padded row | row phase << 16
+#pragma unroll
+    for (int j = 0; j < NREG; ++j) {
+        const uint32_t k = tid + (uint32_t)j * THREADS;
+        rd_off[j] = 0;
+        wr_off[j] = 0;
+        lds_pos[j] = 0;
+        rd_mask[j] = 0xFFFFFFFFu;  // coordinates no remaining extent exceeds: slot unused
+        wr_mask[j] = 0xFFFFFFFFu;
+        wr_aux[j] = 0xFFFFu;       // a row position beyond every run: slot unused
+        if (ALIGN) {
+            // write side: slot = (output row, position in the padded row)
+            if (k < d.oa.total_slots) {
+                const OutSlot o = out_slot(d.oa, k);
+                wr_off[j] = o.goff * (uint32_t)sizeof(T);
+                wr_mask[j] = o.xo;
+                wr_aux[j] = o.s | (o.rho << 16);
+                lds_pos[j] = o.lpos << 16;
+            }
+            if (k < d.tile_vol) {
+                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
+                rd_off[j] = si.goff * (uint32_t)sizeof(T);
+                rd_mask[j] = si.xa | (si.xb << 16);
+                lds_pos[j] |= si.loff;
+            }
+        } else if (k < d.tile_vol) {
+            const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
+            wr_off[j] = so.goff * (uint32_t)sizeof(T);
+            wr_mask[j] = so.xa | (so.xb << 16);
+            if (USE_LDS) {
+                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
+                rd_off[j] = si.goff * (uint32_t)sizeof(T);
+                rd_mask[j] = si.xa | (si.xb << 16);
+                lds_pos[j] = si.loff | (so.loff << 16);
+            } else {
+                rd_off[j] = so.ooff * (uint32_t)sizeof(T);
+                rd_mask[j] = wr_mask[j];
+            }
+        }
+    }
+
+    const uint32_t lane16 = tid & 15u;
+    MajorLane ml;
+    ml.cum = d.major.cum[lane16];
+    ml.ext_div = d.major.ext_div[lane16];
+    ml.ext = d.major.ext[lane16];
+    ml.stride_in = d.major.stride_in[lane16];
+    ml.stride_out = d.major.stride_out[lane16];
+
+    const uint32_t grid = gridDim.x, block = blockIdx.x;
+    uint32_t it = 0;
+    uint32_t b = tile_of(d, block, grid, it);
+    reg_t v[NREG];
+    MajorPos pos, nxt;
+    pos.in = pos.out = pos.rem_a = pos.rem_b = 0;
+    nxt = pos;
+    if (b < d.num_tiles) {
+        pos = major_position(d, ml, b);
+        const uint32_t soff = pos.in * (uint32_t)sizeof(T);
+#pragma unroll
+        for (int j = 0; j < NREG; ++j)
+            if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
+                v[j] = io::load(rsrc_in, rd_off[j], soff);
+    }
+    // the position of the tile after this one is worked out while the loads are in flight
+    uint32_t bn = tile_of(d, block, grid, it + 1);
+    if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
+    const bool two_buffers = d.lds_buffers == 2u;
+    // line-aligned stores: phase of the output base pointer within a 128-byte line
+    const uint32_t line_mask = ALIGN ? d.oa.line_elems - 1u : 0u;
+    const uint32_t out_phase =
+        ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
+    while (b < d.num_tiles) {
+        reg_t w[NREG];
+        uint32_t shift[NREG];     // ALIGN: this tile's lane shift of each slot's row
+        uint32_t lout_rem = 0, rem_other = 0, phi = 0;
+        if (ALIGN) {
+            const bool exists = pos.rem_a != 0u && pos.rem_b != 0u;
+            const uint32_t run_rem = d.oa.run_split == 0u ? pos.rem_a : pos.rem_b;
+            lout_rem = !exists ? 0u : (d.oa.run_split < 2u ? run_rem * d.oa.run_prefix : d.oa.run_len);
+            rem_other = d.oa.other_split == 0u ? pos.rem_a
+                                               : (d.oa.other_split == 1u ? pos.rem_b : TPERM_NO_REM);
+            phi = (out_phase + pos.out) & line_mask;
+        }
+        if (USE_LDS) {
+            // with two LDS images the tiles alternate between them and one barrier per
+            // tile is enough: a wave can only overwrite an image two tiles later, after
+            // the barrier of the tile in between
+            reg_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) img[lds_pos[j] & 0xFFFFu] = v[j];
+            __syncthreads();
+            if (ALIGN) {
+#pragma unroll
+                for (int j = 0; j < NREG; ++j) {
+                    shift[j] = (phi + (wr_aux[j] >> 16)) & line_mask;
+                    const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
+                    if (x < lout_rem && wr_mask[j] < rem_other)
+                        w[j] = img[(lds_pos[j] >> 16) - shift[j]];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NREG; ++j)
+                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j) w[j] = v[j];
+        }
+        // reads of the next tile go out before the stores of this one
+        if (bn < d.num_tiles) {
+            const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b))
+                    v[j] = io::load(rsrc_in, rd_off[j], soff);
+        }
+        const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
+        if (ACC) {
+            // out = out + transposed in: fetch the old output values (all loads first), add
+            reg_t old[NREG];
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
+                    old[j] = io::load(rsrc_out, wr_off[j], soff_out);
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = io::add(old[j], w[j]);
+        }
+        if (ALIGN) {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j) {
+                const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
+                if (x < lout_rem && wr_mask[j] < rem_other)
+                    io::store(w[j], rsrc_out, wr_off[j] - shift[j] * (uint32_t)sizeof(T), soff_out);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j)
+                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
+                    io::store(w[j], rsrc_out, wr_off[j], soff_out);
+        }
+        b = bn;
+        pos = nxt;
+        ++it;
+        bn = tile_of(d, block, grid, it + 1);
+        if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
+        if (USE_LDS && !two_buffers) __syncthreads();  // all waves are done reading the image
+    }
+}
+
+// Kernel pointer for one element type and workgroup size; nullptr if the combination is
+// not instantiated.  Accumulating kernels (ACC) exist for 256 threads, cached policy.
+template <typename T, int THREADS, bool USE_LDS, bool NT, bool ALIGN, bool ACC>
+static const void* tile_kernel_ptr(int nreg) {
+    switch (nreg) {
+#define TPERM_CASE(N) \
+    case N:           \
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC>);
+        TPERM_CASE(4)
+        TPERM_CASE(8)
+        TPERM_CASE(12)
+        TPERM_CASE(16)
+        TPERM_CASE(24)
+        TPERM_CASE(32)
+        default:
+            break;
+    }
+    if constexpr (THREADS == 256) {
+        switch (nreg) {
+            TPERM_CASE(1)
+            TPERM_CASE(2)
+            TPERM_CASE(3)
+            TPERM_CASE(6)
+            default:
+                break;
+        }
+    }
+#undef TPERM_CASE
+    return nullptr;
+}
+
+template <typename T, int THREADS>
+static const void* tile_kernel_select(int nreg, bool use_lds, bool nt, bool align, bool acc) {
+    if constexpr (THREADS == 256) {
+        if (acc) {
+            if (nt || align) return nullptr;
+            return use_lds ? tile_kernel_ptr<T, 256, true, false, false, true>(nreg)
+                           : tile_kernel_ptr<T, 256, false, false, false, true>(nreg);
+        }
+        if (use_lds && align)
+            return nt ? tile_kernel_ptr<T, 256, true, true, true, false>(nreg)
+                      : tile_kernel_ptr<T, 256, true, false, true, false>(nreg);
+    } else {
+        if (acc || align) return nullptr;
+    }
+    if (use_lds)
+        return nt ? tile_kernel_ptr<T, THREADS, true, true, false, false>(nreg)
+                  : tile_kernel_ptr<T, THREADS, true, false, false, false>(nreg);
+    return nt ? tile_kernel_ptr<T, THREADS, false, true, false, false>(nreg)
+              : tile_kernel_ptr<T, THREADS, false, false, false, false>(nreg);
+}
+
+}  // namespace tperm

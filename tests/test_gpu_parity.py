@@ -251,3 +251,25 @@ def test_copy_bytes():
     B.tperm_copy_bytes(a.data_ptr(), b.data_ptr(), (n + 3) * 4, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("kclass", [B.KERNEL_AUTO, B.KERNEL_NAIVE, B.KERNEL_PACKED, B.KERNEL_ROWCOPY])
+@pytest.mark.parametrize("dims,perm", SHAPES + [((4, 6, 5), (0, 1, 2)), ((1000003,), (0,))])
+def test_accumulate_matches_oracle(dims, perm, kclass, elem):
+    """out = out + transpose(in): one IEEE addition per element, so still bit-exact."""
+    case = wl.make_case(0, 13, dims, perm, elem)
+    try:
+        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=kclass)
+    except B.TpermError as e:
+        assert e.status == B.ERR_KERNEL
+        pytest.skip("class cannot run this shape")
+    a = wl.uniform_values(case)
+    b = wl.uniform_values(wl.make_case(0, 14, dims, perm, elem)) * 3
+    a_dev, b_dev = to_device(a), to_device(b)
+    B.tperm_execute_accumulate(plan, a_dev.data_ptr(), b_dev.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = np_uint(b_dev.cpu().numpy())
+    ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
+    bad = np.nonzero(got != ref)[0]
+    assert bad.size == 0, (dims, perm, elem, kclass, bad[:5])

@@ -234,3 +234,28 @@ def test_golden_set2_shapes():
     a = _rand(math.prod(dims), 8, 9)
     assert np.array_equal(oracle.transpose(a, dims, rev),
                           np.ascontiguousarray(a.reshape(dims, order="F").reshape(-1, order="C")))
+
+
+# -- 13. accumulate mode (Section 3.3): out + transposed in, one IEEE addition per element ---
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_accumulate_form(dtype):
+    rng = np.random.default_rng(77)
+    for _ in range(10):
+        r = int(rng.integers(1, 6))
+        dims = tuple(int(x) for x in rng.integers(1, 8, size=r))
+        perm = tuple(int(x) for x in rng.permutation(r))
+        vol = math.prod(dims)
+        a = rng.standard_normal(vol).astype(dtype)
+        b = rng.standard_normal(vol).astype(dtype)
+        got = oracle.transpose_accumulate(a, b, dims, perm)
+        # library form: the addition is elementwise on the transposed input, same dtype
+        ref = b + oracle.transpose_numpy(a, dims, perm)
+        assert got.dtype == dtype and np.array_equal(_u(got), _u(ref))
+        # onto zeros it is the plain transpose (x + 0 keeps every finite x, -0.0 aside)
+        z = oracle.transpose_accumulate(a, np.zeros(vol, dtype=dtype), dims, perm)
+        assert np.array_equal(z, oracle.transpose(a, dims, perm))
+    # small integers are exact: accumulating twice doubles
+    a = np.arange(24, dtype=dtype)
+    once = oracle.transpose_accumulate(a, np.zeros(24, dtype=dtype), (2, 3, 4), (2, 0, 1))
+    twice = oracle.transpose_accumulate(a, once, (2, 3, 4), (2, 0, 1))
+    assert np.array_equal(twice, 2 * once)
