@@ -129,3 +129,49 @@ def test_measured_plans_on_config2_subset():
         got = out[torch.from_numpy(pos).cuda()].cpu().numpy()
         expect = np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
         assert np.array_equal(got, expect) and int(out.sum()) == case.volume * (case.volume - 1) // 2
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_paper_set2_shapes_sampled(which):
+    """The rank-8 (205 M elements) and rank-12 (328 M elements, 2.6 GB: byte offsets beyond
+    2^31) shapes printed in Section 3.2, with the trivial, the reverse and seeded random
+    permutations."""
+    cases = [c for c in wl.set2(6) if c.rank == (8, 12)[which]]
+    vol = cases[0].volume
+    stamp = torch.arange(vol, dtype=torch.int64, device="cuda")
+    out = torch.empty(vol + 2 * GUARD, dtype=torch.int64, device="cuda")
+    for case in cases:
+        _stamp_check(case, stamp, out)
+
+
+def test_accumulate_full_size():
+    """out = out + transpose(in) on two C2 permutations, element by element."""
+    for case in (wl.config2()[3], wl.config2()[22]):
+        a = wl.uniform_values(case)
+        b = wl.uniform_values(wl.make_case(2, 100 + case.index, case.dims, case.perm, 8))
+        a_dev, b_dev = to_device(a), to_device(b)
+        plan = B.tperm_plan_create(case.dims, case.perm, 8)
+        B.tperm_execute_accumulate(plan, a_dev.data_ptr(), b_dev.data_ptr(), _stream())
+        torch.cuda.synchronize()
+        got = np_uint(b_dev.cpu().numpy())
+        ref = np_uint(oracle.transpose_accumulate(a, b, case.dims, case.perm))
+        assert np.array_equal(got, ref), case.name
+
+
+def test_two_streams_share_one_plan():
+    """A plan is immutable: the same plan executed concurrently on two streams."""
+    case = wl.config3()[5]
+    plan = B.tperm_plan_create(case.dims, case.perm, 8)
+    stamp = torch.arange(case.volume, dtype=torch.int64, device="cuda")
+    outs = [torch.full((case.volume,), -1, dtype=torch.int64, device="cuda") for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for s, o in zip(streams, outs):
+            B.tperm_execute(plan, stamp.data_ptr(), o.data_ptr(), s.cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
+    pos = wl.sample_positions(case, N_SAMPLES)
+    got = outs[0][torch.from_numpy(pos).cuda()].cpu().numpy()
+    expect = np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
+    assert np.array_equal(got, expect)
