@@ -1,0 +1,79 @@
+// Host-only fuzz driver for the planner, meant to be built with AddressSanitizer and
+// UndefinedBehaviorSanitizer (see test_planner_host.py).  It links plan.cpp alone (the
+// planner has no HIP dependency), creates plans for random problems and options, and checks
+// every plan's index map for being a bijection of 0..vol-1.
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <random>
+#include <vector>
+
+#include "../paper_1705_01598_amd/csrc/plan.hpp"
+
+int main(int argc, char** argv) {
+    const int iters = argc > 1 ? atoi(argv[1]) : 400;
+    std::mt19937_64 rng(12345);
+    int made = 0, rejected = 0;
+    for (int it = 0; it < iters; ++it) {
+        const int rank = 1 + (int)(rng() % 16);
+        int64_t dims[TPERM_MAX_RANK];
+        int perm[TPERM_MAX_RANK];
+        int64_t vol = 1;
+        for (int z = 0; z < rank; ++z) {
+            const int64_t cap = rank > 8 ? 3 : (rank > 4 ? 7 : 40);
+            dims[z] = 1 + (int64_t)(rng() % cap);
+            if (vol * dims[z] > 200000) dims[z] = 1;
+            vol *= dims[z];
+            perm[z] = z;
+        }
+        for (int z = rank - 1; z > 0; --z) std::swap(perm[z], perm[rng() % (z + 1)]);
+        tperm_plan_opts_t o;
+        std::memset(&o, 0, sizeof(o));
+        o.lds_pad = -1;
+        const int mode = (int)(rng() % 4);
+        if (mode == 1) o.kernel_class = 1 + (int)(rng() % 5);
+        if (mode >= 2) {
+            o.kernel_class = TPERM_KERNEL_PACKED;
+            o.m = 1 + (int)(rng() % rank);
+            o.k = 1 + (int)(rng() % rank);
+            o.tile_in = (int64_t)(rng() % 50);
+            o.tile_out = (int64_t)(rng() % 50);
+            o.grid_mode = (int)(rng() % 9);
+            o.window_in = (int)(rng() % 20);
+            o.window_out = (int)(rng() % 20);
+            o.threads = (rng() % 2) ? 64 : 256;
+            o.lds_buffers = (int)(rng() % 3);
+            o.align_out = (int)(rng() % 3);
+            o.lds_pad = (int)(rng() % 8) - 1;
+        }
+        const size_t elem = (rng() % 2) ? 4 : 8;
+        tperm::Plan* p = nullptr;
+        const tperm_status_t st = tperm::create_plan(&p, rank, dims, perm, elem, &o);
+        if (st != TPERM_OK) {
+            if (st != TPERM_ERR_KERNEL) {
+                std::printf("unexpected status %d at iteration %d\n", (int)st, it);
+                return 1;
+            }
+            ++rejected;
+            continue;
+        }
+        std::vector<int64_t> map((size_t)vol);
+        const tperm_status_t ms = tperm::index_map(*p, map.data());
+        if (ms != TPERM_OK) {
+            std::printf("index map failed (%d) at iteration %d\n", (int)ms, it);
+            return 1;
+        }
+        std::vector<char> seen((size_t)vol, 0);
+        for (int64_t i = 0; i < vol; ++i) {
+            if (map[(size_t)i] < 0 || map[(size_t)i] >= vol || seen[(size_t)map[(size_t)i]]) {
+                std::printf("not a bijection at iteration %d\n", it);
+                return 1;
+            }
+            seen[(size_t)map[(size_t)i]] = 1;
+        }
+        delete p;
+        ++made;
+    }
+    std::printf("ok: %d plans checked, %d option sets rejected\n", made, rejected);
+    return 0;
+}

@@ -243,3 +243,22 @@ def test_selected_tiles_are_sane_for_the_benchmark_shapes():
         assert info.run_out * case.elem_size >= 128, B.info_dict(info)
         if info.kernel_class != B.KERNEL_ROWCOPY:
             assert info.run_in * case.elem_size >= 128, B.info_dict(info)
+
+
+def test_planner_under_address_and_ub_sanitizers(tmp_path):
+    """The planner (pure host C++) is built with ASan + UBSan and driven with random problems
+    and options; every plan's index map must be a bijection and no sanitizer may fire."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("g++ not available")
+    exe = str(tmp_path / "planner_fuzz")
+    src = [os.path.join(ROOT, "tests", "planner_fuzz.cpp"),
+           os.path.join(ROOT, "paper_1705_01598_amd", "csrc", "plan.cpp")]
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=undefined", "-I" + os.path.join(ROOT, "include"),
+                    *src, "-o", exe], check=True)
+    env = dict(os.environ)
+    env["ASAN_OPTIONS"] = "verify_asan_link_order=0:detect_leaks=1"
+    r = subprocess.run([exe, "300"], capture_output=True, text=True, env=env)
+    assert r.returncode == 0 and r.stdout.startswith("ok:"), r.stdout + r.stderr
