@@ -81,7 +81,7 @@ typedef struct {
     int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
     int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */
-    int reserved[1];
+    int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
 } tperm_plan_opts_t;
 
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims

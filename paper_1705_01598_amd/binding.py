@@ -36,7 +36,7 @@ class PlanOpts(ctypes.Structure):
                 ("cache_policy", ctypes.c_int), ("window_in", ctypes.c_int),
                 ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
                 ("lds_buffers", ctypes.c_int), ("align_out", ctypes.c_int),
-                ("reserved", ctypes.c_int * 1)]
+                ("tile_order", ctypes.c_int)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -148,13 +148,14 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                          tile_out: int = 0, lds_pad: int = -1, grid_mode: int = 0,
                          blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
                          window_out: int = 0, threads: int = 0, lds_buffers: int = 0,
-                         align_out: int = 0) -> Plan:
+                         align_out: int = 0, tile_order: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
                     tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
                     blocks_per_cu=int(blocks_per_cu), cache_policy=int(cache_policy),
                     window_in=int(window_in), window_out=int(window_out), threads=int(threads),
-                    lds_buffers=int(lds_buffers), align_out=int(align_out))
+                    lds_buffers=int(lds_buffers), align_out=int(align_out),
+                    tile_order=int(tile_order))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:

@@ -17,9 +17,10 @@ constexpr int64_t kMaxTileVol = (int64_t)kMaxNreg * TPERM_MAX_THREADS;  // 8192 
 constexpr int64_t kMaxLdsBytes = 64 * 1024;
 // Tiles that run at the same time are grouped into windows of this many neighbours along
 // the input side and along the output side (1 = plain input order).
-constexpr int kDefaultWindow = 8;
+constexpr int kDefaultWindow = 1;
 constexpr int kDefaultThreads = 256;
 constexpr int kDefaultLdsBuffers = 1;
+constexpr int kDefaultTileOrder = 1;  // output-major: +1-4 % measured over input-major
 
 // The per-thread slot counts the tile kernel is instantiated for, by workgroup size.
 // Returns the smallest instantiated count >= need, or -1.
@@ -86,7 +87,8 @@ struct TileBuildOpts {
     int window_in = kDefaultWindow, window_out = kDefaultWindow;
     int threads = kDefaultThreads;
     int lds_buffers = kDefaultLdsBuffers;
-    int align_out = 0;      // 0: selector decides, 1: off, 2: on where possible
+    int align_out = 0;      // 0/1: off, 2: on where possible
+    int tile_order = kDefaultTileOrder;  // 0: input-major, 1: output-major
 };
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts);
 void build_naive_desc(Plan* plan);
