@@ -59,7 +59,7 @@ def cpu_baseline(cases, budget_s=12.0):
     import oracle
     from paper_1705_01598_amd import workloads as wl
 
-    sample = cases[:: max(1, len(cases) // 3)][:3]
+    sample = cases[:: max(1, len(cases) // 8)][:8]
     total_bytes, total_t, names = 0, 0.0, []
     t_begin = time.perf_counter()
     for case in sample:
