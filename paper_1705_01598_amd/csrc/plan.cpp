@@ -364,43 +364,72 @@ std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem) {
 
 // LDS cost of the first slots of each wavefront: for every wavefront-wide access, the
 // largest number of distinct addresses that fall into one bank (64 banks of 4 bytes; an
-// 8-byte access is served per half wavefront and occupies two banks).
-double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads) {
-    const int kBanks = 64;
-    double total = 0.0;
-    const int slots = std::min(nreg, 4);
-    for (int side = 0; side < 2; ++side) {
-        const TileDim* dims = side == 0 ? d.in_order : d.out_order;
-        for (int w = 0; w < threads / 64; ++w)
-            for (int j = 0; j < slots; ++j) {
-                const int groups = elem == 8 ? 2 : 1;
-                const int lanes = 64 / groups;
-                for (int gidx = 0; gidx < groups; ++gidx) {
-                    uint32_t addr[64];
-                    int n = 0;
-                    for (int l = 0; l < lanes; ++l) {
-                        const uint32_t k = (uint32_t)(w * 64 + gidx * lanes + l + j * threads);
-                        if (k >= d.tile_vol) continue;
-                        addr[n++] = tile_slot(dims, d.n_tile_dims, k).loff;
-                    }
-                    int worst = 0;
-                    for (int b = 0; b < kBanks; b += (elem == 8 ? 2 : 1)) {
-                        uint32_t seen[64];
-                        int ns = 0;
-                        for (int i = 0; i < n; ++i) {
-                            const uint32_t word = addr[i] * (uint32_t)(elem / 4);
-                            if ((int)(word % kBanks) != b) continue;
-                            bool dup = false;
-                            for (int s = 0; s < ns; ++s) dup |= (seen[s] == addr[i]);
-                            if (!dup) seen[ns++] = addr[i];
+// 8-byte access is served per half wavefront and occupies two banks).  The slot positions
+// are affine in the row padding, so they are sampled once (padding 0 and 1) and the cost
+// of any padding follows without walking the tile dims again.
+namespace {
+
+struct ConflictSampler {
+    struct Group {
+        int n;
+        uint32_t base[64];   // LDS element index at padding 0
+        uint32_t slope[64];  // increase per unit of padding
+    };
+    std::vector<Group> groups;
+    int elem = 8;
+
+    // d0 / d1: the descriptor with LDS strides set for padding 0 / padding 1
+    ConflictSampler(const TileDesc& d0, const TileDesc& d1, int elem_, int nreg, int threads)
+        : elem(elem_) {
+        const int slots = std::min(nreg, 4);
+        const int per = elem == 8 ? 32 : 64;  // lanes served together
+        for (int side = 0; side < 2; ++side) {
+            const TileDim* a = side == 0 ? d0.in_order : d0.out_order;
+            const TileDim* b = side == 0 ? d1.in_order : d1.out_order;
+            for (int w = 0; w < threads / 64; ++w)
+                for (int j = 0; j < slots; ++j)
+                    for (int g = 0; g < 64 / per; ++g) {
+                        Group gr;
+                        gr.n = 0;
+                        for (int l = 0; l < per; ++l) {
+                            const uint32_t k = (uint32_t)(w * 64 + g * per + l + j * threads);
+                            if (k >= d0.tile_vol) continue;
+                            const uint32_t l0 = tile_slot(a, d0.n_tile_dims, k).loff;
+                            const uint32_t l1 = tile_slot(b, d1.n_tile_dims, k).loff;
+                            gr.base[gr.n] = l0;
+                            gr.slope[gr.n] = l1 - l0;
+                            ++gr.n;
                         }
-                        worst = std::max(worst, ns);
+                        if (gr.n > 0) groups.push_back(gr);
                     }
-                    total += worst;
-                }
-            }
+        }
     }
-    return total;
+
+    double cost(uint32_t pad) const {
+        const uint32_t kBanks = 64;
+        const uint32_t words = (uint32_t)(elem / 4);
+        double total = 0.0;
+        for (const Group& gr : groups) {
+            uint32_t addr[64];
+            for (int i = 0; i < gr.n; ++i) addr[i] = gr.base[i] + pad * gr.slope[i];
+            std::sort(addr, addr + gr.n);
+            int per_bank[64] = {0};
+            int worst = 0;
+            for (int i = 0; i < gr.n; ++i) {
+                if (i > 0 && addr[i] == addr[i - 1]) continue;  // same address: one access
+                const uint32_t bank = (addr[i] * words) % kBanks;
+                worst = std::max(worst, ++per_bank[bank]);
+            }
+            total += worst;
+        }
+        return total;
+    }
+};
+
+}  // namespace
+
+double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads) {
+    return ConflictSampler(d, d, elem, nreg, threads).cost(0);
 }
 
 // Fill the LDS strides of both dim lists for a given row padding; returns LDS elements.
@@ -694,10 +723,14 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
             double best = 1e300;
             int best_pad = 0;
             const int max_pad = elem == 8 ? 16 : 32;
+            const uint32_t le0 = lay(0);
+            const TileDesc d0 = d;
+            const uint32_t le1 = lay(1);
+            const ConflictSampler sampler(d0, d, elem, nreg, threads);
             for (int p = 0; p <= max_pad; ++p) {
-                const uint32_t le = lay((uint32_t)p);
-                if ((int64_t)le * elem > kMaxLdsBytes) break;
-                const double cost = lds_conflict_cost(d, elem, nreg, threads);
+                const int64_t le = (int64_t)le0 + (int64_t)p * ((int64_t)le1 - (int64_t)le0);
+                if (le * elem > kMaxLdsBytes) break;
+                const double cost = sampler.cost((uint32_t)p);
                 if (cost < best - 1e-9) {
                     best = cost;
                     best_pad = p;
