@@ -72,8 +72,9 @@ typedef struct {
     int k;              /* number of leading OUTPUT dims (canonical) taken into the tile     */
     int64_t tile_out;   /* tile extent of the last of those k dims (0 = full extent)         */
     int lds_pad;        /* -1 = search; >= 0 forces the LDS row padding (elements)           */
-    int grid_mode;      /* 0 = tiles in launch order; 1 = one contiguous tile range per XCD;  */
-                        /* 2 + g = groups of 2^g consecutive tiles dealt to the XCDs in turn  */
+    int grid_mode;      /* 0 = default; -1 = tiles in launch order; 1 = one contiguous tile   */
+                        /* range per XCD; 2 + g = groups of 2^g consecutive tiles dealt to    */
+                        /* the XCDs in turn                                                   */
     int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
     int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal global access */
     int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */

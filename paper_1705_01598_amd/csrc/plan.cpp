@@ -748,6 +748,9 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     d.grid_mode = grid_mode >= 2 ? 2u : (uint32_t)grid_mode;
     d.group_log2 = grid_mode >= 2 ? (uint32_t)(grid_mode - 2) : 0u;
     if (d.group_log2 > 20u) return TPERM_ERR_KERNEL;
+    // every XCD should get at least 8 groups, or the XCDs run out of balance
+    while (d.grid_mode == 2u && d.group_log2 > 0u && d.num_tiles < ((64u << d.group_log2)))
+        --d.group_log2;
     d.tiles_per_xcd = (uint32_t)ceil_div((int64_t)d.num_tiles, 8);
 
     plan->tile = d;
@@ -860,7 +863,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (!have) return fail(TPERM_ERR_KERNEL);
     TileBuildOpts bo;
     bo.lds_pad = o.lds_pad;
-    bo.grid_mode = o.grid_mode;
+    bo.grid_mode = o.grid_mode == 0 ? kDefaultGridMode : (o.grid_mode < 0 ? 0 : o.grid_mode);
     if (o.window_in > 0) bo.window_in = o.window_in;
     if (o.window_out > 0) bo.window_out = o.window_out;
     if (o.threads > 0) bo.threads = o.threads;

@@ -101,12 +101,12 @@ TILES = [
 
 
 @pytest.mark.parametrize("elem", [8, 4])
-@pytest.mark.parametrize("grid_mode", [0, 1, 2, 6])
+@pytest.mark.parametrize("grid_mode", [-1, 1, 2, 6])
 @pytest.mark.parametrize("dims,perm,m,tin,k,tout", TILES)
 def test_explicit_tiles_match_oracle(dims, perm, m, tin, k, tout, grid_mode, elem):
     case = wl.make_case(0, 3, dims, perm, elem)
     plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin,
-                                  k=k, tile_out=tout, grid_mode=grid_mode, align_out=1 + grid_mode % 2)
+                                  k=k, tile_out=tout, grid_mode=grid_mode, align_out=1 + abs(grid_mode) % 2)
     _check(case, plan)
     plan.destroy()
 

@@ -167,7 +167,7 @@ def test_index_maps_of_every_gpu_test_plan():
                     except B.TpermError as e:
                         assert e.status == B.ERR_KERNEL
         for dims, perm, m, tin, k, tout in G.TILES:
-            for gm in (0, 1, 2, 5):
+            for gm in (-1, 0, 1, 2, 5):
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
                         tile_out=tout, grid_mode=gm)
 
@@ -202,7 +202,7 @@ def test_index_maps_random_shapes_and_tiles():
             tout = int(rng.integers(1, info.canon_dims[info.canon_perm[k - 1]] + 1))
             try:
                 _map_ok(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k,
-                        tile_out=tout, grid_mode=int(rng.integers(0, 8)),
+                        tile_out=tout, grid_mode=int(rng.integers(-1, 9)),
                         window_in=int(rng.choice([0, 1, 4, 16])), window_out=int(rng.choice([0, 1, 3, 16])),
                         threads=int(rng.choice([64, 256])), align_out=int(rng.integers(0, 3)))
             except B.TpermError as e:
