@@ -83,6 +83,8 @@ typedef struct {
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
     int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */
     int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
+    int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (see `paired` below): *
+                         * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
 } tperm_plan_opts_t;
 
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
@@ -109,7 +111,16 @@ typedef struct {
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
     int cache_policy;                      /* 1 = cached, 2 = nontemporal                   */
     int align_out;                         /* 1 if stores are issued line-aligned           */
-    int reserved[5];
+    int paired;                            /* 1: a 4-byte problem whose stride-1 dimension  *
+                                            * stays in front and has an even extent is run  *
+                                            * as the 8-byte problem with that extent halved *
+                                            * (same bytes, half the memory instructions).   *
+                                            * elem_size, volume and every extent above then *
+                                            * describe the 8-byte problem.  Used by         *
+                                            * tperm_execute when both pointers are 8-byte   *
+                                            * aligned; otherwise, and for accumulation, the *
+                                            * plan's unpaired twin runs.                    */
+    int reserved[4];
 } tperm_plan_info_t;
 
 /* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is
@@ -164,7 +175,9 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);
  * whose element the kernel would store there.  out_to_in has volume entries; entries
  * never written are -1.  Returns TPERM_ERR_INTERNAL if an output position is written
  * twice, an LDS slot is read before it is written, or an offset leaves the tensor.
- * Moves no tensor data; meant for volumes small enough to enumerate. */
+ * Moves no tensor data; meant for volumes small enough to enumerate.  For a paired plan
+ * (see tperm_plan_info_t.paired) the map evaluated is that of the 8-byte twin, written out
+ * per 4-byte element. */
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
 
 tperm_status_t tperm_plan_destroy(tperm_plan_t plan);

@@ -12,10 +12,23 @@
 
 using tperm::Plan;
 
-struct tperm_plan_s {
-    Plan* p;
+// One executable plan plus the launch geometry resolved for it on first use.
+struct PlanSlot {
+    Plan* p = nullptr;
     std::atomic<int> max_blocks{0};  // resident workgroups on the whole device; 0 = unknown
+};
+
+struct tperm_plan_s {
+    PlanSlot base;  // the problem as given
+    // Optional twin for 4-byte problems whose canonical stride-1 dimension stays in front
+    // and has an even extent: the same bytes described as 8-byte elements with that extent
+    // halved.  Half the memory instructions per byte; needs 8-byte aligned pointers.
+    PlanSlot wide;
     std::atomic<int> num_cu{0};
+    ~tperm_plan_s() {
+        delete base.p;
+        delete wide.p;
+    }
 };
 
 namespace {
@@ -31,7 +44,7 @@ tperm_status_t device_cu_count(int* num_cu) {
 }
 
 // Number of workgroups to launch for a tile plan: as many as the device keeps resident.
-tperm_status_t resolve_grid(tperm_plan_s* h, int* grid) {
+tperm_status_t resolve_grid(tperm_plan_s* handle, PlanSlot* h, int* grid) {
     int mb = h->max_blocks.load(std::memory_order_acquire);
     if (mb == 0) {
         int num_cu = 0;
@@ -44,7 +57,7 @@ tperm_status_t resolve_grid(tperm_plan_s* h, int* grid) {
         }
         if (h->p->blocks_per_cu > 0 && per_cu > h->p->blocks_per_cu) per_cu = h->p->blocks_per_cu;
         mb = per_cu * num_cu;
-        h->num_cu.store(num_cu, std::memory_order_release);
+        handle->num_cu.store(num_cu, std::memory_order_release);
         h->max_blocks.store(mb, std::memory_order_release);
     }
     int64_t g = h->p->tile.num_tiles;
@@ -62,9 +75,25 @@ tperm_status_t wrap(Plan* p, tperm_plan_t* out) {
         delete p;
         return TPERM_ERR_NOMEM;
     }
-    h->p = p;
+    h->base.p = p;
     *out = h;
     return TPERM_OK;
+}
+
+// True when the canonical problem can be described in 8-byte units: 4-byte elements, the
+// stride-1 dimension first on both sides, an even extent there.  (A canonical rank of 1
+// is the plain copy, which already moves 16 bytes per lane.)
+bool pairable(const tperm::Canonical& c, size_t elem) {
+    return elem == 4 && c.rank >= 2 && c.perm[0] == 0 && (c.dims[0] % 2) == 0;
+}
+
+// The paired problem: canonical dims with the leading extent halved, elements of 8 bytes.
+void paired_problem(const tperm::Canonical& c, int64_t* dims, int* perm) {
+    for (int z = 0; z < c.rank; ++z) {
+        dims[z] = c.dims[z];
+        perm[z] = c.perm[z];
+    }
+    dims[0] /= 2;
 }
 
 }  // namespace
@@ -79,7 +108,21 @@ tperm_status_t tperm_plan_create_ex(tperm_plan_t* plan, int rank, const int64_t*
     Plan* p = nullptr;
     tperm_status_t st = tperm::create_plan(&p, rank, dims, perm, elem_size, opts);
     if (st != TPERM_OK) return st;
-    return wrap(p, plan);
+    st = wrap(p, plan);
+    if (st != TPERM_OK) return st;
+    const bool forced = opts != nullptr && (opts->kernel_class != TPERM_KERNEL_AUTO ||
+                                            opts->m > 0 || opts->k > 0);
+    const int pair = opts ? opts->pair_elems : 0;
+    if ((pair == 2 || (pair == 0 && !forced)) && pairable(p->c, elem_size)) {
+        int64_t wdims[TPERM_MAX_RANK];
+        int wperm[TPERM_MAX_RANK];
+        paired_problem(p->c, wdims, wperm);
+        Plan* w = nullptr;
+        // a twin that cannot be built (forced options that do not fit it) is simply left out
+        if (tperm::create_plan(&w, p->c.rank, wdims, wperm, 8, opts) == TPERM_OK)
+            (*plan)->wide.p = w;
+    }
+    return TPERM_OK;
 }
 
 tperm_status_t tperm_plan_create(tperm_plan_t* plan, int rank, const int64_t* dims,
@@ -89,7 +132,6 @@ tperm_status_t tperm_plan_create(tperm_plan_t* plan, int rank, const int64_t* di
 
 tperm_status_t tperm_plan_destroy(tperm_plan_t plan) {
     if (plan == nullptr) return TPERM_ERR_NULL;
-    delete plan->p;
     delete plan;
     return TPERM_OK;
 }
@@ -98,9 +140,12 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
                                    bool accumulate) {
     if (plan == nullptr || in == nullptr || out == nullptr) return TPERM_ERR_NULL;
     if (in == out) return TPERM_ERR_ALIAS;
-    const Plan& p = *plan->p;
     const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
-    if ((a % (uintptr_t)p.elem) != 0 || (b % (uintptr_t)p.elem) != 0) return TPERM_ERR_ALIGN;
+    const uintptr_t elem = (uintptr_t)plan->base.p->elem;
+    if ((a % elem) != 0 || (b % elem) != 0) return TPERM_ERR_ALIGN;
+    PlanSlot* slot = &plan->base;
+    if (plan->wide.p != nullptr && !accumulate && ((a | b) & 7u) == 0) slot = &plan->wide;
+    const Plan& p = *slot->p;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;
     // accumulating kernels exist for the default workgroup size and store mode only
@@ -128,7 +173,7 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
         case TPERM_KERNEL_TILED:
         case TPERM_KERNEL_PACKED: {
             int grid = 0;
-            tperm_status_t st = resolve_grid(plan, &grid);
+            tperm_status_t st = resolve_grid(plan, slot, &grid);
             if (st != TPERM_OK) return st;
             err = tperm::launch_tile(p, in, out, stream, grid, accumulate);
             break;
@@ -154,11 +199,12 @@ tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void* in, void*
 
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
     if (plan == nullptr || info == nullptr) return TPERM_ERR_NULL;
-    const Plan& p = *plan->p;
+    const Plan& p = plan->wide.p ? *plan->wide.p : *plan->base.p;
     std::memset(info, 0, sizeof(*info));
+    info->paired = plan->wide.p ? 1 : 0;
     info->kernel_class = p.kclass;
     info->elem_size = p.elem;
-    info->rank = p.rank;
+    info->rank = plan->base.p->rank;
     info->canon_rank = p.c.rank;
     for (int z = 0; z < p.c.rank; ++z) {
         info->canon_dims[z] = p.c.dims[z];
@@ -192,7 +238,18 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
 
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t* out_to_in) {
     if (plan == nullptr || out_to_in == nullptr) return TPERM_ERR_NULL;
-    return tperm::index_map(*plan->p, out_to_in);
+    if (plan->wide.p == nullptr) return tperm::index_map(*plan->base.p, out_to_in);
+    // The paired twin is the plan that runs: evaluate its map over pairs, then spell it out
+    // per 4-byte element (pair q holds elements 2q and 2q+1 on both sides).
+    const int64_t pairs = plan->wide.p->c.volume;
+    std::vector<int64_t> m((size_t)pairs);
+    tperm_status_t st = tperm::index_map(*plan->wide.p, m.data());
+    if (st != TPERM_OK) return st;
+    for (int64_t q = 0; q < pairs; ++q) {
+        out_to_in[2 * q] = m[(size_t)q] < 0 ? -1 : 2 * m[(size_t)q];
+        out_to_in[2 * q + 1] = m[(size_t)q] < 0 ? -1 : 2 * m[(size_t)q] + 1;
+    }
+    return TPERM_OK;
 }
 
 tperm_status_t tperm_plan_candidate_count(int rank, const int64_t* dims, const int* perm,
@@ -223,21 +280,12 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t* plan, int rank, const i
     return wrap(p, plan);
 }
 
-tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const int64_t* dims,
-                                          const int* perm, size_t elem_size, const void* in,
-                                          void* out, void* hip_stream, int max_candidates) {
-    if (plan == nullptr) return TPERM_ERR_NULL;
-    *plan = nullptr;
-    if (in == nullptr || out == nullptr) return TPERM_ERR_NULL;
-    if (in == out) return TPERM_ERR_ALIAS;
-    tperm_status_t st = tperm::validate(rank, dims, perm, elem_size);
-    if (st != TPERM_OK) return st;
-    tperm::Canonical c;
-    tperm::canonicalise(rank, dims, perm, &c);
-    if (c.rank < 2) return tperm_plan_create(plan, rank, dims, perm, elem_size);
-    std::vector<tperm::Candidate> cands = tperm::enumerate_candidates(c, (int)elem_size);
-    if (cands.empty()) return TPERM_ERR_KERNEL;
-    if (max_candidates > 0 && (int)cands.size() > max_candidates) cands.resize(max_candidates);
+// Times every candidate plan of (rank, dims, perm, elem) on (in, out) and hands back the
+// fastest as a bare Plan.
+static tperm_status_t measure_best(int rank, const int64_t* dims, const int* perm, size_t elem,
+                                   const std::vector<tperm::Candidate>& cands, const void* in,
+                                   void* out, void* hip_stream, Plan** winner) {
+    *winner = nullptr;
     hipStream_t stream = (hipStream_t)hip_stream;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return TPERM_ERR_HIP;
@@ -250,8 +298,7 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const in
     tperm_status_t result = TPERM_OK;
     for (const auto& cd : cands) {
         Plan* p = nullptr;
-        if (tperm::create_plan_with_candidate(&p, rank, dims, perm, elem_size, cd) != TPERM_OK)
-            continue;
+        if (tperm::create_plan_with_candidate(&p, rank, dims, perm, elem, cd) != TPERM_OK) continue;
         tperm_plan_t h = nullptr;
         if (wrap(p, &h) != TPERM_OK) continue;
         float ms = 0.f;
@@ -282,8 +329,63 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const in
         return result;
     }
     if (best == nullptr) return TPERM_ERR_KERNEL;
-    *plan = best;
+    *winner = best->base.p;
+    best->base.p = nullptr;
+    tperm_plan_destroy(best);
     return TPERM_OK;
+}
+
+tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const int64_t* dims,
+                                          const int* perm, size_t elem_size, const void* in,
+                                          void* out, void* hip_stream, int max_candidates) {
+    if (plan == nullptr) return TPERM_ERR_NULL;
+    *plan = nullptr;
+    if (in == nullptr || out == nullptr) return TPERM_ERR_NULL;
+    if (in == out) return TPERM_ERR_ALIAS;
+    tperm_status_t st = tperm::validate(rank, dims, perm, elem_size);
+    if (st != TPERM_OK) return st;
+    tperm::Canonical c;
+    tperm::canonicalise(rank, dims, perm, &c);
+    if (c.rank < 2) return tperm_plan_create(plan, rank, dims, perm, elem_size);
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if ((a % elem_size) != 0 || (b % elem_size) != 0) return TPERM_ERR_ALIGN;
+    auto trimmed = [&](std::vector<tperm::Candidate> v) {
+        if (max_candidates > 0 && (int)v.size() > max_candidates) v.resize(max_candidates);
+        return v;
+    };
+    if (pairable(c, elem_size) && ((a | b) & 7u) == 0) {
+        // The paired description is what runs on these pointers: measure its candidates and
+        // keep the heuristic plan of the problem as given for unaligned pointers.
+        int64_t wdims[TPERM_MAX_RANK];
+        int wperm[TPERM_MAX_RANK];
+        paired_problem(c, wdims, wperm);
+        tperm::Canonical wc;
+        tperm::canonicalise(c.rank, wdims, wperm, &wc);
+        const auto cands = trimmed(tperm::enumerate_candidates(wc, 8));
+        if (!cands.empty()) {
+            tperm_plan_opts_t off;
+            std::memset(&off, 0, sizeof(off));
+            off.lds_pad = -1;
+            off.pair_elems = 1;
+            st = tperm_plan_create_ex(plan, rank, dims, perm, elem_size, &off);
+            if (st != TPERM_OK) return st;
+            Plan* w = nullptr;
+            st = measure_best(c.rank, wdims, wperm, 8, cands, in, out, hip_stream, &w);
+            if (st != TPERM_OK) {
+                tperm_plan_destroy(*plan);
+                *plan = nullptr;
+                return st;
+            }
+            (*plan)->wide.p = w;
+            return TPERM_OK;
+        }
+    }
+    const auto cands = trimmed(tperm::enumerate_candidates(c, (int)elem_size));
+    if (cands.empty()) return TPERM_ERR_KERNEL;
+    Plan* p = nullptr;
+    st = measure_best(rank, dims, perm, elem_size, cands, in, out, hip_stream, &p);
+    if (st != TPERM_OK) return st;
+    return wrap(p, plan);
 }
 
 tperm_status_t tperm_copy_bytes(const void* in, void* out, size_t nbytes, void* hip_stream) {

@@ -189,6 +189,55 @@ def test_unaligned_base_pointers(elem, offset):
         assert guards and np.array_equal(got, ref), (dims, perm, elem, offset)
 
 
+PAIRED_SHAPES = [
+    ((70, 45, 33), (0, 2, 1)),
+    ((6, 45, 33, 7), (0, 2, 1, 3)),             # three pairs per row: packed
+    ((2, 9, 4, 7, 3, 8), (0, 3, 5, 2, 1, 4)),   # a single pair in front
+    ((2050, 37, 5), (0, 2, 1)),                 # long rows: row copy
+    ((4, 3, 40, 50), (0, 1, 3, 2)),             # leading dims fuse to an even extent
+]
+
+
+@pytest.mark.parametrize("in_off,out_off", [(0, 0), (1, 0), (0, 1), (1, 1), (2, 2)])
+@pytest.mark.parametrize("dims,perm", PAIRED_SHAPES)
+def test_paired_four_byte_plans(dims, perm, in_off, out_off):
+    """4-byte problems run as 8-byte ones when both pointers allow it, and as given otherwise."""
+    case = wl.make_case(0, 8, dims, perm, 4)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(np.concatenate([np.zeros(in_off, dtype=a.dtype), a]))[in_off:]
+    plan = B.tperm_plan_create(dims, perm, 4)
+    assert plan.describe().paired == 1
+    got, guards = run_plan(plan, a_dev, case.volume, 4, out_off)
+    ref = np_uint(oracle.transpose(a, dims, perm))
+    assert guards and np.array_equal(got, ref), (dims, perm, in_off, out_off)
+    plan.destroy()
+
+
+def test_paired_plan_measured_and_accumulate():
+    dims, perm = (70, 45, 33), (0, 2, 1)
+    case = wl.make_case(0, 9, dims, perm, 4)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    scratch = torch.empty(case.volume, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    plan = B.tperm_plan_create_measured(dims, perm, 4, a_dev.data_ptr(), scratch.data_ptr(), stream, 12)
+    assert plan.describe().paired == 1
+    ref = np_uint(oracle.transpose(a, dims, perm))
+    for off in (0, 1):
+        got, guards = run_plan(plan, a_dev, case.volume, 4, off)
+        assert guards and np.array_equal(got, ref)
+    # accumulation adds 4-byte floats: the plan's unpaired twin runs
+    x = wl.uniform_values(case).astype(np.float32)
+    y = wl.uniform_values(wl.make_case(0, 10, dims, perm, 4)).astype(np.float32)
+    x_dev = torch.from_numpy(x).cuda()
+    y_dev = torch.from_numpy(y.copy()).cuda()
+    B.tperm_execute_accumulate(plan, x_dev.data_ptr(), y_dev.data_ptr(), stream)
+    torch.cuda.synchronize()
+    want = oracle.transpose_accumulate(x, y, dims, perm)
+    assert np.array_equal(np_uint(y_dev.cpu().numpy()), np_uint(want))
+    plan.destroy()
+
+
 def test_uniform_values_and_repeat_execution():
     """Same plan executed several times on different inputs (catches a missing barrier)."""
     dims, perm = (150, 40, 30), (2, 0, 1)

@@ -108,8 +108,45 @@ def test_canonical_form_preserves_the_oracle_result():
         info = B.tperm_plan_create(dims, perm, 4).describe()
         cr = info.canon_rank
         a = np.arange(math.prod(dims), dtype=np.int32)
+        # a paired plan describes the same bytes as 8-byte elements
+        src = a.view(np.int64) if info.paired else a
+        assert info.elem_size == src.dtype.itemsize
         assert np.array_equal(oracle.transpose(a, dims, perm),
-                              oracle.transpose(a, tuple(info.canon_dims[:cr]), tuple(info.canon_perm[:cr])))
+                              oracle.transpose(src, tuple(info.canon_dims[:cr]),
+                                               tuple(info.canon_perm[:cr])).view(np.int32))
+
+
+def test_pairing_of_four_byte_elements():
+    d = lambda dims, perm, e, **kw: B.tperm_plan_create_ex(dims, perm, e, **kw).describe()
+    # stride-1 dimension stays in front, even extent, 4-byte elements: paired
+    info = d((6, 5, 7), (0, 2, 1), 4)
+    assert info.paired == 1 and info.elem_size == 8 and info.volume == 3 * 5 * 7
+    assert tuple(info.canon_dims[:info.canon_rank]) == (3, 5, 7)
+    # fused leading dims count as one: (3, 4) travel together, 12 is even
+    info = d((3, 4, 5, 7), (0, 1, 3, 2), 4)
+    assert info.paired == 1 and tuple(info.canon_dims[:info.canon_rank]) == (6, 5, 7)
+    # not paired: odd extent, leading dimension moves, 8-byte elements, copy, switched off, forced
+    assert d((5, 6, 7), (0, 2, 1), 4).paired == 0
+    assert d((6, 5, 7), (1, 0, 2), 4).paired == 0
+    assert d((6, 5, 7), (0, 2, 1), 8).paired == 0
+    assert d((6, 5, 7), (0, 1, 2), 4).paired == 0
+    assert d((6, 5, 7), (0, 2, 1), 4, pair_elems=1).paired == 0
+    assert d((6, 5, 7), (0, 2, 1), 4, kernel_class=B.KERNEL_PACKED).paired == 0
+    assert d((6, 5, 7), (0, 2, 1), 4, kernel_class=B.KERNEL_PACKED, pair_elems=2).paired == 1
+    # the map the paired plan executes is the oracle's, element by element
+    rng = np.random.default_rng(11)
+    for _ in range(30):
+        r = int(rng.integers(2, 7))
+        dims = [int(x) for x in rng.integers(1, 7, size=r)]
+        dims[0] = 2 * int(rng.integers(1, 20))
+        rest = rng.permutation(np.arange(1, r))
+        perm = (0,) + tuple(int(x) for x in rest)
+        plan = B.tperm_plan_create(dims, perm, 4)
+        if not plan.describe().paired:      # canonical form was a copy
+            continue
+        m = B.tperm_plan_index_map(plan)
+        a = np.arange(math.prod(dims), dtype=np.int32)
+        assert np.array_equal(a[m], oracle.transpose(a, dims, perm))
 
 
 def test_class_selection_basics():
