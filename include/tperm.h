@@ -184,6 +184,37 @@ tperm_status_t tperm_plan_destroy(tperm_plan_t plan);
 
 const char *tperm_status_string(tperm_status_t s);
 
+/*
+ * One-call interface over a process-wide plan cache.
+ *
+ * Section 2.3 separates plan creation from execution because choosing a plan costs far more
+ * than running it once, measurement-based choice most of all; a caller that meets the same
+ * problem repeatedly therefore keeps its plans.  These entry points do that keeping: the
+ * cache maps (rank, dims, perm, elem_size), exactly as given, to a plan the library owns.
+ * It is thread-safe, holds at most 4096 plans (least recently used goes first) and lives
+ * until the process ends or tperm_cache_clear is called.
+ *
+ * tperm_transpose / tperm_transpose_accumulate: look the problem up, create the heuristic
+ * plan on a miss, then behave as tperm_execute / tperm_execute_accumulate on that plan
+ * (same pointer rules, same statuses; plan-creation statuses on a miss).
+ *
+ * tperm_cache_tune: runs measurement-based selection (as tperm_plan_create_measured, all
+ * candidates; `out` is overwritten, the stream is synchronised) and installs the winner for
+ * the problem, replacing any cached plan.
+ *
+ * tperm_cache_stats: any of the three result pointers may be NULL.  hits and misses count
+ * lookups by the transpose calls since the last clear.
+ */
+tperm_status_t tperm_transpose(int rank, const int64_t *dims, const int *perm, size_t elem_size,
+                               const void *in, void *out, void *hip_stream);
+tperm_status_t tperm_transpose_accumulate(int rank, const int64_t *dims, const int *perm,
+                                          size_t elem_size, const void *in, void *out,
+                                          void *hip_stream);
+tperm_status_t tperm_cache_tune(int rank, const int64_t *dims, const int *perm, size_t elem_size,
+                                const void *in, void *out, void *hip_stream);
+tperm_status_t tperm_cache_stats(int64_t *entries, int64_t *hits, int64_t *misses);
+tperm_status_t tperm_cache_clear(void);
+
 /* Plain device-to-device copy of nbytes with the library's copy kernel (the bandwidth
  * ceiling the transposes are compared with, in the way Section 3 uses a STREAM figure). */
 tperm_status_t tperm_copy_bytes(const void *in, void *out, size_t nbytes, void *hip_stream);

@@ -26,7 +26,8 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
            "tperm_plan_candidate_count", "tperm_plan_create_candidate",
            "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
-           "tperm_status_string", "tperm_copy_bytes"]
+           "tperm_status_string", "tperm_copy_bytes", "tperm_transpose", "tperm_transpose_accumulate",
+           "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
 
 
 class PlanOpts(ctypes.Structure):
@@ -87,6 +88,11 @@ def lib() -> ctypes.CDLL:
         L.tperm_plan_index_map.argtypes = [vp, i64p]
         L.tperm_plan_destroy.argtypes = [vp]
         L.tperm_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.tperm_transpose.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, vp, vp, vp]
+        L.tperm_transpose_accumulate.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, vp, vp, vp]
+        L.tperm_cache_tune.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, vp, vp, vp]
+        L.tperm_cache_stats.argtypes = [i64p, i64p, i64p]
+        L.tperm_cache_clear.argtypes = []
         L.tperm_status_string.argtypes = [ctypes.c_int]
         L.tperm_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -228,6 +234,40 @@ def tperm_plan_index_map(plan: Plan):
     if st != OK:
         raise TpermError(st, "tperm_plan_index_map")
     return buf
+
+
+def tperm_transpose(dims: Sequence[int], perm: Sequence[int], elem_size: int, in_ptr: int,
+                    out_ptr: int, stream: int = 0, accumulate: bool = False) -> None:
+    """Cached-plan transpose (tperm_transpose / tperm_transpose_accumulate)."""
+    rank, cd, cp = _marshal(dims, perm)
+    fn = lib().tperm_transpose_accumulate if accumulate else lib().tperm_transpose
+    st = fn(rank, cd, cp, int(elem_size), ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+            ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_transpose")
+
+
+def tperm_cache_tune(dims: Sequence[int], perm: Sequence[int], elem_size: int, in_ptr: int,
+                     out_ptr: int, stream: int = 0) -> None:
+    rank, cd, cp = _marshal(dims, perm)
+    st = lib().tperm_cache_tune(rank, cd, cp, int(elem_size), ctypes.c_void_p(in_ptr),
+                                ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_cache_tune")
+
+
+def tperm_cache_stats() -> dict:
+    e, h, m = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    st = lib().tperm_cache_stats(ctypes.byref(e), ctypes.byref(h), ctypes.byref(m))
+    if st != OK:
+        raise TpermError(st, "tperm_cache_stats")
+    return {"entries": e.value, "hits": h.value, "misses": m.value}
+
+
+def tperm_cache_clear() -> None:
+    st = lib().tperm_cache_clear()
+    if st != OK:
+        raise TpermError(st, "tperm_cache_clear")
 
 
 def tperm_plan_destroy(plan: Plan) -> None:

@@ -322,3 +322,51 @@ def test_accumulate_matches_oracle(dims, perm, kclass, elem):
     ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
     bad = np.nonzero(got != ref)[0]
     assert bad.size == 0, (dims, perm, elem, kclass, bad[:5])
+
+
+def test_cached_one_call_interface():
+    """tperm_transpose / tperm_cache_tune / tperm_transpose_accumulate through the plan cache."""
+    from gpu_util import GuardedOut
+    B.tperm_cache_clear()
+    stream = torch.cuda.current_stream().cuda_stream
+    problems = [((70, 45, 33), (2, 1, 0), 8), ((70, 45, 33), (0, 2, 1), 4), ((257, 131), (1, 0), 4),
+                ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 8), ((4, 6, 5), (0, 1, 2), 8)]
+    for rep in range(2):
+        for i, (dims, perm, elem) in enumerate(problems):
+            case = wl.make_case(0, 40 + i + 10 * rep, dims, perm, elem)
+            a = wl.bitpattern_values(case)
+            a_dev = to_device(a)
+            out = GuardedOut(case.volume, elem)
+            B.tperm_transpose(dims, perm, elem, a_dev.data_ptr(), out.ptr, stream)
+            torch.cuda.synchronize()
+            got = np_uint(out.view().cpu().numpy())
+            assert out.guards_intact() and np.array_equal(got, np_uint(oracle.transpose(a, dims, perm)))
+    s = B.tperm_cache_stats()
+    assert s["entries"] == len(problems) and s["misses"] == len(problems) and s["hits"] == len(problems)
+    # tuning replaces the cached plan; results stay bit-exact
+    dims, perm, elem = problems[0]
+    case = wl.make_case(0, 77, dims, perm, elem)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    scratch = torch.empty(case.volume, dtype=torch.int64, device="cuda")
+    B.tperm_cache_tune(dims, perm, elem, a_dev.data_ptr(), scratch.data_ptr(), stream)
+    assert B.tperm_cache_stats()["entries"] == len(problems)
+    out = GuardedOut(case.volume, elem)
+    B.tperm_transpose(dims, perm, elem, a_dev.data_ptr(), out.ptr, stream)
+    torch.cuda.synchronize()
+    ref = oracle.transpose(a, dims, perm)
+    assert out.guards_intact() and np.array_equal(np_uint(out.view().cpu().numpy()), np_uint(ref))
+    assert np.array_equal(np_uint(scratch.cpu().numpy()), np_uint(ref))   # the timed runs wrote it too
+    # accumulate through the cache
+    x = wl.uniform_values(case)
+    y = wl.uniform_values(wl.make_case(0, 78, dims, perm, elem))
+    x_dev, y_dev = torch.from_numpy(x).cuda(), torch.from_numpy(y.copy()).cuda()
+    B.tperm_transpose(dims, perm, elem, x_dev.data_ptr(), y_dev.data_ptr(), stream, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(np_uint(y_dev.cpu().numpy()), np_uint(oracle.transpose_accumulate(x, y, dims, perm)))
+    # errors pass through
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_transpose(dims, perm, elem, a_dev.data_ptr(), a_dev.data_ptr(), stream)
+    assert e.value.status == B.ERR_ALIAS
+    B.tperm_cache_clear()
+    assert B.tperm_cache_stats()["entries"] == 0

@@ -299,3 +299,83 @@ def test_planner_under_address_and_ub_sanitizers(tmp_path):
     env["ASAN_OPTIONS"] = "verify_asan_link_order=0:detect_leaks=1"
     r = subprocess.run([exe, "300"], capture_output=True, text=True, env=env)
     assert r.returncode == 0 and r.stdout.startswith("ok:"), r.stdout + r.stderr
+
+
+def _transpose_status(dims, perm, elem, a=None, b=None):
+    rank = len(dims)
+    cd = (ctypes.c_int64 * max(rank, 1))(*dims)
+    cp = (ctypes.c_int * max(rank, 1))(*perm)
+    pa = a.ctypes.data if a is not None else None
+    pb = b.ctypes.data if b is not None else None
+    return B.lib().tperm_transpose(rank, cd, cp, elem, pa, pb, None)
+
+
+def test_plan_cache_on_the_host():
+    """The cache keeps one plan per problem, counts hits and misses, evicts beyond its
+    capacity and reports plan-creation errors unchanged.  (Without a GPU the execute step of
+    tperm_transpose fails with the HIP status after the plan has been cached.)"""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: covered by the GPU tests")
+    B.tperm_cache_clear()
+    assert B.tperm_cache_stats() == {"entries": 0, "hits": 0, "misses": 0}
+    a = np.zeros(6 * 5 * 7, dtype=np.int64)
+    b = np.zeros_like(a)
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 8, a, b) == B.ERR_HIP
+    assert B.tperm_cache_stats() == {"entries": 1, "hits": 0, "misses": 1}
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 8, a, b) == B.ERR_HIP
+    assert B.tperm_cache_stats() == {"entries": 1, "hits": 1, "misses": 1}
+    # same extents, other permutation or element size: other entries
+    assert _transpose_status((6, 5, 7), (1, 0, 2), 8, a, b) == B.ERR_HIP
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 4, a, b) == B.ERR_HIP
+    assert B.tperm_cache_stats()["entries"] == 3
+    # argument errors come back as they would from plan creation / execute; nothing is cached
+    assert _transpose_status((6, 5, 7), (2, 0, 0), 8, a, b) == B.ERR_PERM
+    assert _transpose_status((6, 0, 7), (2, 0, 1), 8, a, b) == B.ERR_DIMS
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 2, a, b) == B.ERR_ELEM_SIZE
+    assert _transpose_status((), (), 8, a, b) == B.ERR_RANK
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 8, a, a) == B.ERR_ALIAS
+    assert _transpose_status((6, 5, 7), (2, 0, 1), 8, None, b) == B.ERR_NULL
+    assert B.lib().tperm_transpose(3, None, None, 8, None, None, None) == B.ERR_NULL
+    assert B.tperm_cache_stats()["entries"] == 3
+    # capacity: least recently used entries go first
+    for n in range(2, 4200):
+        _transpose_status((n, 3), (1, 0), 8, a, b)
+    s = B.tperm_cache_stats()
+    assert s["entries"] == 4096
+    hits = s["hits"]
+    _transpose_status((4199, 3), (1, 0), 8, a, b)      # recent: still there
+    assert B.tperm_cache_stats()["hits"] == hits + 1
+    _transpose_status((6, 5, 7), (2, 0, 1), 8, a, b)   # oldest: evicted, so a miss
+    assert B.tperm_cache_stats()["hits"] == hits + 1
+    B.tperm_cache_clear()
+    assert B.tperm_cache_stats() == {"entries": 0, "hits": 0, "misses": 0}
+
+
+def test_plan_cache_is_thread_safe():
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: covered by the GPU tests")
+    import threading
+    B.tperm_cache_clear()
+    a = np.zeros(64, dtype=np.int64)
+    b = np.zeros_like(a)
+    errors = []
+
+    def worker(seed):
+        rng = np.random.default_rng(seed)
+        for i in range(300):
+            n = int(rng.integers(2, 40))
+            if _transpose_status((n, 3, 2), (2, 0, 1), 8, a, b) != B.ERR_HIP:
+                errors.append((seed, i))
+            if i % 97 == 0:
+                B.tperm_cache_clear()
+
+    ts = [threading.Thread(target=worker, args=(s,)) for s in range(8)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert not errors
+    assert B.tperm_cache_stats()["entries"] <= 38
+    B.tperm_cache_clear()
