@@ -78,7 +78,9 @@ typedef struct {
     int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
     int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal global access */
     int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
-    int window_out;     /* on the input / output side; 0 = default, 1 = plain input order     */
+    int window_out;     /* on the input / output side; 1 = no window; 0 = default (none on    */
+                        /* the output side; on the input side only a few ragged chunks of the */
+                        /* input run are kept together)                                       */
     int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
     int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */

@@ -15,9 +15,11 @@ namespace tperm {
 constexpr int kMaxNreg = 32;
 constexpr int64_t kMaxTileVol = (int64_t)kMaxNreg * TPERM_MAX_THREADS;  // 8192 elements
 constexpr int64_t kMaxLdsBytes = 64 * 1024;
-// Tiles that run at the same time are grouped into windows of this many neighbours along
-// the input side and along the output side (1 = plain input order).
+// Tiles that run at the same time can be grouped into windows of this many neighbours along
+// the input side and along the output side (1 = no window; on the input side 0 = automatic:
+// only the chunk counter of a few ragged chunks of the input run, see build_tile_plan).
 constexpr int kDefaultWindow = 1;
+constexpr int kDefaultWindowIn = 0;
 constexpr int kDefaultThreads = 256;
 constexpr int kDefaultLdsBuffers = 1;
 // Groups of 32 consecutive tiles are dealt to the XCDs in turn: tiles that are neighbours
@@ -88,7 +90,7 @@ bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
 struct TileBuildOpts {
     int lds_pad = -1;       // -1: search
     int grid_mode = kDefaultGridMode;
-    int window_in = kDefaultWindow, window_out = kDefaultWindow;
+    int window_in = kDefaultWindowIn, window_out = kDefaultWindow;
     int threads = kDefaultThreads;
     int lds_buffers = kDefaultLdsBuffers;
     int align_out = 0;      // 0/1: off, 2: on where possible
