@@ -76,7 +76,8 @@ typedef struct {
                         /* range per XCD; 2 + g = groups of 2^g consecutive tiles dealt to    */
                         /* the XCDs in turn                                                   */
     int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
-    int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal global access */
+    int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal loads and stores; */
+                        /* 3 = nontemporal stores only                                        */
     int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
     int window_out;     /* on the input / output side; 1 = no window; 0 = default (none on    */
                         /* the output side; on the input side only a few ragged chunks of the */
@@ -111,7 +112,7 @@ typedef struct {
     int lds_pad;
     double score;                          /* selector's estimate (relative, lower = better)*/
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
-    int cache_policy;                      /* 1 = cached, 2 = nontemporal                   */
+    int cache_policy;                      /* 1 = cached, 2 = nontemporal, 3 = nt stores    */
     int align_out;                         /* 1 if stores are issued line-aligned           */
     int paired;                            /* 1: a 4-byte problem whose stride-1 dimension  *
                                             * stays in front and has an even extent is run  *

@@ -8,10 +8,10 @@
 
 namespace tperm {
 
-const void* tile_kernel_u64_256(int nreg, bool use_lds, bool nt, bool align, bool acc);
-const void* tile_kernel_u32_256(int nreg, bool use_lds, bool nt, bool align, bool acc);
-const void* tile_kernel_u64_64(int nreg, bool use_lds, bool nt, bool align, bool acc);
-const void* tile_kernel_u32_64(int nreg, bool use_lds, bool nt, bool align, bool acc);
+const void* tile_kernel_u64_256(int nreg, bool use_lds, int nt, bool align, bool acc);
+const void* tile_kernel_u32_256(int nreg, bool use_lds, int nt, bool align, bool acc);
+const void* tile_kernel_u64_64(int nreg, bool use_lds, int nt, bool align, bool acc);
+const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc);
 
 
 // ---------------------------------------------------------------------------------------
@@ -81,7 +81,8 @@ accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
 // ---------------------------------------------------------------------------------------
 
 static const void* tile_kernel_for(const Plan& plan, bool acc) {
-    const bool nt = plan.cache_policy == 2 && !acc;
+    // plan policy 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
+    const int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : 0));
     const bool align = plan.align_out;
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc)

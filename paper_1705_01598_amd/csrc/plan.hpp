@@ -48,6 +48,7 @@ struct Candidate {
     int64_t tile_vol = 0, run_in = 0, run_out = 0, num_tiles = 0;
     bool aligned = false;      // every run starts and ends on a 128-byte line boundary
     bool out_aligned = false;  // output runs start and end on line boundaries
+    bool store_nt = false;     // every written piece starts and ends on a 32-byte sector
     double utilisation = 1.0;  // useful fraction of the slots of all tiles (ragged edges)
     double score = 0.0;        // relative cost estimate, lower is better
 };
@@ -68,7 +69,7 @@ struct Plan {
     bool align_out = false;  // line-aligned store mode in use
     int grid_mode = 0;
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
-    int cache_policy = 1;    // 1 = cached, 2 = nontemporal global loads and stores
+    int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
     TileDesc tile;
     NaiveDesc naive;
     // launch geometry, resolved on first execute (needs the device); 0 = not yet

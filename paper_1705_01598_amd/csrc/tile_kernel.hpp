@@ -73,27 +73,28 @@ __device__ __forceinline__ bool slot_valid(uint32_t packed, uint32_t rem_a, uint
 // scalar registers describes the whole tensor, the tile's major offset rides in the scalar
 // offset operand and each lane supplies only its 32-bit minor byte offset.  One VGPR per
 // address instead of two, no 64-bit vector adds, and the hardware drops any access past
-// the end of the tensor.  NT selects the nontemporal cache policy (every byte is touched
-// exactly once, so nothing is worth keeping in the caches).
+// the end of the tensor.  NT selects the cache policy: 0 = cached, 1 = nontemporal stores
+// (written lines are not worth a place in the caches once they are complete), 2 =
+// nontemporal loads as well (every byte is touched exactly once).
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename T, bool NT> struct Elem;
-template <bool NT> struct Elem<uint32_t, NT> {
+template <typename T, int NT> struct Elem;
+template <int NT> struct Elem<uint32_t, NT> {
     typedef uint32_t reg;
     // accumulate: the 4-byte element is an IEEE binary32 number
     static __device__ __forceinline__ reg add(reg a, reg b) {
         return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
     }
     static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, NT ? 2 : 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
     }
     static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
                                                  uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, NT ? 2 : 0);
+        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
     }
 };
-template <bool NT> struct Elem<uint64_t, NT> {
+template <int NT> struct Elem<uint64_t, NT> {
     typedef u32x2 reg;
     // accumulate: the 8-byte element is an IEEE binary64 number
     static __device__ __forceinline__ reg add(reg a, reg b) {
@@ -104,11 +105,11 @@ template <bool NT> struct Elem<uint64_t, NT> {
         return r;
     }
     static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, NT ? 2 : 0);
+        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
     }
     static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
                                                  uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, NT ? 2 : 0);
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
     }
 };
 
@@ -121,7 +122,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // the tile kernel
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int NREG, int THREADS, bool USE_LDS, bool NT, bool ALIGN, bool ACC>
+template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
     typedef Elem<T, NT> io;
@@ -290,7 +291,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
 
 // Kernel pointer for one element type and workgroup size; nullptr if the combination is
 // not instantiated.  Accumulating kernels (ACC) exist for 256 threads, cached policy.
-template <typename T, int THREADS, bool USE_LDS, bool NT, bool ALIGN, bool ACC>
+template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC>
 static const void* tile_kernel_ptr(int nreg) {
     switch (nreg) {
 #define TPERM_CASE(N) \
@@ -319,25 +320,30 @@ static const void* tile_kernel_ptr(int nreg) {
     return nullptr;
 }
 
+// nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores.  The
+// line-aligned-store and 64-thread variants exist for policies 0 and 2 only (1 runs as 2).
 template <typename T, int THREADS>
-static const void* tile_kernel_select(int nreg, bool use_lds, bool nt, bool align, bool acc) {
+static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc) {
     if constexpr (THREADS == 256) {
         if (acc) {
-            if (nt || align) return nullptr;
-            return use_lds ? tile_kernel_ptr<T, 256, true, false, false, true>(nreg)
-                           : tile_kernel_ptr<T, 256, false, false, false, true>(nreg);
+            if (nt != 0 || align) return nullptr;
+            return use_lds ? tile_kernel_ptr<T, 256, true, 0, false, true>(nreg)
+                           : tile_kernel_ptr<T, 256, false, 0, false, true>(nreg);
         }
         if (use_lds && align)
-            return nt ? tile_kernel_ptr<T, 256, true, true, true, false>(nreg)
-                      : tile_kernel_ptr<T, 256, true, false, true, false>(nreg);
+            return nt != 0 ? tile_kernel_ptr<T, 256, true, 2, true, false>(nreg)
+                           : tile_kernel_ptr<T, 256, true, 0, true, false>(nreg);
+        if (nt == 1)
+            return use_lds ? tile_kernel_ptr<T, 256, true, 1, false, false>(nreg)
+                           : tile_kernel_ptr<T, 256, false, 1, false, false>(nreg);
     } else {
         if (acc || align) return nullptr;
     }
     if (use_lds)
-        return nt ? tile_kernel_ptr<T, THREADS, true, true, false, false>(nreg)
-                  : tile_kernel_ptr<T, THREADS, true, false, false, false>(nreg);
-    return nt ? tile_kernel_ptr<T, THREADS, false, true, false, false>(nreg)
-              : tile_kernel_ptr<T, THREADS, false, false, false, false>(nreg);
+        return nt != 0 ? tile_kernel_ptr<T, THREADS, true, 2, false, false>(nreg)
+                       : tile_kernel_ptr<T, THREADS, true, 0, false, false>(nreg);
+    return nt != 0 ? tile_kernel_ptr<T, THREADS, false, 2, false, false>(nreg)
+                   : tile_kernel_ptr<T, THREADS, false, 0, false, false>(nreg);
 }
 
 }  // namespace tperm

@@ -120,7 +120,7 @@ def test_line_aligned_stores_match_oracle(dims, perm, offset, align_out, elem):
     case = wl.make_case(0, 12, dims, perm, elem)
     try:
         plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, align_out=align_out,
-                                      cache_policy=1 + offset % 2)
+                                      cache_policy=1 + offset % 3)
     except B.TpermError as e:
         assert e.status == B.ERR_KERNEL
         pytest.skip("no LDS-staged plan for this shape")
