@@ -80,9 +80,13 @@ accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
 // dispatch
 // ---------------------------------------------------------------------------------------
 
-static const void* tile_kernel_for(const Plan& plan, bool acc) {
+// sector_aligned_out: the output base pointer is a multiple of 32 bytes.  The planner's
+// choice of nontemporal stores assumes it; from any other base the written pieces end
+// inside sectors and the cached policy is the right one.
+static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_aligned_out) {
     // plan policy 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
-    const int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : 0));
+    int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : 0));
+    if (!sector_aligned_out) nt = 0;
     const bool align = plan.align_out;
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc)
@@ -92,7 +96,7 @@ static const void* tile_kernel_for(const Plan& plan, bool acc) {
 }
 
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {
-    const void* f = tile_kernel_for(plan, false);
+    const void* f = tile_kernel_for(plan, false, true);
     if (f == nullptr) return hipErrorInvalidValue;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, f, plan.threads,
                                                         (size_t)plan.lds_bytes * plan.tile.lds_buffers);
@@ -100,7 +104,7 @@ hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {
 
 hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid,
                        bool accumulate) {
-    const void* f = tile_kernel_for(plan, accumulate);
+    const void* f = tile_kernel_for(plan, accumulate, (reinterpret_cast<uintptr_t>(out) & 31u) == 0);
     if (f == nullptr || grid < 1) return hipErrorInvalidValue;
     TileDesc d = plan.tile;
     uint32_t nbytes = (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
