@@ -259,12 +259,13 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // Nontemporal loads and stores when every run starts and ends on a line boundary.
     cd->aligned = (gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
                    std::fmod(rout, 128.0) == 0.0);
-    // Otherwise nontemporal stores alone pay off when every piece a tile writes starts and ends on a
-    // 32-byte sector boundary (measured over 330 ragged shapes: median +4-9 % from a
-    // granule of 32 bytes up, -1-2 % with swings to -20 % below): whole sectors can go
-    // straight out, while pieces that end inside a sector want the line kept in L2 until
-    // the neighbouring tile has written the rest of it.
-    cd->store_nt = gout >= 32.0;
+    // Otherwise nontemporal stores alone pay off when every piece a tile writes starts and
+    // ends on a 64-byte boundary, or on a 32-byte sector boundary if the pieces are longer
+    // than 1 KiB (measured over 330 ragged shapes: median +3-9 % there; with 32-byte
+    // granules and short pieces -4 to -8 %, below 32 bytes -1-2 % with swings to -20 %):
+    // whole sectors can go straight out, while pieces that end inside a sector want the
+    // line kept in L2 until the neighbouring tile has written the rest of it.
+    cd->store_nt = gout >= 64.0 || (gout >= 32.0 && rout > 1024.0);
     cd->out_aligned = (gout >= 128.0 && std::fmod(rout, 128.0) == 0.0);
     cd->score = cost;
     return true;
