@@ -251,7 +251,8 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // Pipeline fill and drain: a persistent workgroup spends about three tile times without
     // overlap, which matters when it only gets a few tiles (small tensors).
     const double bytes = (double)vol * elem;
-    const double wg_per_cu = std::max(2.0, std::min(8.0, std::round(20480.0 / bytes)));
+    const double wg_per_cu =
+        std::max(2.0, std::min(8.0, std::round((cd->use_lds ? 20480.0 : 14336.0) / bytes)));
     const double iters = (double)tiles / (256.0 * wg_per_cu);
     cost *= 1.0 + 3.0 / std::max(iters, 0.25);
     // The LDS stage itself is not free.
@@ -796,9 +797,12 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     plan->nreg = nreg;
     plan->threads = threads;
     {
-        // resident workgroups per compute unit: aim at ~20 KiB of tile data per CU
+        // resident workgroups per compute unit: aim at ~20 KiB of tile data per CU for the
+        // LDS-staged kernels and ~14 KiB for the LDS-free row copy, whose tiles turn round
+        // faster (measured optimum over the row-copy cases of all benchmark sets: two
+        // workgroups from 6 KiB tiles up, three below)
         const double tile_bytes = (double)cand.tile_vol * elem;
-        int bpc = (int)std::lround(20480.0 / tile_bytes);
+        int bpc = (int)std::lround((cand.use_lds ? 20480.0 : 14336.0) / tile_bytes);
         plan->blocks_per_cu = std::max(2, std::min(8, bpc));
         plan->cache_policy = cand.aligned ? 2 : (cand.store_nt ? 3 : 1);
     }

@@ -113,6 +113,15 @@ template <int NT> struct Elem<uint64_t, NT> {
     }
 };
 
+// Lane offset of a slot that must not touch memory in this tile (ragged edge, tile that
+// does not exist).  It lies beyond every tensor the planner accepts (volume * elem_size <
+// 2^32 - 256), so the buffer range check, which looks at the lane offset only, drops the
+// access: loads return zero, stores are discarded.  Issuing every memory instruction
+// unconditionally keeps their number per tile fixed, which lets the loads of the next tile
+// be waited for with a partial vmcnt while this tile's stores are still in flight; with
+// branches around them the only safe wait is for everything, stores included.
+constexpr uint32_t kDroppedOffset = 0xFFFFFF00u;
+
 // Raw (untyped, unstrided) buffer resource over `bytes` bytes starting at p.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -198,8 +207,15 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         const uint32_t soff = pos.in * (uint32_t)sizeof(T);
 #pragma unroll
         for (int j = 0; j < NREG; ++j)
-            if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b))
-                v[j] = io::load(rsrc_in, rd_off[j], soff);
+            v[j] = io::load(rsrc_in, slot_valid(rd_mask[j], pos.rem_a, pos.rem_b) ? rd_off[j] : kDroppedOffset, soff);
+    }
+    // As many dropped stores as a tile has real ones: every pass through the loop below then
+    // starts with the same queue of memory operations behind it (one tile of loads, one of
+    // stores), which is what lets the compiler wait for the loads alone.
+    {
+        const reg_t nothing = {};
+#pragma unroll
+        for (int j = 0; j < NREG; ++j) io::store(nothing, rsrc_out, kDroppedOffset, 0u);
     }
     // the position of the tile after this one is worked out while the loads are in flight
     uint32_t bn = tile_of(d, block, grid, it + 1);
@@ -252,8 +268,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b))
-                    v[j] = io::load(rsrc_in, rd_off[j], soff);
+                v[j] = io::load(rsrc_in, slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b) ? rd_off[j] : kDroppedOffset, soff);
         }
         const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
         if (ACC) {
@@ -261,24 +276,21 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             reg_t old[NREG];
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
-                    old[j] = io::load(rsrc_out, wr_off[j], soff_out);
+                old[j] = io::load(rsrc_out, slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset, soff_out);
 #pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = io::add(old[j], w[j]);
+            for (int j = 0; j < NREG; ++j) w[j] = io::add(old[j], w[j]);
         }
         if (ALIGN) {
 #pragma unroll
             for (int j = 0; j < NREG; ++j) {
                 const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                if (x < lout_rem && wr_mask[j] < rem_other)
-                    io::store(w[j], rsrc_out, wr_off[j] - shift[j] * (uint32_t)sizeof(T), soff_out);
+                const bool ok = x < lout_rem && wr_mask[j] < rem_other;
+                io::store(w[j], rsrc_out, ok ? wr_off[j] - shift[j] * (uint32_t)sizeof(T) : kDroppedOffset, soff_out);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b))
-                    io::store(w[j], rsrc_out, wr_off[j], soff_out);
+                io::store(w[j], rsrc_out, slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset, soff_out);
         }
         b = bn;
         pos = nxt;
