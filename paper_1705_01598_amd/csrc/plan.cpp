@@ -805,6 +805,8 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         int bpc = (int)std::lround((cand.use_lds ? 20480.0 : 14336.0) / tile_bytes);
         plan->blocks_per_cu = std::max(2, std::min(8, bpc));
         plan->cache_policy = cand.aligned ? 2 : (cand.store_nt ? 3 : 1);
+        // the store throttle pays on line-aligned shapes only (see tile_kernel)
+        plan->drain_stores = cand.aligned;
     }
     plan->lds_pad = pad;
     plan->align_out = align_out;
@@ -914,6 +916,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy >= 1 && o.cache_policy <= 3) p->cache_policy = o.cache_policy;
+    if (o.drain_stores == 1 || o.drain_stores == 2) p->drain_stores = o.drain_stores == 2;
     *out = p;
     return TPERM_OK;
 }
