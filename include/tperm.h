@@ -86,8 +86,9 @@ typedef struct {
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
     int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */
     int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
-    int drain_stores;   /* a workgroup waits for its previous tile's stores before it goes  *
-                         * on: 0 = selector's default; 1 = no; 2 = yes                       */
+    int loads_first;    /* order in which a workgroup issues the next tile's loads and this  *
+                         * tile's stores: 0 = selector's default; 1 = stores first; 2 = loads *
+                         * first                                                              */
     int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (see `paired` below): *
                          * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
 } tperm_plan_opts_t;
@@ -125,7 +126,7 @@ typedef struct {
                                             * tperm_execute when both pointers are 8-byte   *
                                             * aligned; otherwise, and for accumulation, the *
                                             * plan's unpaired twin runs.                    */
-    int drain_stores;                      /* 1: previous tile's stores are awaited         */
+    int loads_first;                       /* 1: next-tile loads are issued before stores   */
     int reserved[3];
 } tperm_plan_info_t;
 

@@ -230,7 +230,7 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
         info->blocks_per_cu = p.blocks_per_cu;
         info->cache_policy = p.cache_policy;
         info->align_out = p.align_out ? 1 : 0;
-        info->drain_stores = p.drain_stores ? 1 : 0;
+        info->loads_first = p.loads_first ? 1 : 0;
     } else {
         info->threads = 256;
     }

@@ -805,8 +805,9 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         int bpc = (int)std::lround((cand.use_lds ? 20480.0 : 14336.0) / tile_bytes);
         plan->blocks_per_cu = std::max(2, std::min(8, bpc));
         plan->cache_policy = cand.aligned ? 2 : (cand.store_nt ? 3 : 1);
-        // the store throttle pays on line-aligned shapes only (see tile_kernel)
-        plan->drain_stores = cand.aligned;
+        // loads before stores pays on line-aligned shapes with small LDS-staged tiles only
+        // (measured per case over all benchmark sets; see tile_kernel)
+        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6;
     }
     plan->lds_pad = pad;
     plan->align_out = align_out;
@@ -916,7 +917,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy >= 1 && o.cache_policy <= 3) p->cache_policy = o.cache_policy;
-    if (o.drain_stores == 1 || o.drain_stores == 2) p->drain_stores = o.drain_stores == 2;
+    if (o.loads_first == 1 || o.loads_first == 2) p->loads_first = o.loads_first == 2;
     *out = p;
     return TPERM_OK;
 }

@@ -69,7 +69,7 @@ struct Plan {
     bool align_out = false;  // line-aligned store mode in use
     int grid_mode = 0;
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
-    bool drain_stores = false;  // wait for the previous tile's stores each tile (see tile_kernel)
+    bool loads_first = false;  // next tile's loads are issued before this tile's stores
     int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
     TileDesc tile;
     NaiveDesc naive;

@@ -3,8 +3,8 @@
 
 namespace tperm {
 
-const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool drain) {
-    return tile_kernel_select<uint32_t, 64>(nreg, use_lds, nt, align, acc, drain);
+const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first) {
+    return tile_kernel_select<uint32_t, 64>(nreg, use_lds, nt, align, acc, loads_first);
 }
 
 }  // namespace tperm

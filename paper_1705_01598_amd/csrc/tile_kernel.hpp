@@ -131,7 +131,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // the tile kernel
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool DRAIN>
+template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
     typedef Elem<T, NT> io;
@@ -216,7 +216,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         const reg_t nothing = {};
 #pragma unroll
         for (int j = 0; j < NREG; ++j)  // distinct offsets, or the compiler folds them into one
-            io::store(nothing, rsrc_out, kDroppedOffset + 4u * (uint32_t)j, 0u);
+            io::store(nothing, rsrc_out, kDroppedOffset + (LOADS_FIRST ? 0u : 4u * (uint32_t)j), 0u);
     }
     // the position of the tile after this one is worked out while the loads are in flight
     uint32_t bn = tile_of(d, block, grid, it + 1);
@@ -228,12 +228,6 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     const uint32_t out_phase =
         ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
     while (b < d.num_tiles) {
-        // Optional throttle: before a tile is touched, all but one of the previous tile's
-        // stores must have left (vmcnt(1), other counters untouched).  Keeps the workgroups
-        // that read neighbouring lines of the same rows closer together in time: +1-3 % on
-        // line-aligned shapes with small tiles, -7 % on large ragged tiles, which do better
-        // when loads never wait for stores; the planner decides.
-        if (DRAIN) __builtin_amdgcn_s_waitcnt(0x0F70 | 1);
         reg_t w[NREG];
         uint32_t shift[NREG];     // ALIGN: this tile's lane shift of each slot's row
         uint32_t lout_rem = 0, rem_other = 0, phi = 0;
@@ -245,11 +239,23 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                                                : (d.oa.other_split == 1u ? pos.rem_b : TPERM_NO_REM);
             phi = (out_phase + pos.out) & line_mask;
         }
-        // The reads of the next tile go out before this tile's stores, after the barrier and
-        // the LDS reads, so that all waves of the workgroup ask for their rows together (the
-        // memory system likes that better than each wave going ahead on its own: measured
-        // -2 to -8 % for issuing them before the barrier).  After the last tile they are
-        // issued all the same, with every lane dropped (nxt then has remaining extents 0).
+        // The reads of the next tile and the stores of this one are issued back to back after
+        // the barrier and the LDS reads, so that all waves of the workgroup ask for their
+        // rows together (issuing the reads before the barrier, each wave on its own, measured
+        // 2-8 % slower).  Which of the two goes first is the plan's choice:
+        //   stores first  (default) the tile's registers are freed at once; every memory
+        //                 instruction is issued unconditionally, so the compiler knows how
+        //                 many are in flight and waits for exactly what it needs.  Best for
+        //                 large or ragged tiles (+5-19 % over the other form).
+        //   LOADS_FIRST   the loads sit in a conditional block ahead of the stores (without
+        //                 the branch the compiler sinks them below the stores: nothing ties
+        //                 the two together), and the workgroup ends up waiting for most of
+        //                 its previous stores before it touches the next tile.  That
+        //                 throttle is worth +3-5 % on small line-aligned tiles whose
+        //                 neighbours read other lines of the same rows (measured on the
+        //                 96^4 set); explicit waits in the other form did not reproduce it.
+        // After the last tile the stores-first form issues the reads all the same, with
+        // every lane dropped (nxt then has remaining extents 0).
         auto issue_next_loads = [&]() {
             const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
 #pragma unroll
@@ -278,11 +284,14 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                 for (int j = 0; j < NREG; ++j)
                     if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
             }
-            issue_next_loads();
         } else {
 #pragma unroll
             for (int j = 0; j < NREG; ++j) w[j] = v[j];
-            issue_next_loads();
+        }
+        if (LOADS_FIRST) {
+            // under a branch on purpose: a conditional block is what keeps the compiler from
+            // sinking these loads below the stores
+            if (bn < d.num_tiles) issue_next_loads();
         }
         const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
         if (ACC) {
@@ -306,6 +315,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             for (int j = 0; j < NREG; ++j)
                 io::store(w[j], rsrc_out, slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset, soff_out);
         }
+        if (!LOADS_FIRST) issue_next_loads();
         b = bn;
         pos = nxt;
         ++it;
@@ -318,12 +328,12 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
 
 // Kernel pointer for one element type and workgroup size; nullptr if the combination is
 // not instantiated.  Accumulating kernels (ACC) exist for 256 threads, cached policy.
-template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool DRAIN = false>
+template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST = false>
 static const void* tile_kernel_ptr(int nreg) {
     switch (nreg) {
 #define TPERM_CASE(N) \
     case N:           \
-        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, DRAIN>);
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, LOADS_FIRST>);
         TPERM_CASE(4)
         TPERM_CASE(8)
         TPERM_CASE(12)
@@ -349,11 +359,11 @@ static const void* tile_kernel_ptr(int nreg) {
 
 // nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores.  The
 // line-aligned-store and 64-thread variants exist for policies 0 and 2 only (1 runs as 2).
-// drain: wait for (all but one of) the previous tile's stores before touching the next tile;
-// exists for the plain 256-thread kernels (elsewhere the flag is ignored).
+// loads_first: order of the next tile's loads and this tile's stores (see the kernel); both
+// orders exist for the plain 256-thread kernels, elsewhere stores go first.
 template <typename T, int THREADS>
 static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc,
-                                      bool drain) {
+                                      bool loads_first) {
     if constexpr (THREADS == 256) {
         if (acc) {
             if (nt != 0 || align) return nullptr;
@@ -363,7 +373,7 @@ static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align
         if (use_lds && align)
             return nt != 0 ? tile_kernel_ptr<T, 256, true, 2, true, false>(nreg)
                            : tile_kernel_ptr<T, 256, true, 0, true, false>(nreg);
-        if (drain) {
+        if (loads_first) {
             if (nt == 1)
                 return use_lds ? tile_kernel_ptr<T, 256, true, 1, false, false, true>(nreg)
                                : tile_kernel_ptr<T, 256, false, 1, false, false, true>(nreg);

@@ -137,7 +137,7 @@ def test_workgroup_size_and_lds_buffering(dims, perm, m, tin, k, tout, lds_buffe
         plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin,
                                       k=k, tile_out=tout, threads=threads, lds_buffers=lds_buffers,
                                       cache_policy=1 + (lds_buffers % 2), window_in=4, window_out=3,
-                                      drain_stores=lds_buffers)
+                                      loads_first=lds_buffers)
     except B.TpermError as e:
         assert e.status == B.ERR_KERNEL and threads == 64     # tile too large for one wavefront
         pytest.skip("tile does not fit a single-wavefront workgroup")
