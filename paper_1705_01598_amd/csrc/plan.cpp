@@ -225,21 +225,21 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // data, plus a fixed per-run overhead.  The constants were fitted on MI355X to the
     // measured times of every candidate of ~220 benchmark cases (half held out: the fit
     // picks plans within 2 % of the best candidate on average on the held-out half):
-    // output runs keep paying off up to about 2 KiB (overhead worth 64 bytes, misalignment
-    // weighted 3x: a partially written line costs far more than a partially read one, cf.
+    // output runs keep paying off up to a few KiB (overhead worth 128 bytes, misalignment
+    // weighted 2x: a partially written line costs more than a partially read one, cf.
     // Eq. (13)), input runs are flat from 128 bytes on (overhead worth 16 bytes).
-    double cost_in = (rin + 16.0 + 2.0 * (128.0 - gin)) / rin;
+    double cost_in = (rin + 16.0 + 0.5 * (128.0 - gin)) / rin;
     if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
-    const double cost_out = (rout + 64.0 + 3.0 * (128.0 - gout)) / rout;
+    const double cost_out = (rout + 128.0 + 2.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
-    // Tile size, by slots per thread of a 256-thread workgroup.  Three to six slots are the
-    // sweet spot (enough loads in flight per wave, several workgroups per compute unit);
-    // a single slot cannot keep enough bytes in flight, and beyond eight slots fewer
-    // workgroups fit and LDS padding runs out of room.  4-byte elements tolerate many
-    // slots better: their tiles are half the bytes.
+    // Tile size, by slots per thread of a 256-thread workgroup: a table fitted with the rest.
+    // Three to eight slots are the sweet spot (enough loads in flight per wave, several
+    // workgroups per compute unit); a single slot cannot keep enough bytes in flight, and
+    // beyond twelve slots fewer workgroups fit and LDS padding runs out of room.  4-byte
+    // elements tolerate many slots better: their tiles are half the bytes.
     static const int kSlots[10] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
-    static const double kWeight8[10] = {1.4, 1.0, 0.92, 0.92, 0.92, 1.0, 1.06, 1.1, 1.17, 1.3};
-    static const double kWeight4[10] = {1.4, 1.0, 0.95, 0.85, 0.95, 1.05, 1.05, 1.05, 1.08, 1.1};
+    static const double kWeight8[10] = {1.4, 1.05, 0.95, 0.95, 1.1, 1.0, 1.06, 1.1, 1.16, 1.2};
+    static const double kWeight4[10] = {1.4, 1.0, 1.0, 0.8, 1.0, 1.0, 1.0, 1.0, 1.06, 1.1};
     const int64_t need = (vol + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
     int bucket = 9;
     for (int i = 0; i < 10; ++i)
@@ -248,13 +248,13 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
             break;
         }
     cost *= (elem == 4 ? kWeight4 : kWeight8)[bucket];
-    // Pipeline fill and drain: a persistent workgroup spends about three tile times without
+    // Pipeline fill and drain: a persistent workgroup spends about four tile times without
     // overlap, which matters when it only gets a few tiles (small tensors).
     const double bytes = (double)vol * elem;
     const double wg_per_cu =
         std::max(2.0, std::min(8.0, std::round((cd->use_lds ? 20480.0 : 14336.0) / bytes)));
     const double iters = (double)tiles / (256.0 * wg_per_cu);
-    cost *= 1.0 + 3.0 / std::max(iters, 0.25);
+    cost *= 1.0 + 4.0 / std::max(iters, 0.25);
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.1;
     // Nontemporal loads and stores when every run starts and ends on a line boundary.

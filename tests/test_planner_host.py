@@ -277,9 +277,10 @@ def test_selected_tiles_are_sane_for_the_benchmark_shapes():
         assert info.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
         assert info.lds_bytes <= 64 * 1024
         assert info.tile_volume <= info.nreg * info.threads
-        assert info.run_out * case.elem_size >= 128, B.info_dict(info)
+        # (a paired plan counts its runs in 8-byte units: info.elem_size, not the case's)
+        assert info.run_out * info.elem_size >= 128, B.info_dict(info)
         if info.kernel_class != B.KERNEL_ROWCOPY:
-            assert info.run_in * case.elem_size >= 128, B.info_dict(info)
+            assert info.run_in * info.elem_size >= 128, B.info_dict(info)
 
 
 def test_planner_under_address_and_ub_sanitizers(tmp_path):
