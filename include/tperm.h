@@ -89,6 +89,10 @@ typedef struct {
     int loads_first;    /* order in which a workgroup issues the next tile's loads and this  *
                          * tile's stores: 0 = selector's default; 1 = stores first; 2 = loads *
                          * first                                                              */
+    int vec2;           /* transposing 4-byte plans with 8-byte global accesses (see `vec2`  *
+                         * below): 0 = default (a twin plan is kept for 8-byte aligned       *
+                         * pointers), 1 = off, 2 = in this plan itself where the shape       *
+                         * allows, which then requires 8-byte aligned pointers               */
     int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (see `paired` below): *
                          * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
 } tperm_plan_opts_t;
@@ -127,7 +131,15 @@ typedef struct {
                                             * aligned; otherwise, and for accumulation, the *
                                             * plan's unpaired twin runs.                    */
     int loads_first;                       /* 1: next-tile loads are issued before stores   */
-    int reserved[3];
+    int vec2;                              /* 1: a 4-byte plan that reads two neighbours    *
+                                            * along input dim 0 and writes two neighbours   *
+                                            * along output dim 0 with single 8-byte         *
+                                            * accesses (even extents and tile extents       *
+                                            * along both); nreg counts pairs per thread.      *
+                                            * Used by tperm_execute when both pointers are  *
+                                            * 8-byte aligned; otherwise, and for            *
+                                            * accumulation, the plan's plain twin runs.     */
+    int reserved[2];
 } tperm_plan_info_t;
 
 /* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is

@@ -38,7 +38,7 @@ class PlanOpts(ctypes.Structure):
                 ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
                 ("lds_buffers", ctypes.c_int), ("align_out", ctypes.c_int),
                 ("tile_order", ctypes.c_int), ("loads_first", ctypes.c_int),
-                ("pair_elems", ctypes.c_int)]
+                ("vec2", ctypes.c_int), ("pair_elems", ctypes.c_int)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -52,7 +52,8 @@ class PlanInfo(ctypes.Structure):
                 ("lds_pad", ctypes.c_int), ("score", ctypes.c_double),
                 ("blocks_per_cu", ctypes.c_int), ("cache_policy", ctypes.c_int),
                 ("align_out", ctypes.c_int), ("paired", ctypes.c_int),
-                ("loads_first", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+                ("loads_first", ctypes.c_int), ("vec2", ctypes.c_int),
+                ("reserved", ctypes.c_int * 2)]
 
 
 class TpermError(RuntimeError):
@@ -157,7 +158,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                          blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
                          window_out: int = 0, threads: int = 0, lds_buffers: int = 0,
                          align_out: int = 0, tile_order: int = 0, pair_elems: int = 0,
-                         loads_first: int = 0) -> Plan:
+                         loads_first: int = 0, vec2: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
                     tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
@@ -165,7 +166,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                     window_in=int(window_in), window_out=int(window_out), threads=int(threads),
                     lds_buffers=int(lds_buffers), align_out=int(align_out),
                     tile_order=int(tile_order), pair_elems=int(pair_elems),
-                    loads_first=int(loads_first))
+                    loads_first=int(loads_first), vec2=int(vec2))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:
@@ -293,4 +294,4 @@ def info_dict(info: PlanInfo) -> dict:
             "lds_pad": info.lds_pad, "score": round(info.score, 4),
             "blocks_per_cu": info.blocks_per_cu, "cache_policy": info.cache_policy,
             "align_out": info.align_out, "paired": info.paired,
-            "loads_first": info.loads_first}
+            "loads_first": info.loads_first, "vec2": info.vec2}

@@ -113,6 +113,21 @@ tperm_status_t tperm_plan_create_ex(tperm_plan_t* plan, int rank, const int64_t*
     const bool forced = opts != nullptr && (opts->kernel_class != TPERM_KERNEL_AUTO ||
                                             opts->m > 0 || opts->k > 0);
     const int pair = opts ? opts->pair_elems : 0;
+    const int vec2 = opts ? opts->vec2 : 0;
+    if (vec2 == 0 && !forced && elem_size == 4 && !pairable(p->c, elem_size) &&
+        (p->kclass == TPERM_KERNEL_TILED || p->kclass == TPERM_KERNEL_PACKED)) {
+        // twin that moves the 4-byte elements in pairs, for 8-byte aligned pointers
+        tperm_plan_opts_t o;
+        std::memset(&o, 0, sizeof(o));
+        o.lds_pad = -1;
+        if (opts) o = *opts;
+        o.vec2 = 2;
+        Plan* w = nullptr;
+        if (tperm::create_plan(&w, rank, dims, perm, elem_size, &o) == TPERM_OK) {
+            if (w->vec2) (*plan)->wide.p = w;
+            else delete w;
+        }
+    }
     if ((pair == 2 || (pair == 0 && !forced)) && pairable(p->c, elem_size)) {
         int64_t wdims[TPERM_MAX_RANK];
         int wperm[TPERM_MAX_RANK];
@@ -146,6 +161,8 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
     PlanSlot* slot = &plan->base;
     if (plan->wide.p != nullptr && !accumulate && ((a | b) & 7u) == 0) slot = &plan->wide;
     const Plan& p = *slot->p;
+    // a plan that moves pairs by itself (forced through the options) has no plain twin
+    if (p.vec2 && (accumulate || ((a | b) & 7u) != 0)) return accumulate ? TPERM_ERR_KERNEL : TPERM_ERR_ALIGN;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;
     // accumulating kernels exist for the default workgroup size and store mode only
@@ -201,7 +218,7 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
     if (plan == nullptr || info == nullptr) return TPERM_ERR_NULL;
     const Plan& p = plan->wide.p ? *plan->wide.p : *plan->base.p;
     std::memset(info, 0, sizeof(*info));
-    info->paired = plan->wide.p ? 1 : 0;
+    info->paired = (plan->wide.p && !plan->wide.p->vec2) ? 1 : 0;
     info->kernel_class = p.kclass;
     info->elem_size = p.elem;
     info->rank = plan->base.p->rank;
@@ -231,6 +248,7 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
         info->cache_policy = p.cache_policy;
         info->align_out = p.align_out ? 1 : 0;
         info->loads_first = p.loads_first ? 1 : 0;
+        info->vec2 = p.vec2 ? 1 : 0;
     } else {
         info->threads = 256;
     }
@@ -240,6 +258,7 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t* out_to_in) {
     if (plan == nullptr || out_to_in == nullptr) return TPERM_ERR_NULL;
     if (plan->wide.p == nullptr) return tperm::index_map(*plan->base.p, out_to_in);
+    if (plan->wide.p->vec2) return tperm::index_map(*plan->wide.p, out_to_in);
     // The paired twin is the plan that runs: evaluate its map over pairs, then spell it out
     // per 4-byte element (pair q holds elements 2q and 2q+1 on both sides).
     const int64_t pairs = plan->wide.p->c.volume;
@@ -278,14 +297,26 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t* plan, int rank, const i
     Plan* p = nullptr;
     st = tperm::create_plan_with_candidate(&p, rank, dims, perm, elem_size, cands[index]);
     if (st != TPERM_OK) return st;
-    return wrap(p, plan);
+    st = wrap(p, plan);
+    if (st != TPERM_OK) return st;
+    if (elem_size == 4) {
+        // the same candidate moving pairs, for 8-byte aligned pointers (as tperm_plan_create)
+        Plan* w = nullptr;
+        if (tperm::create_plan_with_candidate(&w, rank, dims, perm, elem_size, cands[index], true) ==
+            TPERM_OK) {
+            if (w->vec2) (*plan)->wide.p = w;
+            else delete w;
+        }
+    }
+    return TPERM_OK;
 }
 
 // Times every candidate plan of (rank, dims, perm, elem) on (in, out) and hands back the
 // fastest as a bare Plan.
 static tperm_status_t measure_best(int rank, const int64_t* dims, const int* perm, size_t elem,
                                    const std::vector<tperm::Candidate>& cands, const void* in,
-                                   void* out, void* hip_stream, Plan** winner) {
+                                   void* out, void* hip_stream, Plan** winner,
+                                   bool vec2 = false) {
     *winner = nullptr;
     hipStream_t stream = (hipStream_t)hip_stream;
     hipEvent_t e0, e1;
@@ -299,7 +330,7 @@ static tperm_status_t measure_best(int rank, const int64_t* dims, const int* per
     tperm_status_t result = TPERM_OK;
     for (const auto& cd : cands) {
         Plan* p = nullptr;
-        if (tperm::create_plan_with_candidate(&p, rank, dims, perm, elem, cd) != TPERM_OK) continue;
+        if (tperm::create_plan_with_candidate(&p, rank, dims, perm, elem, cd, vec2) != TPERM_OK) continue;
         tperm_plan_t h = nullptr;
         if (wrap(p, &h) != TPERM_OK) continue;
         float ms = 0.f;
@@ -383,10 +414,23 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const in
     }
     const auto cands = trimmed(tperm::enumerate_candidates(c, (int)elem_size));
     if (cands.empty()) return TPERM_ERR_KERNEL;
+    const bool try_vec2 = elem_size == 4 && ((a | b) & 7u) == 0;
     Plan* p = nullptr;
-    st = measure_best(rank, dims, perm, elem_size, cands, in, out, hip_stream, &p);
+    st = measure_best(rank, dims, perm, elem_size, cands, in, out, hip_stream, &p, try_vec2);
     if (st != TPERM_OK) return st;
-    return wrap(p, plan);
+    if (!p->vec2) return wrap(p, plan);
+    // the winner moves pairs: keep it for aligned pointers beside a plain heuristic plan
+    tperm_plan_opts_t off;
+    std::memset(&off, 0, sizeof(off));
+    off.lds_pad = -1;
+    off.vec2 = 1;
+    st = tperm_plan_create_ex(plan, rank, dims, perm, elem_size, &off);
+    if (st != TPERM_OK) {
+        delete p;
+        return st;
+    }
+    (*plan)->wide.p = p;
+    return TPERM_OK;
 }
 
 tperm_status_t tperm_copy_bytes(const void* in, void* out, size_t nbytes, void* hip_stream) {

@@ -8,10 +8,10 @@
 
 namespace tperm {
 
-const void* tile_kernel_u64_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first);
-const void* tile_kernel_u32_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first);
-const void* tile_kernel_u64_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first);
-const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first);
+const void* tile_kernel_u64_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
+const void* tile_kernel_u32_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
+const void* tile_kernel_u64_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
+const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
 
 
 // ---------------------------------------------------------------------------------------
@@ -89,10 +89,10 @@ static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_align
     if (!sector_aligned_out) nt = 0;
     const bool align = plan.align_out;
     if (plan.elem == 8)
-        return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first)
-                                  : tile_kernel_u64_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first);
-    return plan.threads == 64 ? tile_kernel_u32_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first)
-                              : tile_kernel_u32_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first);
+        return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)
+                                  : tile_kernel_u64_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2);
+    return plan.threads == 64 ? tile_kernel_u32_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)
+                              : tile_kernel_u32_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2);
 }
 
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {

@@ -240,14 +240,20 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     static const int kSlots[10] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     static const double kWeight8[10] = {1.4, 1.05, 0.95, 0.95, 1.1, 1.0, 1.06, 1.1, 1.16, 1.2};
     static const double kWeight4[10] = {1.4, 1.0, 1.0, 0.8, 1.0, 1.0, 1.0, 1.0, 1.06, 1.1};
-    const int64_t need = (vol + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
+    // A 4-byte candidate that can move its elements in pairs (see build_tile_plan) has half
+    // the slots and behaves like the 8-byte kernel of the same tile bytes.
+    const int q0 = c.perm[0];
+    const bool pairs = elem == 4 && cd->use_lds && q0 != 0 && c.dims[0] % 2 == 0 &&
+                       c.dims[q0] % 2 == 0 && cd->t[0] % 2 == 0 && cd->t[q0] % 2 == 0;
+    const int64_t slots_needed = pairs ? vol / 2 : vol;
+    const int64_t need = (slots_needed + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
     int bucket = 9;
     for (int i = 0; i < 10; ++i)
         if (kSlots[i] >= need) {
             bucket = i;
             break;
         }
-    cost *= (elem == 4 ? kWeight4 : kWeight8)[bucket];
+    cost *= (elem == 4 && !pairs ? kWeight4 : kWeight8)[bucket];
     // Pipeline fill and drain: a persistent workgroup spends about four tile times without
     // overlap, which matters when it only gets a few tiles (small tensors).
     const double bytes = (double)vol * elem;
@@ -790,11 +796,45 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         --d.group_log2;
     d.tiles_per_xcd = (uint32_t)ceil_div((int64_t)d.num_tiles, 8);
 
+    // Pairs of 4-byte elements (vec2).  A transposing tile of 4-byte elements can read two
+    // neighbours along input dim 0 with one 8-byte load and write two neighbours along output
+    // dim 0 with one 8-byte store when every pair is whole and 8-byte aligned: even extents
+    // and even tile extents along both dims (all other strides are then even too).  Half
+    // the global memory instructions per byte; the LDS image and its padding stay as laid
+    // out above, in single elements.
+    int nreg_final = nreg;
+    plan->vec2 = false;
+    {
+        const int q = c.perm[0];
+        const int nreg2 = pick_nreg(cand.tile_vol / 2, threads);
+        if (opts.vec2 == 1 && elem == 4 && cand.use_lds && !align_out && threads == 256 && q != 0 &&
+            nreg2 > 0 && c.dims[0] % 2 == 0 && c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 &&
+            cand.t[q] % 2 == 0 && dim_of_in[0] == 0 && dim_of_out[0] == q) {
+            TileDim& a = d.in_order[0];
+            a.ext /= 2;
+            a.div = make_fastdiv(a.ext);
+            a.gstride *= 2;
+            a.lstride *= 2;
+            a.xshift = 1;
+            TileDim& o = d.out_order[0];
+            d.pair_lstride = o.lstride;
+            o.ext /= 2;
+            o.div = make_fastdiv(o.ext);
+            o.gstride *= 2;
+            o.lstride *= 2;
+            o.xshift = 1;
+            d.tile_vol /= 2;
+            d.vec2 = 1;
+            nreg_final = nreg2;
+            plan->vec2 = true;
+        }
+    }
+
     plan->tile = d;
     plan->cand = cand;
     plan->kclass = cand.kclass;
     plan->use_lds = cand.use_lds;
-    plan->nreg = nreg;
+    plan->nreg = nreg_final;
     plan->threads = threads;
     {
         // resident workgroups per compute unit: aim at ~20 KiB of tile data per CU for the
@@ -807,7 +847,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         plan->cache_policy = cand.aligned ? 2 : (cand.store_nt ? 3 : 1);
         // loads before stores pays on line-aligned shapes with small LDS-staged tiles only
         // (measured per case over all benchmark sets; see tile_kernel)
-        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6;
+        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6 && !plan->vec2;
     }
     plan->lds_pad = pad;
     plan->align_out = align_out;
@@ -913,6 +953,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (o.lds_buffers > 0) bo.lds_buffers = o.lds_buffers;
     bo.align_out = o.align_out;
     bo.tile_order = o.tile_order > 0 ? o.tile_order - 1 : kDefaultTileOrder;
+    bo.vec2 = o.vec2 == 2 ? 1 : 0;
     st = build_tile_plan(p, chosen, bo);
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
@@ -923,7 +964,8 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
 }
 
 tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* dims,
-                                          const int* perm, size_t elem, const Candidate& cand) {
+                                          const int* perm, size_t elem, const Candidate& cand,
+                                          bool vec2) {
     if (out == nullptr) return TPERM_ERR_NULL;
     *out = nullptr;
     tperm_status_t st = validate(rank, dims, perm, elem);
@@ -939,7 +981,9 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
     canonicalise(rank, dims, perm, &p->c);
     std::memset(&p->tile, 0, sizeof(p->tile));
     build_naive_desc(p);
-    st = build_tile_plan(p, cand, TileBuildOpts());
+    TileBuildOpts bo;
+    bo.vec2 = vec2 ? 1 : 0;
+    st = build_tile_plan(p, cand, bo);
     if (st != TPERM_OK) {
         delete p;
         return st;
@@ -988,7 +1032,32 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
             }
             uint32_t rem_a = 0, rem_b = 0;
             tile_remaining(d, [&](uint32_t l) { return coord[l]; }, &rem_a, &rem_b);
-            if (plan.use_lds) {
+            if (plan.use_lds && d.vec2) {
+                // pairs: two neighbours along input dim 0 in, two along output dim 0 out
+                std::fill(lds.begin(), lds.end(), -1);
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.in_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && s.xb < rem_b)) continue;
+                    for (uint32_t e = 0; e < 2; ++e) {
+                        const uint64_t gi = maj_in + s.goff + e;
+                        if (gi >= (uint64_t)vol || s.loff + e >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                        if (lds[s.loff + e] != -1) return TPERM_ERR_INTERNAL;
+                        lds[s.loff + e] = (int64_t)gi;
+                    }
+                }
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.out_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && s.xb < rem_b)) continue;
+                    for (uint32_t e = 0; e < 2; ++e) {
+                        const uint64_t go = maj_out + s.goff + e;
+                        const uint32_t li = s.loff + e * d.pair_lstride;
+                        if (go >= (uint64_t)vol || li >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                        if (lds[li] == -1) return TPERM_ERR_INTERNAL;
+                        if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                        out_to_in[go] = lds[li];
+                    }
+                }
+            } else if (plan.use_lds) {
                 std::fill(lds.begin(), lds.end(), -1);
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {
                     const Slot s = tile_slot(d.in_order, d.n_tile_dims, k);

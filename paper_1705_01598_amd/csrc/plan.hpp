@@ -69,6 +69,7 @@ struct Plan {
     bool align_out = false;  // line-aligned store mode in use
     int grid_mode = 0;
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
+    bool vec2 = false;         // 4-byte elements move in pairs; needs 8-byte aligned pointers
     bool loads_first = false;  // next tile's loads are issued before this tile's stores
     int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
     TileDesc tile;
@@ -97,6 +98,7 @@ struct TileBuildOpts {
     int lds_buffers = kDefaultLdsBuffers;
     int align_out = 0;      // 0/1: off, 2: on where possible
     int tile_order = kDefaultTileOrder;  // 0: input-major, 1: output-major
+    int vec2 = 0;           // 4-byte elements in pairs: 0 = off, 1 = where possible
 };
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts);
 void build_naive_desc(Plan* plan);
@@ -106,8 +108,11 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
                            size_t elem, const tperm_plan_opts_t* opts);
 
 // Plan for one explicit candidate (measurement-based selection tries them one by one).
+// vec2: move 4-byte elements in pairs where the candidate allows (the plan then needs 8-byte
+// aligned pointers; plan->vec2 tells whether it does).
 tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* dims,
-                                          const int* perm, size_t elem, const Candidate& cand);
+                                          const int* perm, size_t elem, const Candidate& cand,
+                                          bool vec2 = false);
 
 // Host evaluation of the plan's index maps (see tperm_plan_index_map).
 tperm_status_t index_map(const Plan& plan, int64_t* out_to_in);

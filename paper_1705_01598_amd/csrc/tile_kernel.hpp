@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "tperm_desc.h"
 
 namespace tperm {
@@ -131,13 +133,17 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // the tile kernel
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST>
+template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
-    typedef Elem<T, NT> io;
+    // VEC2 (4-byte elements only): a slot is a pair of elements, moved through global memory
+    // with 8-byte accesses; the LDS image stays in single elements.
+    static_assert(!VEC2 || (sizeof(T) == 4 && USE_LDS && !ALIGN && !ACC), "vec2 is a 4-byte LDS-staged form");
+    typedef Elem<typename std::conditional<VEC2, uint64_t, T>::type, NT> io;
     typedef typename io::reg reg_t;
+    typedef typename std::conditional<VEC2, uint32_t, reg_t>::type lds_t;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    reg_t* lds = reinterpret_cast<reg_t*>(smem_raw);
+    lds_t* lds = reinterpret_cast<lds_t*>(smem_raw);
     const uint32_t tid = threadIdx.x;
     const __amdgpu_buffer_rsrc_t rsrc_in = make_rsrc(in, nbytes);
     const __amdgpu_buffer_rsrc_t rsrc_out = make_rsrc(out, nbytes);
@@ -266,23 +272,40 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             // with two LDS images the tiles alternate between them and one barrier per
             // tile is enough: a wave can only overwrite an image two tiles later, after
             // the barrier of the tile in between
-            reg_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
+            lds_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) img[lds_pos[j] & 0xFFFFu] = v[j];
+                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) {
+                    if constexpr (VEC2) {
+                        // neighbours along input dim 0 are neighbours in the image
+                        img[lds_pos[j] & 0xFFFFu] = v[j].x;
+                        img[(lds_pos[j] & 0xFFFFu) + 1u] = v[j].y;
+                    } else {
+                        img[lds_pos[j] & 0xFFFFu] = v[j];
+                    }
+                }
             __syncthreads();
             if (ALIGN) {
 #pragma unroll
                 for (int j = 0; j < NREG; ++j) {
                     shift[j] = (phi + (wr_aux[j] >> 16)) & line_mask;
                     const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                    if (x < lout_rem && wr_mask[j] < rem_other)
-                        w[j] = img[(lds_pos[j] >> 16) - shift[j]];
+                    if constexpr (!VEC2)
+                        if (x < lout_rem && wr_mask[j] < rem_other)
+                            w[j] = img[(lds_pos[j] >> 16) - shift[j]];
                 }
             } else {
 #pragma unroll
                 for (int j = 0; j < NREG; ++j)
-                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) w[j] = img[lds_pos[j] >> 16];
+                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) {
+                        if constexpr (VEC2) {
+                            // neighbours along output dim 0 are pair_lstride apart
+                            w[j].x = img[lds_pos[j] >> 16];
+                            w[j].y = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                        } else {
+                            w[j] = img[lds_pos[j] >> 16];
+                        }
+                    }
             }
         } else {
 #pragma unroll
@@ -328,12 +351,12 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
 
 // Kernel pointer for one element type and workgroup size; nullptr if the combination is
 // not instantiated.  Accumulating kernels (ACC) exist for 256 threads, cached policy.
-template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST = false>
+template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST = false, bool VEC2 = false>
 static const void* tile_kernel_ptr(int nreg) {
     switch (nreg) {
 #define TPERM_CASE(N) \
     case N:           \
-        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, LOADS_FIRST>);
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, LOADS_FIRST, VEC2>);
         TPERM_CASE(4)
         TPERM_CASE(8)
         TPERM_CASE(12)
@@ -363,7 +386,17 @@ static const void* tile_kernel_ptr(int nreg) {
 // orders exist for the plain 256-thread kernels, elsewhere stores go first.
 template <typename T, int THREADS>
 static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc,
-                                      bool loads_first) {
+                                      bool loads_first, bool vec2) {
+    if constexpr (THREADS == 256 && sizeof(T) == 4) {
+        // pairs of 4-byte elements: LDS-staged, stores first
+        if (vec2) {
+            if (!use_lds || align || acc) return nullptr;
+            if (nt == 1) return tile_kernel_ptr<T, 256, true, 1, false, false, false, true>(nreg);
+            return nt != 0 ? tile_kernel_ptr<T, 256, true, 2, false, false, false, true>(nreg)
+                           : tile_kernel_ptr<T, 256, true, 0, false, false, false, true>(nreg);
+        }
+    }
+    if (vec2) return nullptr;
     if constexpr (THREADS == 256) {
         if (acc) {
             if (nt != 0 || align) return nullptr;

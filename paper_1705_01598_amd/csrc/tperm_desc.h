@@ -41,6 +41,8 @@ struct TileDim {
     uint32_t ostride;  // element stride of this dim in global memory on the other side
     uint32_t lstride;  // element stride of this dim in the LDS image of the tile
     uint32_t sel;      // 0: whole dim is in the tile; 1: split dim A; 2: split dim B
+    uint32_t xshift;   // 1 if this entry counts pairs of elements (vec2 plans), else 0: the
+                       // coordinate compared with the remaining extent is x << xshift
 };
 
 // One term of the major-offset sums (Eqs. (2),(3)): lane j of every 16-lane row holds
@@ -120,6 +122,10 @@ struct TileDesc {
     uint32_t split_tile[2]; // tile extent t of split dim A / B
     uint32_t lds_elems;     // size of one LDS image (with padding), elements
     uint32_t lds_buffers;   // 1, or 2: tiles alternate between two images (one barrier per tile)
+    uint32_t vec2;          // 1: 4-byte elements move in pairs (8-byte global accesses): entry 0
+                            // of in_order counts pairs along input dim 0, entry 0 of out_order
+                            // pairs along output dim 0; tile_vol is in pairs
+    uint32_t pair_lstride;  // vec2: LDS distance of the two elements of an output-side pair
     uint32_t grid_mode;     // how workgroups walk the tiles, see tile_of()
     uint32_t tiles_per_xcd; // grid_mode 1: ceil(num_tiles / 8)
     uint32_t group_log2;    // grid_mode 2: log2 of the tile group dealt to one XCD
@@ -155,8 +161,8 @@ TPERM_HD Slot tile_slot(const TileDim* dims, uint32_t n, uint32_t k) {
         s.goff += x * dims[i].gstride;
         s.ooff += x * dims[i].ostride;
         s.loff += x * dims[i].lstride;
-        if (dims[i].sel == 1u) s.xa = x;
-        if (dims[i].sel == 2u) s.xb = x;
+        if (dims[i].sel == 1u) s.xa = x << dims[i].xshift;
+        if (dims[i].sel == 2u) s.xb = x << dims[i].xshift;
     }
     return s;
 }

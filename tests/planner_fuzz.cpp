@@ -45,6 +45,9 @@ int main(int argc, char** argv) {
             o.lds_buffers = (int)(rng() % 3);
             o.align_out = (int)(rng() % 3);
             o.lds_pad = (int)(rng() % 8) - 1;
+            o.vec2 = (int)(rng() % 3);
+            o.loads_first = (int)(rng() % 3);
+            o.tile_order = (int)(rng() % 3);
         }
         const size_t elem = (rng() % 2) ? 4 : 8;
         tperm::Plan* p = nullptr;

@@ -239,6 +239,55 @@ def test_paired_plan_measured_and_accumulate():
     plan.destroy()
 
 
+VEC2_SHAPES = [
+    ((258, 130), (1, 0)),                        # ragged chunks on both sides, even extents
+    ((64, 64), (1, 0)),
+    ((64, 45, 32), (2, 1, 0)),
+    ((6, 5, 4, 8, 3, 8), (3, 0, 5, 2, 1, 4)),    # pairs along dims 0 and 3
+    ((2, 1000), (1, 0)),                         # a single pair per input row
+    ((1000, 2), (1, 0)),
+    ((16, 16, 16, 16), (2, 3, 0, 1)),
+    ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4)),
+]
+
+
+@pytest.mark.parametrize("in_off,out_off", [(0, 0), (1, 0), (0, 1), (2, 2)])
+@pytest.mark.parametrize("dims,perm", VEC2_SHAPES)
+def test_vec2_four_byte_plans(dims, perm, in_off, out_off):
+    """4-byte transposes move pairs when both pointers are 8-byte aligned, single elements
+    otherwise; bit-exact either way."""
+    case = wl.make_case(0, 13, dims, perm, 4)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(np.concatenate([np.zeros(in_off, dtype=a.dtype), a]))[in_off:]
+    plan = B.tperm_plan_create(dims, perm, 4)
+    assert plan.describe().vec2 == 1
+    got, guards = run_plan(plan, a_dev, case.volume, 4, out_off)
+    ref = np_uint(oracle.transpose(a, dims, perm))
+    assert guards and np.array_equal(got, ref), (dims, perm, in_off, out_off)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("dims,perm,tin,tout", [((258, 130), (1, 0), 32, 32), ((258, 130), (1, 0), 100, 6),
+                                                ((70, 46, 34), (2, 1, 0), 14, 8), ((20, 7, 34, 6), (2, 1, 3, 0), 4, 10)])
+@pytest.mark.parametrize("cache_policy", [1, 2, 3])
+def test_vec2_explicit_tiles(dims, perm, tin, tout, cache_policy):
+    case = wl.make_case(0, 14, dims, perm, 4)
+    plan = B.tperm_plan_create_ex(dims, perm, 4, kernel_class=B.KERNEL_PACKED, m=1, tile_in=tin, k=1,
+                                  tile_out=tout, vec2=2, cache_policy=cache_policy)
+    assert plan.describe().vec2 == 1
+    _check(case, plan)
+    # such a plan has no plain twin: unaligned pointers and accumulation are refused
+    a_dev = to_device(np.zeros(case.volume + 1, dtype=np.int32))
+    out = torch.zeros(case.volume + 1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute(plan, a_dev.data_ptr() + 4, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert e.value.status == B.ERR_ALIGN
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_execute_accumulate(plan, a_dev.data_ptr(), out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert e.value.status == B.ERR_KERNEL
+    plan.destroy()
+
+
 def test_uniform_values_and_repeat_execution():
     """Same plan executed several times on different inputs (catches a missing barrier)."""
     dims, perm = (150, 40, 30), (2, 0, 1)

@@ -149,6 +149,42 @@ def test_pairing_of_four_byte_elements():
         assert np.array_equal(a[m], oracle.transpose(a, dims, perm))
 
 
+def test_vec2_plans_for_four_byte_transposes():
+    """4-byte plans that transpose even-extent leading dims move pairs; the map they execute,
+    evaluated on the host, is the oracle's."""
+    d = lambda dims, perm, e, **kw: B.tperm_plan_create_ex(dims, perm, e, **kw).describe()
+    assert d((64, 48), (1, 0), 4).vec2 == 1
+    assert d((64, 48), (1, 0), 8).vec2 == 0            # 8-byte elements
+    assert d((63, 48), (1, 0), 4).vec2 == 0            # odd input leading extent
+    assert d((64, 47), (1, 0), 4).vec2 == 0            # odd output leading extent
+    assert d((64, 48), (1, 0), 4, vec2=1).vec2 == 0    # switched off
+    assert d((64, 6, 48), (0, 2, 1), 4).vec2 == 0      # leading dim stays: paired instead
+    assert d((64, 6, 48), (0, 2, 1), 4).paired == 1
+    rng = np.random.default_rng(21)
+    seen = 0
+    for _ in range(60):
+        r = int(rng.integers(2, 6))
+        dims = [int(x) for x in rng.integers(1, 9, size=r)]
+        perm = [int(x) for x in rng.permutation(r)]
+        if perm[0] == 0:
+            perm[0], perm[1] = perm[1], perm[0]
+        dims[0] = 2 * int(rng.integers(1, 40))
+        dims[perm[0]] = 2 * int(rng.integers(1, 40))
+        for kw in ({}, dict(vec2=2), dict(vec2=2, kernel_class=B.KERNEL_PACKED, m=1, tile_in=int(2 * rng.integers(1, 9)),
+                                          k=1, tile_out=int(2 * rng.integers(1, 9)))):
+            try:
+                plan = B.tperm_plan_create_ex(dims, perm, 4, **kw)
+            except B.TpermError as e:
+                assert e.status == B.ERR_KERNEL
+                continue
+            info = plan.describe()
+            seen += info.vec2
+            m = B.tperm_plan_index_map(plan)
+            a = np.arange(math.prod(dims), dtype=np.int32)
+            assert np.array_equal(a[m], oracle.transpose(a, dims, perm)), (dims, perm, kw, B.info_dict(info))
+    assert seen > 60
+
+
 def test_class_selection_basics():
     k = lambda d, p, e=8: B.tperm_plan_create(d, p, e).describe().kernel_class
     assert k((1000,), (0,)) == B.KERNEL_COPY
@@ -276,7 +312,7 @@ def test_selected_tiles_are_sane_for_the_benchmark_shapes():
         info = B.tperm_plan_create(case.dims, case.perm, case.elem_size).describe()
         assert info.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
         assert info.lds_bytes <= 64 * 1024
-        assert info.tile_volume <= info.nreg * info.threads
+        assert info.tile_volume <= info.nreg * info.threads * (2 if info.vec2 else 1)
         # (a paired plan counts its runs in 8-byte units: info.elem_size, not the case's)
         assert info.run_out * info.elem_size >= 128, B.info_dict(info)
         if info.kernel_class != B.KERNEL_ROWCOPY:
