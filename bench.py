@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per launch of the tile kernel on the default workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs scaled by what the same counters read for the library's
 # plain copy of known size (see profiles/tile_kernel_c2_96x96x96x96_fp64.txt).  None = not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c2": 1359036116}
+TRAFFIC_BYTES_PER_LAUNCH = {"c2": 1359045700}
 
 
 def parse_args():

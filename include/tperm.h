@@ -166,7 +166,10 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const i
 /* Measurement-based plan selection (Section 2.3): every candidate plan the selector
  * enumerates is executed on (in, out) on `hip_stream` and timed with HIP events; the
  * fastest is kept.  in/out are device buffers of at least volume*elem_size bytes; out is
- * overwritten.  Synchronises the stream.  max_candidates <= 0 means all. */
+ * overwritten.  Synchronises the stream.  max_candidates <= 0 means all.  The candidates
+ * are timed back to back on these buffers as they are: a tensor small enough to stay in the
+ * last-level cache is timed cache-hot, which need not rank the plans as HBM-resident data
+ * would. */
 tperm_status_t tperm_plan_create_measured(tperm_plan_t *plan, int rank, const int64_t *dims,
                                           const int *perm, size_t elem_size, const void *in,
                                           void *out, void *hip_stream, int max_candidates);
