@@ -114,9 +114,9 @@ tperm_status_t tperm_plan_create_ex(tperm_plan_t* plan, int rank, const int64_t*
                                             opts->m > 0 || opts->k > 0);
     const int pair = opts ? opts->pair_elems : 0;
     const int vec2 = opts ? opts->vec2 : 0;
-    if (vec2 == 0 && !forced && elem_size == 4 && !pairable(p->c, elem_size) &&
+    if (vec2 == 0 && !forced && !pairable(p->c, elem_size) &&
         (p->kclass == TPERM_KERNEL_TILED || p->kclass == TPERM_KERNEL_PACKED)) {
-        // twin that moves the 4-byte elements in pairs, for 8-byte aligned pointers
+        // twin that moves the elements in pairs, for pointers aligned to two elements
         tperm_plan_opts_t o;
         std::memset(&o, 0, sizeof(o));
         o.lds_pad = -1;
@@ -159,10 +159,12 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
     const uintptr_t elem = (uintptr_t)plan->base.p->elem;
     if ((a % elem) != 0 || (b % elem) != 0) return TPERM_ERR_ALIGN;
     PlanSlot* slot = &plan->base;
-    if (plan->wide.p != nullptr && !accumulate && ((a | b) & 7u) == 0) slot = &plan->wide;
+    const uintptr_t pair_mask = 2u * elem - 1u;  // the twin moves two elements per access
+    if (plan->wide.p != nullptr && !accumulate && ((a | b) & pair_mask) == 0) slot = &plan->wide;
     const Plan& p = *slot->p;
     // a plan that moves pairs by itself (forced through the options) has no plain twin
-    if (p.vec2 && (accumulate || ((a | b) & 7u) != 0)) return accumulate ? TPERM_ERR_KERNEL : TPERM_ERR_ALIGN;
+    if (p.vec2 && (accumulate || ((a | b) & pair_mask) != 0))
+        return accumulate ? TPERM_ERR_KERNEL : TPERM_ERR_ALIGN;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;
     // accumulating kernels exist for the default workgroup size and store mode only
@@ -299,8 +301,8 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t* plan, int rank, const i
     if (st != TPERM_OK) return st;
     st = wrap(p, plan);
     if (st != TPERM_OK) return st;
-    if (elem_size == 4) {
-        // the same candidate moving pairs, for 8-byte aligned pointers (as tperm_plan_create)
+    {
+        // the same candidate moving pairs, for suitably aligned pointers (as tperm_plan_create)
         Plan* w = nullptr;
         if (tperm::create_plan_with_candidate(&w, rank, dims, perm, elem_size, cands[index], true) ==
             TPERM_OK) {
@@ -414,7 +416,7 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t* plan, int rank, const in
     }
     const auto cands = trimmed(tperm::enumerate_candidates(c, (int)elem_size));
     if (cands.empty()) return TPERM_ERR_KERNEL;
-    const bool try_vec2 = elem_size == 4 && ((a | b) & 7u) == 0;
+    const bool try_vec2 = ((a | b) & (2u * (uintptr_t)elem_size - 1u)) == 0;
     Plan* p = nullptr;
     st = measure_best(rank, dims, perm, elem_size, cands, in, out, hip_stream, &p, try_vec2);
     if (st != TPERM_OK) return st;

@@ -807,7 +807,12 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     {
         const int q = c.perm[0];
         const int nreg2 = pick_nreg(cand.tile_vol / 2, threads);
-        if (opts.vec2 == 1 && elem == 4 && cand.use_lds && !align_out && threads == 256 && q != 0 &&
+        // 8-byte elements in 16-byte accesses: measured neutral to +1 % on ragged shapes, +6 %
+        // on small line-aligned tensors (few tiles per workgroup), but -2 to -5 % on large
+        // line-aligned ones, which do better with single elements (and loads first).
+        const double rounds = (double)d.num_tiles / (256.0 * std::max(2.0, std::min(8.0, std::round(20480.0 / ((double)cand.tile_vol * elem)))));
+        const bool worth_it = elem == 4 || !cand.aligned || rounds < 16.0;
+        if (opts.vec2 == 1 && worth_it && cand.use_lds && !align_out && threads == 256 && q != 0 &&
             nreg2 > 0 && c.dims[0] % 2 == 0 && c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 &&
             cand.t[q] % 2 == 0 && dim_of_in[0] == 0 && dim_of_out[0] == q) {
             TileDim& a = d.in_order[0];

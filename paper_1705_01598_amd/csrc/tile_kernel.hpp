@@ -124,6 +124,22 @@ template <int NT> struct Elem<uint64_t, NT> {
 // branches around them the only safe wait is for everything, stores included.
 constexpr uint32_t kDroppedOffset = 0xFFFFFF00u;
 
+// 16-byte accesses: two 8-byte elements at once (vec2 plans of 8-byte problems); never
+// accumulated.
+struct Pair64 {};
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int NT> struct Elem<Pair64, NT> {
+    typedef u32x4 reg;
+    static __device__ __forceinline__ reg add(reg a, reg) { return a; }
+    static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
+    }
+    static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
+                                                 uint32_t soff) {
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
+    }
+};
+
 // Raw (untyped, unstrided) buffer resource over `bytes` bytes starting at p.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -136,12 +152,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
-    // VEC2 (4-byte elements only): a slot is a pair of elements, moved through global memory
-    // with 8-byte accesses; the LDS image stays in single elements.
-    static_assert(!VEC2 || (sizeof(T) == 4 && USE_LDS && !ALIGN && !ACC), "vec2 is a 4-byte LDS-staged form");
-    typedef Elem<typename std::conditional<VEC2, uint64_t, T>::type, NT> io;
+    // VEC2: a slot is a pair of elements, moved through global memory with one access of
+    // twice the element size; the LDS image stays in single elements.
+    static_assert(!VEC2 || (USE_LDS && !ALIGN && !ACC), "vec2 is a plain LDS-staged form");
+    typedef typename std::conditional<sizeof(T) == 4, uint64_t, Pair64>::type pair_t;
+    typedef Elem<typename std::conditional<VEC2, pair_t, T>::type, NT> io;
     typedef typename io::reg reg_t;
-    typedef typename std::conditional<VEC2, uint32_t, reg_t>::type lds_t;
+    typedef typename Elem<T, NT>::reg lds_t;  // one element
     extern __shared__ __align__(16) unsigned char smem_raw[];
     lds_t* lds = reinterpret_cast<lds_t*>(smem_raw);
     const uint32_t tid = threadIdx.x;
@@ -278,8 +295,13 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                 if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) {
                     if constexpr (VEC2) {
                         // neighbours along input dim 0 are neighbours in the image
-                        img[lds_pos[j] & 0xFFFFu] = v[j].x;
-                        img[(lds_pos[j] & 0xFFFFu) + 1u] = v[j].y;
+                        if constexpr (sizeof(T) == 4) {
+                            img[lds_pos[j] & 0xFFFFu] = v[j].x;
+                            img[(lds_pos[j] & 0xFFFFu) + 1u] = v[j].y;
+                        } else {
+                            img[lds_pos[j] & 0xFFFFu] = lds_t{v[j].x, v[j].y};
+                            img[(lds_pos[j] & 0xFFFFu) + 1u] = lds_t{v[j].z, v[j].w};
+                        }
                     } else {
                         img[lds_pos[j] & 0xFFFFu] = v[j];
                     }
@@ -300,8 +322,14 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                     if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) {
                         if constexpr (VEC2) {
                             // neighbours along output dim 0 are pair_lstride apart
-                            w[j].x = img[lds_pos[j] >> 16];
-                            w[j].y = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                            if constexpr (sizeof(T) == 4) {
+                                w[j].x = img[lds_pos[j] >> 16];
+                                w[j].y = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                            } else {
+                                const lds_t lo = img[lds_pos[j] >> 16];
+                                const lds_t hi = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                                w[j] = reg_t{lo.x, lo.y, hi.x, hi.y};
+                            }
                         } else {
                             w[j] = img[lds_pos[j] >> 16];
                         }
@@ -387,8 +415,8 @@ static const void* tile_kernel_ptr(int nreg) {
 template <typename T, int THREADS>
 static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc,
                                       bool loads_first, bool vec2) {
-    if constexpr (THREADS == 256 && sizeof(T) == 4) {
-        // pairs of 4-byte elements: LDS-staged, stores first
+    if constexpr (THREADS == 256) {
+        // pairs of elements: LDS-staged, stores first
         if (vec2) {
             if (!use_lds || align || acc) return nullptr;
             if (nt == 1) return tile_kernel_ptr<T, 256, true, 1, false, false, false, true>(nreg);

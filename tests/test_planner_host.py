@@ -149,12 +149,12 @@ def test_pairing_of_four_byte_elements():
         assert np.array_equal(a[m], oracle.transpose(a, dims, perm))
 
 
-def test_vec2_plans_for_four_byte_transposes():
-    """4-byte plans that transpose even-extent leading dims move pairs; the map they execute,
-    evaluated on the host, is the oracle's."""
+def test_vec2_plans_move_pairs():
+    """Plans that transpose even-extent leading dims move pairs of elements; the map they
+    execute, evaluated on the host, is the oracle's."""
     d = lambda dims, perm, e, **kw: B.tperm_plan_create_ex(dims, perm, e, **kw).describe()
     assert d((64, 48), (1, 0), 4).vec2 == 1
-    assert d((64, 48), (1, 0), 8).vec2 == 0            # 8-byte elements
+    assert d((64, 48), (1, 0), 8).vec2 == 1            # 8-byte elements: 16-byte accesses
     assert d((63, 48), (1, 0), 4).vec2 == 0            # odd input leading extent
     assert d((64, 47), (1, 0), 4).vec2 == 0            # odd output leading extent
     assert d((64, 48), (1, 0), 4, vec2=1).vec2 == 0    # switched off
@@ -170,10 +170,11 @@ def test_vec2_plans_for_four_byte_transposes():
             perm[0], perm[1] = perm[1], perm[0]
         dims[0] = 2 * int(rng.integers(1, 40))
         dims[perm[0]] = 2 * int(rng.integers(1, 40))
+        elem = int(rng.choice([4, 8]))
         for kw in ({}, dict(vec2=2), dict(vec2=2, kernel_class=B.KERNEL_PACKED, m=1, tile_in=int(2 * rng.integers(1, 9)),
                                           k=1, tile_out=int(2 * rng.integers(1, 9)))):
             try:
-                plan = B.tperm_plan_create_ex(dims, perm, 4, **kw)
+                plan = B.tperm_plan_create_ex(dims, perm, elem, **kw)
             except B.TpermError as e:
                 assert e.status == B.ERR_KERNEL
                 continue
