@@ -123,7 +123,12 @@ tperm_status_t tperm_plan_create_ex(tperm_plan_t* plan, int rank, const int64_t*
         if (opts) o = *opts;
         o.vec2 = 2;
         Plan* w = nullptr;
-        if (tperm::create_plan(&w, rank, dims, perm, elem_size, &o) == TPERM_OK) {
+        // without options the twin reuses the candidate already chosen (no second search)
+        const tperm_status_t ws =
+            opts == nullptr
+                ? tperm::create_plan_with_candidate(&w, rank, dims, perm, elem_size, p->cand, true)
+                : tperm::create_plan(&w, rank, dims, perm, elem_size, &o);
+        if (ws == TPERM_OK) {
             if (w->vec2) (*plan)->wide.p = w;
             else delete w;
         }
