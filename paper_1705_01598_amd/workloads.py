@@ -257,3 +257,51 @@ def set2(n_random: int = 500) -> List[Case]:
 def square_sweep() -> List[Case]:
     """Figure 8 shapes: fp32 square matrices with side 13952..13968."""
     return [make_case(7, s - 13952, (s, s), (1, 0), 4, f"side{s}") for s in range(13952, 13969)]
+
+
+def contraction_cases(n_cases: int = 24, target_volume: int = 1 << 24) -> list:
+    """Seeded sample of binary tensor contractions D += L * R in the style of the paper's
+    contraction benchmark (Section 3.4): tensors of rank up to 8, contracted and uncontracted
+    dimensions at random places, a few large dimensions and every other extent 8, sizes scaled
+    so that the largest of the three tensors has about `target_volume` elements.
+
+    Each case is a dict: name, seed, d / l / r (label strings, first label = stride-1
+    dimension) and extents (label -> extent).  Stands in for the paper's 9306-contraction
+    sample, which is not reproduced."""
+    rng = np.random.default_rng(SEED_BASE + 8_000_000)
+    labels = "abcdefghijklmnop"
+    cases = []
+    while len(cases) < n_cases:
+        nc = int(rng.integers(1, 4))               # contracted dims
+        fl = int(rng.integers(1, 5))               # uncontracted dims of L
+        fr = int(rng.integers(1, 5))
+        if fl + nc > 8 or fr + nc > 8 or fl + fr > 8:
+            continue
+        ls = labels[:fl]
+        rs = labels[fl:fl + fr]
+        cs = labels[fl + fr:fl + fr + nc]
+        ext = {c: 8 for c in ls + rs + cs}
+        # up to two large dims in each group
+        large = []
+        for grp in (ls, rs, cs):
+            k = int(rng.integers(1, min(2, len(grp)) + 1))
+            large += list(rng.choice(list(grp), size=k, replace=False))
+        for c in large:
+            ext[c] = int(rng.integers(16, 97))
+        vol = lambda s: int(np.prod([ext[c] for c in s], dtype=np.int64))
+        # scale the large extents so that the largest tensor is close to the target
+        for _ in range(40):
+            big = max(vol(ls + rs), vol(ls + cs), vol(cs + rs))
+            if 0.7 * target_volume <= big <= 1.4 * target_volume:
+                break
+            f = (target_volume / big) ** (1.0 / max(1, len(large)))
+            for c in large:
+                ext[c] = max(2, min(4096, int(round(ext[c] * f))))
+        big = max(vol(ls + rs), vol(ls + cs), vol(cs + rs))
+        if not (0.4 * target_volume <= big <= 2.5 * target_volume):
+            continue
+        shuffle = lambda s: "".join(rng.permutation(list(s)))
+        case = {"name": f"k{len(cases):02d}_r{fl + fr}{fl + nc}{fr + nc}", "seed": int(SEED_BASE % (1 << 31)) + len(cases),
+                "d": shuffle(ls + rs), "l": shuffle(ls + cs), "r": shuffle(cs + rs), "extents": dict(ext)}
+        cases.append(case)
+    return cases
