@@ -1,5 +1,5 @@
-// HIP kernels for gfx950 (MI355X): the tile kernel that every staged transpose class runs
-// through, the plain copy and the naive gather.
+// HIP device code for gfx950 (MI355X): the tile kernel that every staged transpose class
+// runs through.
 //
 // Tile kernel, per workgroup (256 threads = 4 wavefronts of 64):
 //   prologue  every thread evaluates, once, the minor positions (Eqs. (4)-(6)) of the
@@ -8,8 +8,9 @@
 //             16-lane DPP row holds term j, a row_shr scan adds them, v_readlane moves the
 //             sum into scalar registers (the wave64 form of the paper's Algorithm 1);
 //             global -> registers -> LDS (input order), barrier, LDS (output order) ->
-//             registers -> global.  The loads of the next tile are issued before the
-//             stores of the current one so reads stay in flight all the time.
+//             registers -> global.  The loads of the next tile are issued back to back
+//             with the stores of the current one, so reads are in flight while the tile
+//             is finished; which of the two goes first is a plan choice (see the loop).
 // This header holds the device code; tile_inst_*.hip instantiate it per element type and
 // workgroup size so that the units compile in parallel.
 #pragma once
