@@ -195,18 +195,76 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                 rd_mask[j] = si.xa | (si.xb << 16);
                 lds_pos[j] |= si.loff;
             }
-        } else if (k < d.tile_vol) {
-            const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
-            wr_off[j] = so.goff * (uint32_t)sizeof(T);
-            wr_mask[j] = so.xa | (so.xb << 16);
+        }
+    }
+    if (!ALIGN) {
+        // Slots walk the tile dims in groups of up to four: each dim's constants are fetched
+        // once per group (scalar loads) and the group's independent digit steps overlap,
+        // instead of one dependent chain per slot that waits for the same loads again.
+        // Larger groups would raise the register peak of the kernel above the main loop's.
+        constexpr int G = NREG <= 4 ? NREG : (NREG % 4 == 0 ? 4 : 3);
+        static_assert(NREG % G == 0, "slot groups must tile the slots");
+#pragma unroll
+        for (int g0 = 0; g0 < NREG; g0 += G) {
+            uint32_t rem[G], loff_o[G], loff_i[G];
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                rem[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
+                wr_off[g0 + jj] = 0;
+                wr_mask[g0 + jj] = 0;
+                loff_o[jj] = 0;
+                loff_i[jj] = 0;
+            }
+            // write side (output order); LDS-free kernels read the same slots through ostride
+            for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
+                const TileDim td = d.out_order[i];
+                const uint32_t mask_shift = td.sel == 2u ? 16u + td.xshift : td.xshift;
+#pragma unroll
+                for (int jj = 0; jj < G; ++jj) {
+                    const int j = g0 + jj;
+                    const uint32_t q = fdiv(rem[jj], td.div);
+                    const uint32_t x = rem[jj] - q * td.ext;
+                    rem[jj] = q;
+                    wr_off[j] += x * td.gstride;
+                    if (USE_LDS) loff_o[jj] += x * td.lstride;
+                    else rd_off[j] += x * td.ostride;
+                    if (td.sel != 0u) wr_mask[j] |= x << mask_shift;
+                }
+            }
             if (USE_LDS) {
-                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
-                rd_off[j] = si.goff * (uint32_t)sizeof(T);
-                rd_mask[j] = si.xa | (si.xb << 16);
-                lds_pos[j] = si.loff | (so.loff << 16);
-            } else {
-                rd_off[j] = so.ooff * (uint32_t)sizeof(T);
-                rd_mask[j] = wr_mask[j];
+#pragma unroll
+                for (int jj = 0; jj < G; ++jj) {
+                    rem[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
+                    rd_mask[g0 + jj] = 0;
+                }
+                for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
+                    const TileDim td = d.in_order[i];
+                    const uint32_t mask_shift = td.sel == 2u ? 16u + td.xshift : td.xshift;
+#pragma unroll
+                    for (int jj = 0; jj < G; ++jj) {
+                        const int j = g0 + jj;
+                        const uint32_t q = fdiv(rem[jj], td.div);
+                        const uint32_t x = rem[jj] - q * td.ext;
+                        rem[jj] = q;
+                        rd_off[j] += x * td.gstride;
+                        loff_i[jj] += x * td.lstride;
+                        if (td.sel != 0u) rd_mask[j] |= x << mask_shift;
+                    }
+                }
+            }
+#pragma unroll
+            for (int jj = 0; jj < G; ++jj) {
+                const int j = g0 + jj;
+                const bool used = tid + (uint32_t)j * THREADS < d.tile_vol;
+                wr_off[j] = used ? wr_off[j] * (uint32_t)sizeof(T) : 0u;
+                rd_off[j] = used ? rd_off[j] * (uint32_t)sizeof(T) : 0u;
+                wr_mask[j] = used ? wr_mask[j] : 0xFFFFFFFFu;
+                if (USE_LDS) {
+                    rd_mask[j] = used ? rd_mask[j] : 0xFFFFFFFFu;
+                    lds_pos[j] = used ? (loff_i[jj] | (loff_o[jj] << 16)) : 0u;
+                } else {
+                    rd_mask[j] = wr_mask[j];
+                }
             }
         }
     }
