@@ -206,49 +206,45 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         static_assert(NREG % G == 0, "slot groups must tile the slots");
 #pragma unroll
         for (int g0 = 0; g0 < NREG; g0 += G) {
-            uint32_t rem[G], loff_o[G], loff_i[G];
+            uint32_t rem_o[G], rem_i[G], loff_o[G], loff_i[G];
 #pragma unroll
             for (int jj = 0; jj < G; ++jj) {
-                rem[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
+                rem_o[jj] = rem_i[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
                 wr_off[g0 + jj] = 0;
                 wr_mask[g0 + jj] = 0;
+                rd_mask[g0 + jj] = 0;
                 loff_o[jj] = 0;
                 loff_i[jj] = 0;
             }
-            // write side (output order); LDS-free kernels read the same slots through ostride
+            // Entry i of both orders in one pass: the write side (output order; LDS-free
+            // kernels read the same slots through ostride) and, with an LDS stage, the read
+            // side (input order).
             for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
-                const TileDim td = d.out_order[i];
-                const uint32_t mask_shift = td.sel == 2u ? 16u + td.xshift : td.xshift;
+                const TileDim to = d.out_order[i];
+                const uint32_t shift_o = to.sel == 2u ? 16u + to.xshift : to.xshift;
 #pragma unroll
                 for (int jj = 0; jj < G; ++jj) {
                     const int j = g0 + jj;
-                    const uint32_t q = fdiv(rem[jj], td.div);
-                    const uint32_t x = rem[jj] - q * td.ext;
-                    rem[jj] = q;
-                    wr_off[j] += x * td.gstride;
-                    if (USE_LDS) loff_o[jj] += x * td.lstride;
-                    else rd_off[j] += x * td.ostride;
-                    if (td.sel != 0u) wr_mask[j] |= x << mask_shift;
+                    const uint32_t q = fdiv(rem_o[jj], to.div);
+                    const uint32_t x = rem_o[jj] - q * to.ext;
+                    rem_o[jj] = q;
+                    wr_off[j] += x * to.gstride;
+                    if (USE_LDS) loff_o[jj] += x * to.lstride;
+                    else rd_off[j] += x * to.ostride;
+                    if (to.sel != 0u) wr_mask[j] |= x << shift_o;
                 }
-            }
-            if (USE_LDS) {
-#pragma unroll
-                for (int jj = 0; jj < G; ++jj) {
-                    rem[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
-                    rd_mask[g0 + jj] = 0;
-                }
-                for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
-                    const TileDim td = d.in_order[i];
-                    const uint32_t mask_shift = td.sel == 2u ? 16u + td.xshift : td.xshift;
+                if (USE_LDS) {
+                    const TileDim ti = d.in_order[i];
+                    const uint32_t shift_i = ti.sel == 2u ? 16u + ti.xshift : ti.xshift;
 #pragma unroll
                     for (int jj = 0; jj < G; ++jj) {
                         const int j = g0 + jj;
-                        const uint32_t q = fdiv(rem[jj], td.div);
-                        const uint32_t x = rem[jj] - q * td.ext;
-                        rem[jj] = q;
-                        rd_off[j] += x * td.gstride;
-                        loff_i[jj] += x * td.lstride;
-                        if (td.sel != 0u) rd_mask[j] |= x << mask_shift;
+                        const uint32_t q = fdiv(rem_i[jj], ti.div);
+                        const uint32_t x = rem_i[jj] - q * ti.ext;
+                        rem_i[jj] = q;
+                        rd_off[j] += x * ti.gstride;
+                        loff_i[jj] += x * ti.lstride;
+                        if (ti.sel != 0u) rd_mask[j] |= x << shift_i;
                     }
                 }
             }
