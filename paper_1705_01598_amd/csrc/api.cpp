@@ -172,9 +172,8 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
         return accumulate ? TPERM_ERR_KERNEL : TPERM_ERR_ALIGN;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;
-    // accumulating kernels exist for the default workgroup size and store mode only
-    if (accumulate && (p.align_out || (p.threads != 256 && p.kclass != TPERM_KERNEL_COPY &&
-                                       p.kclass != TPERM_KERNEL_NAIVE)))
+    // accumulating kernels exist for the default workgroup size only
+    if (accumulate && p.threads != 256 && p.kclass != TPERM_KERNEL_COPY && p.kclass != TPERM_KERNEL_NAIVE)
         return TPERM_ERR_KERNEL;
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t err = hipSuccess;

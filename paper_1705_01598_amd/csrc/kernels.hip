@@ -86,7 +86,7 @@ accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
 static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_aligned_out) {
     // plan policy 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
     int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : 0));
-    if (!sector_aligned_out) nt = 0;
+    if (!sector_aligned_out && !plan.align_out) nt = 0;  // aligned windows follow the pointer's phase
     const bool align = plan.align_out;
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)

@@ -216,6 +216,21 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     const double rin = (double)(cd->use_lds ? run_in : cd->t[0]) * elem;
     const double rout = (double)run_out * elem;
     double gin = granule(true), gout = granule(false);
+    // Line-aligned output windows: the leading output dim is cut into chunks of whole lines
+    // and every row shifts its window to line boundaries, at the price of a halo of one
+    // line's worth of coordinates on the read side.  Only where rows are misaligned.
+    const int q0 = c.perm[0];
+    const int64_t line_elems = 128 / elem;
+    int64_t read_vol = vol;
+    if (cd->align) {
+        if (!cd->use_lds || q0 == 0 || cd->k != 1 || cd->t[q0] >= c.dims[q0] ||
+            cd->t[q0] % line_elems != 0 || gout >= 128.0)
+            return false;
+        read_vol = vol / cd->t[q0] * (cd->t[q0] + line_elems);
+        if (read_vol > 16 * TPERM_MAX_THREADS) return false;  // beyond 16 slots the kernel's registers allow one workgroup per CU only
+        if (read_vol * elem > kMaxLdsBytes - 8192) return false;
+        gout = 128.0;
+    }
     if (!cd->use_lds) {
         // rows are read in output-lane order: contiguous only along dim 0
         gin = (double)gcd64(128, (r > 1 ? sI[1] : 1) * elem);
@@ -230,6 +245,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // Eq. (13)), input runs are flat from 128 bytes on (overhead worth 16 bytes).
     double cost_in = (rin + 16.0 + 0.5 * (128.0 - gin)) / rin;
     if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
+    if (cd->align) cost_in *= 1.0 + kAlignHaloWeight * std::pow((double)line_elems / (double)cd->t[q0], kAlignHaloPower);
     const double cost_out = (rout + 128.0 + 2.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
     // Tile size, by slots per thread of a 256-thread workgroup: a table fitted with the rest.
@@ -242,10 +258,9 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     static const double kWeight4[10] = {1.4, 1.0, 1.0, 0.8, 1.0, 1.0, 1.0, 1.0, 1.06, 1.1};
     // A 4-byte candidate that can move its elements in pairs (see build_tile_plan) has half
     // the slots and behaves like the 8-byte kernel of the same tile bytes.
-    const int q0 = c.perm[0];
-    const bool pairs = elem == 4 && cd->use_lds && q0 != 0 && c.dims[0] % 2 == 0 &&
+    const bool pairs = elem == 4 && cd->use_lds && !cd->align && q0 != 0 && c.dims[0] % 2 == 0 &&
                        c.dims[q0] % 2 == 0 && cd->t[0] % 2 == 0 && cd->t[q0] % 2 == 0;
-    const int64_t slots_needed = pairs ? vol / 2 : vol;
+    const int64_t slots_needed = pairs ? vol / 2 : read_vol;
     const int64_t need = (slots_needed + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
     int bucket = 9;
     for (int i = 0; i < 10; ++i)
@@ -265,6 +280,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     cost *= 1.0 + 4.0 / std::max(rounds, 4.0);
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.1;
+    if (cd->align) cost *= kAlignWeight;
     // Tiny tensors (a few rounds of tiles at most) are bound by latency, not bandwidth: what
     // counts is how long one workgroup needs for its tiles, about 1 us per slot of a thread
     // and a little more per tile dim (the prologue evaluates every slot's position), spread
@@ -332,13 +348,14 @@ static std::vector<SideChoice> side_choices(const Canonical& c, const int* order
 }
 
 bool make_candidate(const Canonical& c, int elem, int m, int64_t tile_in, int k,
-                    int64_t tile_out, bool use_lds, Candidate* out) {
+                    int64_t tile_out, bool use_lds, Candidate* out, bool align) {
     const int r = c.rank;
     if (m < 1 || m > r || k < 1 || k > r) return false;
     Candidate cd;
     cd.m = m;
     cd.k = k;
     cd.use_lds = use_lds;
+    cd.align = align;
     for (int z = 0; z < r; ++z) cd.t[z] = 1;
     for (int z = 0; z < m - 1; ++z) cd.t[z] = c.dims[z];
     const int za = m - 1;
@@ -369,7 +386,7 @@ std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem) {
     const auto outs = side_choices(c, c.perm);
     auto push = [&](const Candidate& cd) {
         for (const auto& o : out) {
-            if (o.use_lds != cd.use_lds) continue;
+            if (o.use_lds != cd.use_lds || o.align != cd.align) continue;
             bool same = true;
             for (int z = 0; z < c.rank; ++z) same &= (o.t[z] == cd.t[z]);
             if (same) return;
@@ -380,6 +397,9 @@ std::vector<Candidate> enumerate_candidates(const Canonical& c, int elem) {
         for (const auto& b : outs) {
             Candidate cd;
             if (make_candidate(c, elem, a.count, a.last, b.count, b.last, true, &cd)) push(cd);
+            // the same tile with line-aligned output windows, where that form applies
+            if (b.count == 1 && make_candidate(c, elem, a.count, a.last, b.count, b.last, true, &cd, true))
+                push(cd);
         }
     if (c.perm[0] == 0) {
         // LDS-free row copy: the tile is taken in output order only
@@ -487,26 +507,6 @@ static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* di
     return cum;
 }
 
-// Same for an LDS image kept in OUTPUT order: the first `run_dims` output dims of the tile
-// (one output run) are contiguous, the remaining dims ("rows") follow with a padded pitch.
-static uint32_t set_lds_strides_out(TileDesc* d, const int* dim_of_in, const int* dim_of_out,
-                                    int run_dims, uint32_t pad) {
-    uint32_t lstride[TPERM_DESC_MAX_DIMS];
-    uint32_t cum = 1;
-    const uint32_t n = d->n_tile_dims;
-    for (uint32_t j = 0; j < n; ++j) {
-        if ((int)j == run_dims && run_dims > 0) cum += pad;
-        lstride[j] = cum;
-        cum *= d->out_order[j].ext;
-        d->out_order[j].lstride = lstride[j];
-        if ((int)j >= run_dims) d->oa.rows[j - run_dims].lstride = lstride[j];
-    }
-    for (uint32_t i = 0; i < n; ++i)
-        for (uint32_t j = 0; j < n; ++j)
-            if (dim_of_out[j] == dim_of_in[i]) d->in_order[i].lstride = lstride[j];
-    return cum;
-}
-
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts) {
     const int lds_pad = opts.lds_pad, grid_mode = opts.grid_mode, window_in = opts.window_in,
               window_out = opts.window_out, threads = opts.threads, lds_buffers = opts.lds_buffers;
@@ -531,16 +531,32 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
             if (s >= 2) return TPERM_ERR_KERNEL;
             split_dim[s++] = z;
         }
+    // Line-aligned output windows (see OutAlign): the output's leading dimension q0 is cut
+    // into chunks of whole lines, every row shifts its window down to a line boundary, and the
+    // read side covers a halo of one line's worth of coordinates in front of the chunk.
+    const int q0 = c.perm[0];
+    const int64_t line_elems = 128 / elem;
+    bool align_out = false;
+    if ((opts.align_out == 2 || (opts.align_out == 0 && cand.align)) && cand.use_lds && threads == 256 &&
+        q0 != 0 && cand.k == 1 && cand.t[q0] < c.dims[q0] &&
+        cand.t[q0] >= line_elems && cand.t[q0] % line_elems == 0 &&
+        cand.t[q0] + line_elems <= 0x7FFF &&
+        (c.volume + line_elems * sI[q0]) * elem + 512 < ((int64_t)1 << 32) - 256) {
+        align_out = true;
+        // the shifted dimension is always split dim B
+        if (split_dim[0] == q0) std::swap(split_dim[0], split_dim[1]);
+    }
     auto sel_of = [&](int z) -> uint32_t {
         return z == split_dim[0] ? 1u : (z == split_dim[1] ? 2u : 0u);
     };
-    // tile dims in input order and in output order
+    // tile dims in input order and in output order; with aligned windows the read side sees
+    // the shifted dimension with its halo, the write side without
     int dim_of_in[TPERM_DESC_MAX_DIMS], dim_of_out[TPERM_DESC_MAX_DIMS];
     uint32_t n = 0;
     for (int z = 0; z < r; ++z)
         if (cand.t[z] > 1) {
             TileDim& td = d.in_order[n];
-            td.ext = (uint32_t)cand.t[z];
+            td.ext = (uint32_t)(cand.t[z] + (align_out && z == q0 ? line_elems : 0));
             td.div = make_fastdiv(td.ext);
             td.gstride = (uint32_t)sI[z];
             td.ostride = (uint32_t)sO[inv[z]];
@@ -561,10 +577,23 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         }
     }
     d.n_tile_dims = n;
-    d.tile_vol = (uint32_t)cand.tile_vol;
+    // read-side slots (with the halo); the write side has cand.tile_vol slots
+    const int64_t read_vol = align_out ? cand.tile_vol / cand.t[q0] * (cand.t[q0] + line_elems) : cand.tile_vol;
+    if (read_vol > kMaxTileVol) return TPERM_ERR_KERNEL;
+    d.tile_vol = (uint32_t)read_vol;
     for (int s = 0; s < 2; ++s) {
         d.split_ext[s] = split_dim[s] >= 0 ? (uint32_t)c.dims[split_dim[s]] : 0u;
         d.split_tile[s] = split_dim[s] >= 0 ? (uint32_t)cand.t[split_dim[s]] : 0u;
+        d.split_step[s] = d.split_tile[s];
+        d.split_halo[s] = 0;
+    }
+    if (align_out) {
+        // coordinates of the shifted dimension are counted from the halo origin: the first
+        // line_elems of them do not exist, tiles are t + line_elems wide and t apart
+        d.split_ext[1] = (uint32_t)(c.dims[q0] + line_elems);
+        d.split_tile[1] = (uint32_t)(cand.t[q0] + line_elems);
+        d.split_step[1] = (uint32_t)cand.t[q0];
+        d.split_halo[1] = (uint32_t)line_elems;
     }
     // Major terms.  The order of the lanes is the order in which the tile index b walks the
     // tiles, and with it which tiles run at the same time.  A "window" of up to window_in
@@ -592,7 +621,8 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         if (cand.t[z] >= c.dims[z]) continue;
         MDim m;
         m.z = z;
-        m.count = (uint32_t)ceil_div(c.dims[z], cand.t[z]);
+        // shifted windows reach up to line_elems - 1 short of the chunk's nominal end
+        m.count = (uint32_t)ceil_div(c.dims[z] + (align_out && z == q0 ? line_elems - 1 : 0), cand.t[z]);
         m.sin = (uint64_t)cand.t[z] * sI[z];
         m.sout = (uint64_t)cand.t[z] * sO[inv[z]];
         m.split = z == split_dim[0] ? 0 : (z == split_dim[1] ? 1 : -1);
@@ -703,55 +733,18 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     if (cum >= ((uint64_t)1 << 31)) return TPERM_ERR_KERNEL;
     d.num_tiles = (uint32_t)cum;  // includes the non-existent combinations of split counters
 
-    // Line-aligned stores: worth it when output runs do not sit on line boundaries.
-    int orun_dims = 0;
-    for (uint32_t j = 0; j < n; ++j) {
-        if (dim_of_out[j] != c.perm[j]) break;
-        ++orun_dims;
-        if (cand.t[dim_of_out[j]] < c.dims[dim_of_out[j]]) break;
-    }
-    bool align_out = false;
     std::memset(&d.oa, 0, sizeof(d.oa));
-    d.oa.run_split = d.oa.other_split = 2;
-    // Measured on MI355X this mode gains 1-3 % when output runs are long and loses up to
-    // 20 % when the padded rows push the slot count up, so it is only used on request.
-    if (cand.use_lds && orun_dims > 0 && opts.align_out == 2 && threads == 256) {
-        OutAlign& oa = d.oa;
-        oa.line_elems = 128u / (uint32_t)elem;
-        uint32_t run_len = 1;
-        for (int j = 0; j < orun_dims; ++j) run_len *= d.out_order[j].ext;
-        oa.run_len = run_len;
-        oa.slots_per_row = (run_len + 2 * oa.line_elems - 2) / oa.line_elems * oa.line_elems;
-        oa.slots_div = make_fastdiv(oa.slots_per_row);
-        const int z_last = dim_of_out[orun_dims - 1];
-        if (cand.t[z_last] < c.dims[z_last]) {
-            oa.run_split = z_last == split_dim[0] ? 0u : 1u;
-            oa.run_prefix = run_len / (uint32_t)cand.t[z_last];
-        }
-        for (int sidx = 0; sidx < 2; ++sidx)
-            if (split_dim[sidx] >= 0 && (uint32_t)sidx != oa.run_split) oa.other_split = (uint32_t)sidx;
-        uint32_t rows = 1;
-        oa.n_row_dims = n - (uint32_t)orun_dims;
-        for (uint32_t j = (uint32_t)orun_dims; j < n; ++j) {
-            TileDim td = d.out_order[j];
-            td.sel = (oa.other_split < 2u && dim_of_out[j] == split_dim[oa.other_split]) ? 1u : 0u;
-            oa.rows[j - orun_dims] = td;
-            rows *= td.ext;
-        }
-        oa.total_slots = rows * oa.slots_per_row;
-        if ((int64_t)oa.total_slots <= (int64_t)kMaxNreg * threads &&
-            pick_nreg(std::max<int64_t>(cand.tile_vol, oa.total_slots), threads) > 0) {
-            oa.enabled = 1;
-            align_out = true;
-        }
+    if (align_out) {
+        d.oa.enabled = 1;
+        d.oa.line_elems = (uint32_t)line_elems;
+        d.oa.total_slots = (uint32_t)cand.tile_vol;
+        d.oa.in_halo_elems = (uint32_t)(line_elems * sI[q0]);
     }
-    const int nreg = pick_nreg(align_out ? std::max<int64_t>(cand.tile_vol, d.oa.total_slots)
-                                         : cand.tile_vol, threads);
+    const int nreg = pick_nreg(read_vol, threads);
     if (nreg < 0) return TPERM_ERR_KERNEL;
 
-    // LDS image.  Default: tile in input order, rows of the contiguous input run separated
-    // by a padded pitch.  With line-aligned stores: output order, rows = output runs.  The
-    // pad is chosen to minimise the bank conflicts of the strided side.
+    // LDS image: tile in input order, rows of the contiguous input run separated by a padded
+    // pitch.  The pad is chosen to minimise the bank conflicts of the strided side.
     int run_dims = 0;
     for (uint32_t i = 0; i < n; ++i) {
         // dims of the run are the leading canonical dims 0,1,..: tile dim i belongs to
@@ -760,11 +753,8 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         ++run_dims;
         if (cand.t[i] < c.dims[i]) break;
     }
-    auto lay = [&](uint32_t p) {
-        return align_out ? set_lds_strides_out(&d, dim_of_in, dim_of_out, orun_dims, p)
-                         : set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, p);
-    };
-    const int layout_run_dims = align_out ? orun_dims : run_dims;
+    auto lay = [&](uint32_t p) { return set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, p); };
+    const int layout_run_dims = run_dims;
     int pad = 0;
     uint32_t lds_elems = 0;
     if (cand.use_lds) {
@@ -798,6 +788,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         if (lds_elems + 64u > 0xFFFFu) return TPERM_ERR_KERNEL;  // LDS slots are kept in 16 bits
     }
     d.lds_elems = lds_elems;
+    if (align_out) d.oa.lstride_b = d.out_order[0].lstride;
     d.lds_buffers = (cand.use_lds && lds_buffers == 2 && (int64_t)lds_elems * elem * 2 <= kMaxLdsBytes) ? 2u : 1u;
     // grid_mode values >= 2 carry the group size: mode 2 + log2(group) (2 -> groups of 1)
     d.grid_mode = grid_mode >= 2 ? 2u : (uint32_t)grid_mode;
@@ -861,10 +852,10 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         const double tile_bytes = (double)cand.tile_vol * elem;
         int bpc = (int)std::lround((cand.use_lds ? 20480.0 : 14336.0) / tile_bytes);
         plan->blocks_per_cu = std::max(2, std::min(8, bpc));
-        plan->cache_policy = cand.aligned ? 2 : (cand.store_nt ? 3 : 1);
+        plan->cache_policy = cand.aligned ? 2 : (cand.store_nt || align_out ? 3 : 1);  // aligned windows write whole lines
         // loads before stores pays on line-aligned shapes with small LDS-staged tiles only
         // (measured per case over all benchmark sets; see tile_kernel)
-        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6 && !plan->vec2;
+        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6 && !plan->vec2 && !align_out;
     }
     plan->lds_pad = pad;
     plan->align_out = align_out;
@@ -1013,7 +1004,9 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
 // host evaluation of a plan's index maps
 // ---------------------------------------------------------------------------------------
 
-tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
+// out_phase: what the kernel would see as (output pointer / element size) mod line_elems; only
+// plans with line-aligned output windows look at it.
+static tperm_status_t index_map_at_phase(const Plan& plan, int64_t* out_to_in, uint32_t out_phase) {
     const int64_t vol = plan.c.volume;
     for (int64_t i = 0; i < vol; ++i) out_to_in[i] = -1;
     if (plan.kclass == TPERM_KERNEL_COPY) {
@@ -1047,8 +1040,8 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
                 maj_in += (uint64_t)coord[l] * d.major.stride_in[l];
                 maj_out += (uint64_t)coord[l] * d.major.stride_out[l];
             }
-            uint32_t rem_a = 0, rem_b = 0;
-            tile_remaining(d, [&](uint32_t l) { return coord[l]; }, &rem_a, &rem_b);
+            uint32_t rem_a = 0, rem_b = 0, lo_b = 0;
+            tile_remaining(d, [&](uint32_t l) { return coord[l]; }, &rem_a, &rem_b, &lo_b);
             if (plan.use_lds && d.vec2) {
                 // pairs: two neighbours along input dim 0 in, two along output dim 0 out
                 std::fill(lds.begin(), lds.end(), -1);
@@ -1074,6 +1067,35 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
                         out_to_in[go] = lds[li];
                     }
                 }
+            } else if (plan.use_lds && d.oa.enabled) {
+                // line-aligned output windows: the read side covers the halo, every row of
+                // the write side shifts its window by its own phase
+                const OutAlign& oa = d.oa;
+                const uint32_t span_b = rem_b > lo_b ? rem_b - lo_b : 0u;
+                std::fill(lds.begin(), lds.end(), -1);
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.in_order, d.n_tile_dims, k);
+                    if (!(s.xa < rem_a && (s.xb - lo_b) < span_b)) continue;
+                    const int64_t gi = (int64_t)maj_in + (int64_t)s.goff - (int64_t)oa.in_halo_elems;
+                    if (gi < 0 || gi >= vol || s.loff >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                    if (lds[s.loff] != -1) return TPERM_ERR_INTERNAL;
+                    lds[s.loff] = gi;
+                }
+                const uint32_t phi = (uint32_t)((maj_out + out_phase) & (oa.line_elems - 1u));
+                for (uint32_t k = 0; k < oa.total_slots; ++k) {
+                    const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
+                    const uint32_t p = so.xb;                       // position in the chunk
+                    const uint32_t rho = (so.goff - p) & (oa.line_elems - 1u);
+                    const uint32_t shift = (phi + rho) & (oa.line_elems - 1u);
+                    const uint32_t xb = p + oa.line_elems - shift;  // tile coordinate written
+                    if (!(so.xa < rem_a && (xb - lo_b) < span_b)) continue;
+                    const int64_t go = (int64_t)maj_out + (int64_t)so.goff - (int64_t)shift;
+                    const int64_t li = (int64_t)so.loff + (int64_t)(oa.line_elems - shift) * oa.lstride_b;
+                    if (go < 0 || go >= vol || li < 0 || li >= (int64_t)d.lds_elems) return TPERM_ERR_INTERNAL;
+                    if (lds[li] == -1) return TPERM_ERR_INTERNAL;
+                    if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                    out_to_in[go] = lds[li];
+                }
             } else if (plan.use_lds) {
                 std::fill(lds.begin(), lds.end(), -1);
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {
@@ -1084,36 +1106,6 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
                     if (lds[s.loff] != -1) return TPERM_ERR_INTERNAL;
                     lds[s.loff] = (int64_t)gi;
                 }
-                if (d.oa.enabled) {
-                    // line-aligned stores: the phase the kernel derives from the output
-                    // pointer is taken as 0 here (any phase gives the same element map)
-                    const OutAlign& oa = d.oa;
-                    const uint32_t rems[2] = {rem_a, rem_b};
-                    const bool exists = rem_a != 0u && rem_b != 0u;
-                    const uint32_t lout_rem = !exists ? 0u
-                                              : (oa.run_split < 2u ? rems[oa.run_split] * oa.run_prefix
-                                                                   : oa.run_len);
-                    const uint32_t rem_other = oa.other_split < 2u ? rems[oa.other_split] : TPERM_NO_REM;
-                    for (uint32_t phase_try = 0; phase_try < 2; ++phase_try) {
-                        const uint32_t phi = (uint32_t)((maj_out + (phase_try ? 5u : 0u)) & (oa.line_elems - 1u));
-                        for (uint32_t k = 0; k < oa.total_slots; ++k) {
-                            const OutSlot o = out_slot(oa, k);
-                            const uint32_t q = (phi + o.rho) & (oa.line_elems - 1u);
-                            const uint32_t x = o.s - q;
-                            if (!(x < lout_rem && o.xo < rem_other)) continue;
-                            const uint64_t go = maj_out + o.goff - q;
-                            const uint32_t li = o.lpos - q;
-                            if (go >= (uint64_t)vol || li >= d.lds_elems) return TPERM_ERR_INTERNAL;
-                            if (lds[li] == -1) return TPERM_ERR_INTERNAL;
-                            if (phase_try == 0) {
-                                if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
-                                out_to_in[go] = lds[li];
-                            } else if (out_to_in[go] != lds[li]) {
-                                return TPERM_ERR_INTERNAL;  // a different phase must not change the map
-                            }
-                        }
-                    }
-                } else
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {
                     const Slot s = tile_slot(d.out_order, d.n_tile_dims, k);
                     if (!(s.xa < rem_a && s.xb < rem_b)) continue;
@@ -1138,6 +1130,21 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
         if (!tile_seen[b]) return TPERM_ERR_INTERNAL;
     // The map is in canonical coordinates; canonicalisation leaves scalar positions
     // unchanged, so it is also the map of the problem as given.
+    return TPERM_OK;
+}
+
+tperm_status_t index_map(const Plan& plan, int64_t* out_to_in) {
+    const tperm_status_t st = index_map_at_phase(plan, out_to_in, 0u);
+    if (st != TPERM_OK) return st;
+    if (plan.kclass != TPERM_KERNEL_COPY && plan.kclass != TPERM_KERNEL_NAIVE && plan.tile.oa.enabled) {
+        // which tile writes an element depends on the phase of the output pointer; the
+        // element map must not
+        std::vector<int64_t> other((size_t)plan.c.volume);
+        const tperm_status_t st2 = index_map_at_phase(plan, other.data(), 5u);
+        if (st2 != TPERM_OK) return st2;
+        for (int64_t i = 0; i < plan.c.volume; ++i)
+            if (other[(size_t)i] != out_to_in[i]) return TPERM_ERR_INTERNAL;
+    }
     return TPERM_OK;
 }
 

@@ -44,6 +44,8 @@ __device__ __forceinline__ uint32_t read_lane(uint32_t v, uint32_t lane) {
 struct MajorPos {
     uint32_t in, out;        // element offsets of the tile (wave-uniform)
     uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
+    uint32_t lo_b, span_b;   // line-aligned windows: coordinates lo_b <= x < lo_b + span_b
+                             // of split dim B exist in this tile
 };
 
 // One lane's term of the major sums, kept in registers for the whole kernel.
@@ -61,12 +63,19 @@ __device__ __forceinline__ MajorPos major_position(const TileDesc& d, const Majo
     MajorPos p;
     p.in = read_lane(sum_in, 15);
     p.out = read_lane(sum_out, 15);
-    tile_remaining(d, [&](uint32_t lane) { return read_lane(c, lane); }, &p.rem_a, &p.rem_b);
+    tile_remaining(d, [&](uint32_t lane) { return read_lane(c, lane); }, &p.rem_a, &p.rem_b, &p.lo_b);
+    p.span_b = p.rem_b > p.lo_b ? p.rem_b - p.lo_b : 0u;
     return p;
 }
 
 __device__ __forceinline__ bool slot_valid(uint32_t packed, uint32_t rem_a, uint32_t rem_b) {
     return ((packed & 0xFFFFu) < rem_a) && ((packed >> 16) < rem_b);
+}
+
+// The same with a lower bound on the coordinate along split dim B: lo_b <= x < lo_b + span_b.
+__device__ __forceinline__ bool slot_valid_from(uint32_t packed, uint32_t rem_a, uint32_t lo_b,
+                                                uint32_t span_b) {
+    return ((packed & 0xFFFFu) < rem_a) && (((packed >> 16) - lo_b) < span_b);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -163,47 +172,32 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     extern __shared__ __align__(16) unsigned char smem_raw[];
     lds_t* lds = reinterpret_cast<lds_t*>(smem_raw);
     const uint32_t tid = threadIdx.x;
-    const __amdgpu_buffer_rsrc_t rsrc_in = make_rsrc(in, nbytes);
-    const __amdgpu_buffer_rsrc_t rsrc_out = make_rsrc(out, nbytes);
+    // ALIGN (line-aligned output windows): tile coordinates along the shifted dimension count
+    // from a halo origin one line's worth of elements in front of the chunk, so both buffers
+    // are described from that far in front of the tensors; the slots that would fall before
+    // a tensor's first element are masked (lo_b).
+    const uint32_t halo_in = ALIGN ? d.oa.in_halo_elems * (uint32_t)sizeof(T) : 0u;
+    const uint32_t halo_out = ALIGN ? d.oa.line_elems * (uint32_t)sizeof(T) : 0u;
+    const __amdgpu_buffer_rsrc_t rsrc_in =
+        make_rsrc(reinterpret_cast<const char*>(in) - halo_in, nbytes + halo_in);
+    const __amdgpu_buffer_rsrc_t rsrc_out =
+        make_rsrc(reinterpret_cast<char*>(out) - halo_out, nbytes + halo_out);
 
     // minor positions of this thread's slots; global offsets are kept in BYTES
     uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
     uint32_t lds_pos[NREG];  // low half: slot written on the read side; high half: slot
                              // read on the write side
-    uint32_t wr_aux[NREG];   // line-aligned stores: position in the padded row | row phase << 16
-#pragma unroll
-    for (int j = 0; j < NREG; ++j) {
-        const uint32_t k = tid + (uint32_t)j * THREADS;
-        rd_off[j] = 0;
-        wr_off[j] = 0;
-        lds_pos[j] = 0;
-        rd_mask[j] = 0xFFFFFFFFu;  // coordinates no remaining extent exceeds: slot unused
-        wr_mask[j] = 0xFFFFFFFFu;
-        wr_aux[j] = 0xFFFFu;       // a row position beyond every run: slot unused
-        if (ALIGN) {
-            // write side: slot = (output row, position in the padded row)
-            if (k < d.oa.total_slots) {
-                const OutSlot o = out_slot(d.oa, k);
-                wr_off[j] = o.goff * (uint32_t)sizeof(T);
-                wr_mask[j] = o.xo;
-                wr_aux[j] = o.s | (o.rho << 16);
-                lds_pos[j] = o.lpos << 16;
-            }
-            if (k < d.tile_vol) {
-                const Slot si = tile_slot(d.in_order, d.n_tile_dims, k);
-                rd_off[j] = si.goff * (uint32_t)sizeof(T);
-                rd_mask[j] = si.xa | (si.xb << 16);
-                lds_pos[j] |= si.loff;
-            }
-        }
-    }
-    if (!ALIGN) {
+    uint32_t wr_aux[NREG];   // ALIGN: unshifted tile coordinate along the shifted dim |
+                             // phase of the row start << 16
+    {
         // Slots walk the tile dims in groups of up to four: each dim's constants are fetched
         // once per group (scalar loads) and the group's independent digit steps overlap,
         // instead of one dependent chain per slot that waits for the same loads again.
         // Larger groups would raise the register peak of the kernel above the main loop's.
         constexpr int G = NREG <= 4 ? NREG : (NREG % 4 == 0 ? 4 : 3);
         static_assert(NREG % G == 0, "slot groups must tile the slots");
+        // ALIGN: the write side has fewer slots than the read side (no halo)
+        const uint32_t write_slots = ALIGN ? d.oa.total_slots : d.tile_vol;
 #pragma unroll
         for (int g0 = 0; g0 < NREG; g0 += G) {
             uint32_t rem_o[G], rem_i[G], loff_o[G], loff_i[G];
@@ -211,6 +205,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             for (int jj = 0; jj < G; ++jj) {
                 rem_o[jj] = rem_i[jj] = tid + (uint32_t)(g0 + jj) * THREADS;
                 wr_off[g0 + jj] = 0;
+                rd_off[g0 + jj] = 0;
                 wr_mask[g0 + jj] = 0;
                 rd_mask[g0 + jj] = 0;
                 loff_o[jj] = 0;
@@ -251,13 +246,25 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
 #pragma unroll
             for (int jj = 0; jj < G; ++jj) {
                 const int j = g0 + jj;
-                const bool used = tid + (uint32_t)j * THREADS < d.tile_vol;
-                wr_off[j] = used ? wr_off[j] * (uint32_t)sizeof(T) : 0u;
-                rd_off[j] = used ? rd_off[j] * (uint32_t)sizeof(T) : 0u;
-                wr_mask[j] = used ? wr_mask[j] : 0xFFFFFFFFu;
-                if (USE_LDS) {
-                    rd_mask[j] = used ? rd_mask[j] : 0xFFFFFFFFu;
-                    lds_pos[j] = used ? (loff_i[jj] | (loff_o[jj] << 16)) : 0u;
+                const uint32_t k = tid + (uint32_t)j * THREADS;
+                const bool used_r = k < d.tile_vol, used_w = k < write_slots;
+                wr_aux[j] = 0;
+                if (ALIGN) {
+                    // p = position in the chunk (output stride 1); the slot reads the tile
+                    // coordinate p + line_elems - shift and stores that many elements on
+                    // from the halo origin, where shift is this row's phase in the tile
+                    const uint32_t p = wr_mask[j] >> 16;
+                    const uint32_t rho = (wr_off[j] - p) & (d.oa.line_elems - 1u);
+                    wr_aux[j] = used_w ? ((p + d.oa.line_elems) | (rho << 16)) : 0u;
+                    wr_off[j] += d.oa.line_elems;
+                    loff_o[jj] += d.oa.line_elems * d.oa.lstride_b;
+                }
+                wr_off[j] = used_w ? wr_off[j] * (uint32_t)sizeof(T) : 0u;
+                rd_off[j] = used_r ? rd_off[j] * (uint32_t)sizeof(T) : 0u;
+                wr_mask[j] = used_w ? wr_mask[j] : 0xFFFFFFFFu;  // coordinates no remaining
+                if (USE_LDS) {                                    // extent exceeds: unused
+                    rd_mask[j] = used_r ? rd_mask[j] : 0xFFFFFFFFu;
+                    lds_pos[j] = (used_r ? loff_i[jj] : 0u) | ((used_w ? loff_o[jj] : 0u) << 16);
                 } else {
                     rd_mask[j] = wr_mask[j];
                 }
@@ -278,14 +285,19 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     uint32_t b = tile_of(d, block, grid, it);
     reg_t v[NREG];
     MajorPos pos, nxt;
-    pos.in = pos.out = pos.rem_a = pos.rem_b = 0;
+    pos.in = pos.out = pos.rem_a = pos.rem_b = pos.lo_b = pos.span_b = 0;
     nxt = pos;
+    // does read-side slot j exist in tile t
+    auto read_ok = [&](int j, const MajorPos& t) {
+        return ALIGN ? slot_valid_from(rd_mask[j], t.rem_a, t.lo_b, t.span_b)
+                     : slot_valid(rd_mask[j], t.rem_a, t.rem_b);
+    };
     if (b < d.num_tiles) {
         pos = major_position(d, ml, b);
         const uint32_t soff = pos.in * (uint32_t)sizeof(T);
 #pragma unroll
         for (int j = 0; j < NREG; ++j)
-            v[j] = io::load(rsrc_in, slot_valid(rd_mask[j], pos.rem_a, pos.rem_b) ? rd_off[j] : kDroppedOffset, soff);
+            v[j] = io::load(rsrc_in, read_ok(j, pos) ? rd_off[j] : kDroppedOffset, soff);
     }
     // As many dropped stores as a tile has real ones: every pass through the loop below then
     // starts with the same queue of memory operations behind it (one tile of loads, one of
@@ -301,22 +313,27 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     const MajorPos no_tile = nxt;  // all zero: no slot is valid
     if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
     const bool two_buffers = d.lds_buffers == 2u;
-    // line-aligned stores: phase of the output base pointer within a 128-byte line
+    // line-aligned windows: phase of the output base pointer within a 128-byte line
     const uint32_t line_mask = ALIGN ? d.oa.line_elems - 1u : 0u;
     const uint32_t out_phase =
         ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
     while (b < d.num_tiles) {
         reg_t w[NREG];
-        uint32_t shift[NREG];     // ALIGN: this tile's lane shift of each slot's row
-        uint32_t lout_rem = 0, rem_other = 0, phi = 0;
-        if (ALIGN) {
-            const bool exists = pos.rem_a != 0u && pos.rem_b != 0u;
-            const uint32_t run_rem = d.oa.run_split == 0u ? pos.rem_a : pos.rem_b;
-            lout_rem = !exists ? 0u : (d.oa.run_split < 2u ? run_rem * d.oa.run_prefix : d.oa.run_len);
-            rem_other = d.oa.other_split == 0u ? pos.rem_a
-                                               : (d.oa.other_split == 1u ? pos.rem_b : TPERM_NO_REM);
-            phi = (out_phase + pos.out) & line_mask;
-        }
+        // Write side of this tile: byte offset of every slot, or kDroppedOffset.  ALIGN: the
+        // slot's row starts `shift` elements past a line boundary (phase of the tile origin +
+        // phase of the row within the tile), so the slot moves down by that much, in the
+        // output and in the LDS image alike.
+        const uint32_t phi = ALIGN ? (out_phase + pos.out) & line_mask : 0u;
+        auto row_shift = [&](int j) { return (phi + (wr_aux[j] >> 16)) & line_mask; };
+        auto write_at = [&](int j) -> uint32_t {
+            if (ALIGN) {
+                const uint32_t sh = row_shift(j);
+                const uint32_t xb = (wr_aux[j] & 0xFFFFu) - sh;
+                const bool ok = ((wr_mask[j] & 0xFFFFu) < pos.rem_a) && ((xb - pos.lo_b) < pos.span_b);
+                return ok ? wr_off[j] - sh * (uint32_t)sizeof(T) : kDroppedOffset;
+            }
+            return slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset;
+        };
         // The reads of the next tile and the stores of this one are issued back to back after
         // the barrier and the LDS reads, so that all waves of the workgroup ask for their
         // rows together (issuing the reads before the barrier, each wave on its own, measured
@@ -338,7 +355,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                v[j] = io::load(rsrc_in, slot_valid(rd_mask[j], nxt.rem_a, nxt.rem_b) ? rd_off[j] : kDroppedOffset, soff);
+                v[j] = io::load(rsrc_in, read_ok(j, nxt) ? rd_off[j] : kDroppedOffset, soff);
         };
         if (USE_LDS) {
             // with two LDS images the tiles alternate between them and one barrier per
@@ -347,7 +364,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             lds_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                if (slot_valid(rd_mask[j], pos.rem_a, pos.rem_b)) {
+                if (read_ok(j, pos)) {
                     if constexpr (VEC2) {
                         // neighbours along input dim 0 are neighbours in the image
                         if constexpr (sizeof(T) == 4) {
@@ -363,18 +380,16 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                 }
             __syncthreads();
             if (ALIGN) {
+                if constexpr (!VEC2) {
 #pragma unroll
-                for (int j = 0; j < NREG; ++j) {
-                    shift[j] = (phi + (wr_aux[j] >> 16)) & line_mask;
-                    const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                    if constexpr (!VEC2)
-                        if (x < lout_rem && wr_mask[j] < rem_other)
-                            w[j] = img[(lds_pos[j] >> 16) - shift[j]];
+                    for (int j = 0; j < NREG; ++j)
+                        if (write_at(j) != kDroppedOffset)
+                            w[j] = img[(lds_pos[j] >> 16) - row_shift(j) * d.oa.lstride_b];
                 }
             } else {
 #pragma unroll
                 for (int j = 0; j < NREG; ++j)
-                    if (slot_valid(wr_mask[j], pos.rem_a, pos.rem_b)) {
+                    if (write_at(j) != kDroppedOffset) {
                         if constexpr (VEC2) {
                             // neighbours along output dim 0 are pair_lstride apart
                             if constexpr (sizeof(T) == 4) {
@@ -405,22 +420,12 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             reg_t old[NREG];
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
-                old[j] = io::load(rsrc_out, slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset, soff_out);
+                old[j] = io::load(rsrc_out, write_at(j), soff_out);
 #pragma unroll
             for (int j = 0; j < NREG; ++j) w[j] = io::add(old[j], w[j]);
         }
-        if (ALIGN) {
 #pragma unroll
-            for (int j = 0; j < NREG; ++j) {
-                const uint32_t x = (wr_aux[j] & 0xFFFFu) - shift[j];
-                const bool ok = x < lout_rem && wr_mask[j] < rem_other;
-                io::store(w[j], rsrc_out, ok ? wr_off[j] - shift[j] * (uint32_t)sizeof(T) : kDroppedOffset, soff_out);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                io::store(w[j], rsrc_out, slot_valid(wr_mask[j], pos.rem_a, pos.rem_b) ? wr_off[j] : kDroppedOffset, soff_out);
-        }
+        for (int j = 0; j < NREG; ++j) io::store(w[j], rsrc_out, write_at(j), soff_out);
         if (!LOADS_FIRST) issue_next_loads();
         b = bn;
         pos = nxt;
@@ -463,8 +468,8 @@ static const void* tile_kernel_ptr(int nreg) {
     return nullptr;
 }
 
-// nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores.  The
-// line-aligned-store and 64-thread variants exist for policies 0 and 2 only (1 runs as 2).
+// nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores.  The 64-thread
+// variants exist for policies 0 and 2 only (1 runs as 2).
 // loads_first: order of the next tile's loads and this tile's stores (see the kernel); both
 // orders exist for the plain 256-thread kernels, elsewhere stores go first.
 template <typename T, int THREADS>
@@ -481,14 +486,18 @@ static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align
     }
     if (vec2) return nullptr;
     if constexpr (THREADS == 256) {
+        if (align && !use_lds) return nullptr;
         if (acc) {
-            if (nt != 0 || align) return nullptr;
+            if (nt != 0) return nullptr;
+            if (align) return tile_kernel_ptr<T, 256, true, 0, true, true>(nreg);
             return use_lds ? tile_kernel_ptr<T, 256, true, 0, false, true>(nreg)
                            : tile_kernel_ptr<T, 256, false, 0, false, true>(nreg);
         }
-        if (use_lds && align)
+        if (align) {
+            if (nt == 1) return tile_kernel_ptr<T, 256, true, 1, true, false>(nreg);
             return nt != 0 ? tile_kernel_ptr<T, 256, true, 2, true, false>(nreg)
                            : tile_kernel_ptr<T, 256, true, 0, true, false>(nreg);
+        }
         if (loads_first) {
             if (nt == 1)
                 return use_lds ? tile_kernel_ptr<T, 256, true, 1, false, false, true>(nreg)

@@ -63,53 +63,24 @@ struct SplitPair {
     uint32_t lane_lo, lane_hi, width, count;
 };
 
-// Line-aligned stores.  When output runs do not start on 128-byte lines, the write side can
-// enumerate its slots as (output row, position in a padded row) and shift every row by its
-// own phase so that lane l always stores to an address congruent to l modulo one line: each
-// group of 16 lanes (fp64; 32 for fp32) then writes exactly one line.  The LDS image is kept
-// in OUTPUT order in this mode, so a row's elements are consecutive in LDS as well.
+// Line-aligned output windows.  When the rows of the output are not aligned to 128-byte lines,
+// a tile that writes the same index range [c t, (c+1) t) of the output's leading dimension in
+// every row starts and ends each row piece inside a line, and partially written lines are what
+// the memory system handles worst.  In this mode every row writes the window
+// [c t - s, (c+1) t - s) instead, with s in [0, line_elems) chosen per row so that the window
+// starts on a line boundary; t is a multiple of line_elems, so it ends on one too, and the
+// windows of consecutive chunks still tile the row.  The data for the shifted windows comes
+// from a halo: on the read side the tile covers line_elems extra coordinates in front,
+// [c t - line_elems, (c+1) t), which the neighbouring tile reads as well (from cache, mostly).
+// That dimension is always split dim B here; its tile coordinate x stands for the output
+// coordinate c t - line_elems + x, valid when lo <= x < remaining (see tile_remaining).
 struct OutAlign {
     uint32_t enabled;
-    uint32_t line_elems;     // elements per 128-byte line
-    uint32_t run_len;        // elements of one output run inside a full tile
-    uint32_t slots_per_row;  // run_len + line_elems - 1, rounded up to whole lines
-    FastDiv slots_div;
-    uint32_t n_row_dims;
-    uint32_t total_slots;    // rows * slots_per_row
-    uint32_t run_split;      // 0 / 1: split dim A / B is the last dim of the run; 2: none
-    uint32_t run_prefix;     // run elements per unit of that split dim's coordinate
-    uint32_t other_split;    // 0 / 1: split dim that is a row dim; 2: none
-    TileDim rows[TPERM_DESC_MAX_DIMS];  // row dims, output order (gstride = output stride)
+    uint32_t line_elems;     // elements per 128-byte line (the halo width)
+    uint32_t total_slots;    // write-side slots of a tile: rows * t
+    uint32_t lstride_b;      // LDS stride of the shifted dimension
+    uint32_t in_halo_elems;  // input elements between the tensor base and the halo origin
 };
-
-// One write-side slot in line-aligned mode.
-struct OutSlot {
-    uint32_t goff;   // output element offset of (row start + s), relative to the major offset
-    uint32_t lpos;   // LDS index of (row start + s)
-    uint32_t s;      // position in the padded row
-    uint32_t rho;    // (row start offset) mod line_elems
-    uint32_t xo;     // coordinate along the split dim that is a row dim (0 if none)
-};
-
-TPERM_HD OutSlot out_slot(const OutAlign& a, uint32_t k) {
-    OutSlot o;
-    const uint32_t r = fdiv(k, a.slots_div);
-    o.s = k - r * a.slots_per_row;
-    uint32_t rem = r, g = 0, l = 0;
-    o.xo = 0;
-    for (uint32_t i = 0; i < a.n_row_dims; ++i) {
-        const uint32_t q = fdiv(rem, a.rows[i].div);
-        const uint32_t x = rem - q * a.rows[i].ext;
-        rem = q;
-        g += x * a.rows[i].gstride;
-        l += x * a.rows[i].lstride;
-        if (a.rows[i].sel != 0u) o.xo = x;
-    }
-    o.rho = g & (a.line_elems - 1u);
-    o.goff = g + o.s;
-    o.lpos = l + o.s;
-    return o;
-}
 
 // Descriptor of the generic tile kernel (Tiled, Packed, PackedSplit and the LDS-free
 // row-copy all reduce to it).
@@ -119,7 +90,11 @@ struct TileDesc {
     uint32_t n_tile_dims;
     uint32_t n_major;       // terms in use in `major` (the rest are neutral)
     uint32_t split_ext[2];  // full extent d of split dim A / B (0 if none)
-    uint32_t split_tile[2]; // tile extent t of split dim A / B
+    uint32_t split_tile[2]; // tile extent of split dim A / B
+    uint32_t split_step[2]; // distance of consecutive chunk origins (= split_tile unless the
+                            // tiles overlap: line-aligned output windows)
+    uint32_t split_halo[2]; // leading coordinates of the dim that do not exist (the halo in
+                            // front of the first chunk); 0 normally
     uint32_t lds_elems;     // size of one LDS image (with padding), elements
     uint32_t lds_buffers;   // 1, or 2: tiles alternate between two images (one barrier per tile)
     uint32_t vec2;          // 1: 4-byte elements move in pairs (8-byte global accesses): entry 0
@@ -174,9 +149,9 @@ TPERM_HD uint32_t major_coord(const MajorDims& m, uint32_t lane, uint32_t b) {
 }
 
 // Remaining extent of a split dim in the chunk with counter `chunk` (ragged last chunk).
-TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t chunk) {
+TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t step, uint32_t chunk) {
     if (full_ext == 0u) return TPERM_NO_REM;
-    const uint32_t start = chunk * tile_ext;
+    const uint32_t start = chunk * step;
     if (start >= full_ext) return 0u;
     const uint32_t left = full_ext - start;
     return left < tile_ext ? left : tile_ext;
@@ -184,9 +159,11 @@ TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t
 
 // From the per-lane coordinates of a tile (coord(l) returns lane l's coordinate): does the
 // tile exist, and what is left of the split dims in it.  A tile that does not exist gets
-// remaining extents of 0, which masks every slot.
+// remaining extents of 0, which masks every slot.  lo_b: first valid coordinate of split dim B
+// in this tile (non-zero only in the first chunk of a dim with a halo).
 template <typename CoordFn>
-TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, uint32_t* rem_b) {
+TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, uint32_t* rem_b,
+                             uint32_t* lo_b) {
     bool exists = true;
     uint32_t counter[2] = {0u, 0u};
     for (int p = 0; p < 2; ++p)
@@ -196,8 +173,10 @@ TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, 
         }
     const uint32_t chunk_a = d.chunk_pair[0] < 2u ? counter[d.chunk_pair[0]] : coord(d.lane_a);
     const uint32_t chunk_b = d.chunk_pair[1] < 2u ? counter[d.chunk_pair[1]] : coord(d.lane_b);
-    *rem_a = exists ? split_remaining(d.split_ext[0], d.split_tile[0], chunk_a) : 0u;
-    *rem_b = exists ? split_remaining(d.split_ext[1], d.split_tile[1], chunk_b) : 0u;
+    *rem_a = exists ? split_remaining(d.split_ext[0], d.split_tile[0], d.split_step[0], chunk_a) : 0u;
+    *rem_b = exists ? split_remaining(d.split_ext[1], d.split_tile[1], d.split_step[1], chunk_b) : 0u;
+    const uint32_t start_b = chunk_b * d.split_step[1];
+    *lo_b = d.split_halo[1] > start_b ? d.split_halo[1] - start_b : 0u;
 }
 
 // Tile visited by workgroup `block` of `grid` on its i-th iteration, or num_tiles if done.

@@ -127,6 +127,51 @@ def test_line_aligned_stores_match_oracle(dims, perm, offset, align_out, elem):
     _check(case, plan, offset=offset)
 
 
+ALIGNED_WINDOW_TILES = [
+    # dims, perm, m, tile_in, k, tile_out (tile_out in lines of 128 bytes): misaligned output rows
+    ((257, 331), (1, 0), 1, 32, 1, 2),          # several chunks, ragged last window
+    ((101, 1003), (1, 0), 1, 16, 1, 4),
+    ((70, 45, 333), (2, 1, 0), 1, 16, 1, 2),     # rows from two other dims
+    ((7, 9, 400, 3), (2, 0, 1, 3), 2, 9, 1, 1),  # packed input run, one line per chunk
+    ((37, 130, 5), (1, 0, 2), 1, 37, 1, 2),      # the shifted dim is the only split dim
+    ((64, 200), (1, 0), 1, 64, 1, 1),
+]
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("offset", [0, 1, 7, 15, 16, 31])
+@pytest.mark.parametrize("dims,perm,m,tin,k,lines", ALIGNED_WINDOW_TILES)
+def test_line_aligned_windows_match_oracle(dims, perm, m, tin, k, lines, offset, elem):
+    """Line-aligned output windows (halo on the read side, every row shifted to whole lines),
+    with the output base pointer at several phases inside a cache line."""
+    case = wl.make_case(0, 21, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, m=m, tile_in=tin, k=k,
+                                  tile_out=lines * (128 // elem), align_out=2, cache_policy=1 + offset % 3)
+    assert plan.describe().align_out == 1
+    _check(case, plan, offset=offset)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("dims,perm", [((4001, 3777), (1, 0)), ((1001, 15, 1003), (2, 1, 0))])
+def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
+    """Misaligned low-rank transposes: the selector takes the aligned-window form by itself;
+    plain execution and accumulation both go through it."""
+    case = wl.make_case(0, 22, dims, perm, elem)
+    plan = B.tperm_plan_create(dims, perm, elem)
+    assert plan.describe().align_out == 1, B.info_dict(plan.describe())
+    _check(case, plan, offset=3)
+    a = wl.uniform_values(case)
+    b = wl.uniform_values(wl.make_case(0, 23, dims, perm, elem)) * 3
+    a_dev, b_dev = to_device(a), to_device(b)
+    B.tperm_execute_accumulate(plan, a_dev.data_ptr(), b_dev.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = np_uint(b_dev.cpu().numpy())
+    ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
+    assert np.array_equal(got, ref)
+    plan.destroy()
+
+
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("threads", [64, 256])
 @pytest.mark.parametrize("lds_buffers", [1, 2])

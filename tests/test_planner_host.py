@@ -246,6 +246,27 @@ def test_index_maps_of_every_gpu_test_plan():
                         tile_out=tout, grid_mode=gm)
 
 
+def test_line_aligned_windows_maps():
+    """Aligned-window plans (halo on the read side, rows shifted to whole lines): the element
+    map is the transpose, whatever the phase of the output pointer (the library evaluates the
+    map at two phases and compares them itself)."""
+    import test_gpu_parity as G
+    for elem in (8, 4):
+        for dims, perm, m, tin, k, lines in G.ALIGNED_WINDOW_TILES:
+            plan = _map_ok(dims, perm, elem, m=m, tile_in=tin, k=k, tile_out=lines * (128 // elem), align_out=2)
+            info = plan.describe()
+            assert info.align_out == 1
+            # the read side carries one line's worth of halo coordinates along the chunk
+            assert info.nreg * info.threads >= math.prod(t for t in B.info_dict(info)["tile"])
+    # the selector takes the form by itself for misaligned low-rank transposes of 8-byte elements ...
+    assert _map_ok((4001, 3777), (1, 0), 8).describe().align_out == 1
+    # ... and not when rows are line-aligned or the leading output dim is short
+    assert _map_ok((4096, 3072), (1, 0), 8).describe().align_out == 0
+    assert _map_ok((9, 11, 13, 12, 7), (4, 3, 2, 1, 0), 8).describe().align_out == 0
+    # switched off on request
+    assert B.tperm_plan_create_ex((4001, 3777), (1, 0), 8, align_out=1).describe().align_out == 0
+
+
 def test_index_maps_all_perms_small_grid():
     n = 0
     for dims in [(5, 4, 3), (2, 7, 3, 2), (3, 3, 3, 3), (2, 2, 3, 2, 2), (6, 1, 5, 2), (37, 11),
