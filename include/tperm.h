@@ -84,7 +84,10 @@ typedef struct {
                         /* input run are kept together)                                       */
     int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
     int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
-    int align_out;      /* line-aligned stores: 0 = default (off), 1 = off, 2 = on            */
+    int align_out;      /* line-aligned output windows (tiles read a one-line halo along the  *
+                         * output's leading dim, every row writes a window shifted to whole  *
+                         * 128-byte lines): 0 = the selector decides, 1 = off, 2 = on where   *
+                         * the tile allows it (k = 1, tile_out a multiple of one line)        */
     int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
     int loads_first;    /* order in which a workgroup issues the next tile's loads and this  *
                          * tile's stores: 0 = selector's default; 1 = stores first; 2 = loads *
@@ -120,7 +123,7 @@ typedef struct {
     double score;                          /* selector's estimate (relative, lower = better)*/
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
     int cache_policy;                      /* 1 = cached, 2 = nontemporal, 3 = nt stores    */
-    int align_out;                         /* 1 if stores are issued line-aligned           */
+    int align_out;                         /* 1 if the plan writes line-aligned windows     */
     int paired;                            /* 1: a 4-byte problem whose stride-1 dimension  *
                                             * stays in front and has an even extent is run  *
                                             * as the 8-byte problem with that extent halved *
