@@ -28,13 +28,17 @@ constexpr int kDefaultLdsBuffers = 1;
 constexpr int kDefaultGridMode = 2 + 5;
 constexpr int kDefaultTileOrder = 1;  // output-major: +1-4 % measured over input-major
 // Score of a candidate with line-aligned output windows, fitted to the measured times of all
-// candidates of 87 ragged benchmark cases (both halves of the sample give the same constants;
-// picks land at 97.9 % of the best candidate against 95.7 % without this form): the halo makes
-// the reads cost (1 + 1.5 (line / chunk)^1.5) as much, the rest costs 5 % less than the
-// granule terms of a line-aligned output say.
-constexpr double kAlignHaloWeight = 1.5;
+// candidates of 82 ragged benchmark cases that have such candidates (both halves of the sample
+// give the same constants; picks land at 97.6 % of the best candidate against 94.9 % without
+// this form): input runs keep paying off longer than in plain tiles (overhead worth 64 bytes
+// instead of 16: the rows it reads are the misaligned side now), the halo makes the reads cost
+// (1 + 3 (line / chunk)^1.5) as much, an output run costs a fixed 32 bytes on top of its
+// length, and the whole is 15 % cheaper than those terms say.
+constexpr double kAlignInOverhead = 64.0;
+constexpr double kAlignOutOverhead = 32.0;
+constexpr double kAlignHaloWeight = 3.0;
 constexpr double kAlignHaloPower = 1.5;
-constexpr double kAlignWeight = 0.95;
+constexpr double kAlignWeight = 0.85;
 
 // The per-thread slot counts the tile kernel is instantiated for, by workgroup size.
 // Returns the smallest instantiated count >= need, or -1.

@@ -159,7 +159,7 @@ def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
     plain execution and accumulation both go through it."""
     case = wl.make_case(0, 22, dims, perm, elem)
     plan = B.tperm_plan_create(dims, perm, elem)
-    assert plan.describe().align_out == 1, B.info_dict(plan.describe())
+    assert plan.describe().align_out == (1 if elem == 8 else 0), B.info_dict(plan.describe())
     _check(case, plan, offset=3)
     a = wl.uniform_values(case)
     b = wl.uniform_values(wl.make_case(0, 23, dims, perm, elem)) * 3
