@@ -172,6 +172,42 @@ def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
     plan.destroy()
 
 
+def _random_midsize_cases():
+    """Seeded shapes of 2-16 M elements, ranks 2-5, ragged extents: large enough for the
+    selector to use every form it has (aligned windows, pairs, row copies, big tiles)."""
+    rng = np.random.default_rng(20240607)
+    cases = []
+    while len(cases) < 24:
+        r = int(rng.integers(2, 6))
+        target = float(rng.uniform(21, 24))
+        logs = rng.dirichlet(np.ones(r) * 1.5) * target
+        dims = tuple(max(2, int(round(2 ** x)) + int(rng.integers(0, 3))) for x in logs)
+        if not (1 << 21) <= math.prod(dims) <= (1 << 24):
+            continue
+        perm = tuple(int(x) for x in rng.permutation(r))
+        if perm == tuple(range(r)):
+            continue
+        cases.append((dims, perm, int(rng.choice([4, 8])), int(rng.integers(0, 4)), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("dims,perm,elem,offset,accumulate", _random_midsize_cases())
+def test_random_midsize_shapes(dims, perm, elem, offset, accumulate):
+    case = wl.make_case(0, 31, dims, perm, elem)
+    plan = B.tperm_plan_create(dims, perm, elem)
+    if not accumulate:
+        _check(case, plan, offset=offset)
+    else:
+        a = wl.uniform_values(case)
+        b = wl.uniform_values(wl.make_case(0, 32, dims, perm, elem)) * 3
+        a_dev, b_dev = to_device(a), to_device(b)
+        B.tperm_execute_accumulate(plan, a_dev.data_ptr(), b_dev.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(np_uint(b_dev.cpu().numpy()), np_uint(oracle.transpose_accumulate(a, b, dims, perm))), \
+            B.info_dict(plan.describe())
+    plan.destroy()
+
+
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("threads", [64, 256])
 @pytest.mark.parametrize("lds_buffers", [1, 2])
