@@ -13,7 +13,7 @@
 int main(int argc, char** argv) {
     const int iters = argc > 1 ? atoi(argv[1]) : 400;
     std::mt19937_64 rng(12345);
-    int made = 0, rejected = 0;
+    int made = 0, rejected = 0, windows = 0;
     for (int it = 0; it < iters; ++it) {
         const int rank = 1 + (int)(rng() % 16);
         int64_t dims[TPERM_MAX_RANK];
@@ -27,10 +27,25 @@ int main(int argc, char** argv) {
             perm[z] = z;
         }
         for (int z = rank - 1; z > 0; --z) std::swap(perm[z], perm[rng() % (z + 1)]);
+        // every fourth problem of rank 2-4 gets a long leading output dim, so that the
+        // line-aligned window form (chunks of whole lines along it) can apply
+        const bool long_q0 = rank >= 2 && rank <= 4 && (it % 4) == 3 && perm[0] != 0;
+        if (long_q0) {
+            vol /= dims[perm[0]];
+            dims[perm[0]] = 40 + (int64_t)(rng() % 300);
+            for (int z = 0; z < rank && vol * dims[perm[0]] > 400000; ++z)
+                if (z != perm[0] && dims[z] > 1) {
+                    vol /= dims[z];
+                    dims[z] = 1 + dims[z] / 4;
+                    vol *= dims[z];
+                }
+            vol *= dims[perm[0]];
+        }
         tperm_plan_opts_t o;
         std::memset(&o, 0, sizeof(o));
         o.lds_pad = -1;
-        const int mode = (int)(rng() % 4);
+        const size_t elem = ((it / 4) & 1) ? 4 : 8;
+        const int mode = long_q0 ? 2 : (int)(rng() % 4);
         if (mode == 1) o.kernel_class = 1 + (int)(rng() % 5);
         if (mode >= 2) {
             o.kernel_class = TPERM_KERNEL_PACKED;
@@ -44,12 +59,20 @@ int main(int argc, char** argv) {
             o.threads = (rng() % 2) ? 64 : 256;
             o.lds_buffers = (int)(rng() % 3);
             o.align_out = (int)(rng() % 3);
+            if (long_q0) {
+                o.align_out = 2;
+                // make the line-aligned window form likely: one leading output dim in the
+                // tile, chunked in whole 128-byte lines
+                o.k = 1;
+                o.tile_out = (int64_t)(128 / (int)elem) * (1 + (int64_t)(rng() % 3));
+                o.threads = 256;
+                o.vec2 = 0;
+            }
             o.lds_pad = (int)(rng() % 8) - 1;
             o.vec2 = (int)(rng() % 3);
             o.loads_first = (int)(rng() % 3);
             o.tile_order = (int)(rng() % 3);
         }
-        const size_t elem = (rng() % 2) ? 4 : 8;
         tperm::Plan* p = nullptr;
         const tperm_status_t st = tperm::create_plan(&p, rank, dims, perm, elem, &o);
         if (st != TPERM_OK) {
@@ -74,9 +97,11 @@ int main(int argc, char** argv) {
             }
             seen[(size_t)map[(size_t)i]] = 1;
         }
+        if (p->align_out) ++windows;
         delete p;
         ++made;
     }
-    std::printf("ok: %d plans checked, %d option sets rejected\n", made, rejected);
+    std::printf("ok: %d plans checked (%d with line-aligned windows), %d option sets rejected\n", made, windows,
+                rejected);
     return 0;
 }
