@@ -79,7 +79,7 @@ struct Plan {
     int threads = TPERM_MAX_THREADS;  // workgroup size: 256 (four wavefronts) or 64 (one)
     int lds_pad = 0;
     int lds_bytes = 0;
-    bool align_out = false;  // line-aligned store mode in use
+    bool align_out = false;  // the plan writes line-aligned output windows
     int grid_mode = 0;
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
     bool vec2 = false;         // 4-byte elements move in pairs; needs 8-byte aligned pointers
@@ -109,7 +109,7 @@ struct TileBuildOpts {
     int window_in = kDefaultWindowIn, window_out = kDefaultWindow;
     int threads = kDefaultThreads;
     int lds_buffers = kDefaultLdsBuffers;
-    int align_out = 0;      // 0/1: off, 2: on where possible
+    int align_out = 0;      // line-aligned output windows: 0 = as the candidate says, 1 = off, 2 = on where the tile allows
     int tile_order = kDefaultTileOrder;  // 0: input-major, 1: output-major
     int vec2 = 0;           // 4-byte elements in pairs: 0 = off, 1 = where possible
 };
