@@ -77,7 +77,7 @@ typedef struct {
                         /* the XCDs in turn                                                   */
     int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
     int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal loads and stores; */
-                        /* 3 = nontemporal stores only                                        */
+                        /* 3 = nontemporal stores only; 4 = nontemporal loads only            */
     int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
     int window_out;     /* on the input / output side; 1 = no window; 0 = default (none on    */
                         /* the output side; on the input side only a few ragged chunks of the */
@@ -122,7 +122,8 @@ typedef struct {
     int lds_pad;
     double score;                          /* selector's estimate (relative, lower = better)*/
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
-    int cache_policy;                      /* 1 = cached, 2 = nontemporal, 3 = nt stores    */
+    int cache_policy;                      /* 1 = cached, 2 = nontemporal, 3 = nt stores,   *
+                                            * 4 = nt loads                                  */
     int align_out;                         /* 1 if the plan writes line-aligned windows     */
     int paired;                            /* 1: a 4-byte problem whose stride-1 dimension  *
                                             * stays in front and has an even extent is run  *

@@ -85,8 +85,9 @@ accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
 // inside sectors and the cached policy is the right one.
 static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_aligned_out) {
     // plan policy 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
-    int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : 0));
-    if (!sector_aligned_out && !plan.align_out) nt = 0;  // aligned windows follow the pointer's phase
+    int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : (plan.cache_policy == 4 ? 3 : 0)));
+    if (!sector_aligned_out && !plan.align_out) nt = (nt == 2 || nt == 3) ? 3 : 0;  // aligned windows follow the pointer's phase
+    if (nt == 3 && (plan.loads_first || plan.threads != 256)) nt = 0;
     const bool align = plan.align_out;
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)

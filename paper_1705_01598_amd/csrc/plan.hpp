@@ -61,6 +61,7 @@ struct Candidate {
     int64_t tile_vol = 0, run_in = 0, run_out = 0, num_tiles = 0;
     bool aligned = false;      // every run starts and ends on a 128-byte line boundary
     bool out_aligned = false;  // output runs start and end on line boundaries
+    bool load_nt = false;      // every input run starts and ends on a 128-byte line boundary
     bool store_nt = false;     // every written piece starts and ends on a 32-byte sector
     double utilisation = 1.0;  // useful fraction of the slots of all tiles (ragged edges)
     double score = 0.0;        // relative cost estimate, lower is better
@@ -84,7 +85,7 @@ struct Plan {
     int blocks_per_cu = 0;   // cap on resident workgroups per compute unit (0 = none)
     bool vec2 = false;         // 4-byte elements move in pairs; needs 8-byte aligned pointers
     bool loads_first = false;  // next tile's loads are issued before this tile's stores
-    int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
+    int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores, 4 = nontemporal loads
     TileDesc tile;
     NaiveDesc naive;
     // launch geometry, resolved on first execute (needs the device); 0 = not yet

@@ -87,7 +87,8 @@ __device__ __forceinline__ bool slot_valid_from(uint32_t packed, uint32_t rem_a,
 // address instead of two, no 64-bit vector adds, and the hardware drops any access past
 // the end of the tensor.  NT selects the cache policy: 0 = cached, 1 = nontemporal stores
 // (written lines are not worth a place in the caches once they are complete), 2 =
-// nontemporal loads as well (every byte is touched exactly once).
+// nontemporal loads as well (every byte is touched exactly once), 3 = nontemporal loads only
+// (line-aligned input, output pieces that end inside lines and want them kept in L2).
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -99,11 +100,11 @@ template <int NT> struct Elem<uint32_t, NT> {
         return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
     }
     static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, (NT == 2 || NT == 3) ? 2 : 0);
     }
     static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
                                                  uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
+        __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)voff, (int)soff, (NT == 1 || NT == 2) ? 2 : 0);
     }
 };
 template <int NT> struct Elem<uint64_t, NT> {
@@ -117,11 +118,11 @@ template <int NT> struct Elem<uint64_t, NT> {
         return r;
     }
     static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
+        return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, (NT == 2 || NT == 3) ? 2 : 0);
     }
     static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
                                                  uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, (NT == 1 || NT == 2) ? 2 : 0);
     }
 };
 
@@ -142,11 +143,11 @@ template <int NT> struct Elem<Pair64, NT> {
     typedef u32x4 reg;
     static __device__ __forceinline__ reg add(reg a, reg) { return a; }
     static __device__ __forceinline__ reg load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, NT == 2 ? 2 : 0);
+        return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, (NT == 2 || NT == 3) ? 2 : 0);
     }
     static __device__ __forceinline__ void store(reg v, __amdgpu_buffer_rsrc_t r, uint32_t voff,
                                                  uint32_t soff) {
-        __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, (int)soff, NT != 0 ? 2 : 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)voff, (int)soff, (NT == 1 || NT == 2) ? 2 : 0);
     }
 };
 
@@ -468,14 +469,22 @@ static const void* tile_kernel_ptr(int nreg) {
     return nullptr;
 }
 
-// nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores.  The 64-thread
-// variants exist for policies 0 and 2 only (1 runs as 2).
+// nt: 0 = cached, 1 = nontemporal stores, 2 = nontemporal loads and stores, 3 = nontemporal
+// loads.  The 64-thread variants exist for policies 0 and 2 only (1 runs as 2).
 // loads_first: order of the next tile's loads and this tile's stores (see the kernel); both
 // orders exist for the plain 256-thread kernels, elsewhere stores go first.
 template <typename T, int THREADS>
 static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc,
                                       bool loads_first, bool vec2) {
     if constexpr (THREADS == 256) {
+        if (nt == 3) {
+            // nontemporal loads only: plain stores-first forms
+            if (acc || loads_first) return nullptr;
+            if (vec2) return use_lds && !align ? tile_kernel_ptr<T, 256, true, 3, false, false, false, true>(nreg) : nullptr;
+            if (align) return use_lds ? tile_kernel_ptr<T, 256, true, 3, true, false>(nreg) : nullptr;
+            return use_lds ? tile_kernel_ptr<T, 256, true, 3, false, false>(nreg)
+                           : tile_kernel_ptr<T, 256, false, 3, false, false>(nreg);
+        }
         // pairs of elements: LDS-staged, stores first
         if (vec2) {
             if (!use_lds || align || acc) return nullptr;

@@ -120,7 +120,7 @@ def test_line_aligned_stores_match_oracle(dims, perm, offset, align_out, elem):
     case = wl.make_case(0, 12, dims, perm, elem)
     try:
         plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, align_out=align_out,
-                                      cache_policy=1 + offset % 3)
+                                      cache_policy=1 + offset % 4)
     except B.TpermError as e:
         assert e.status == B.ERR_KERNEL
         pytest.skip("no LDS-staged plan for this shape")
@@ -146,7 +146,7 @@ def test_line_aligned_windows_match_oracle(dims, perm, m, tin, k, lines, offset,
     with the output base pointer at several phases inside a cache line."""
     case = wl.make_case(0, 21, dims, perm, elem)
     plan = B.tperm_plan_create_ex(dims, perm, elem, m=m, tile_in=tin, k=k,
-                                  tile_out=lines * (128 // elem), align_out=2, cache_policy=1 + offset % 3)
+                                  tile_out=lines * (128 // elem), align_out=2, cache_policy=1 + offset % 4)
     assert plan.describe().align_out == 1
     _check(case, plan, offset=offset)
     plan.destroy()
@@ -169,6 +169,23 @@ def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
     got = np_uint(b_dev.cpu().numpy())
     ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
     assert np.array_equal(got, ref)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+def test_nontemporal_loads_only_policy(elem):
+    """Line-aligned input rows, misaligned output rows: the selector takes nontemporal loads with
+    cached stores (policy 4)."""
+    dims, perm = (1024, 1001), (1, 0)
+    case = wl.make_case(0, 24, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, align_out=1)
+    if elem == 8:
+        assert plan.describe().cache_policy == 4, B.info_dict(plan.describe())
+    else:
+        plan.destroy()
+        plan = B.tperm_plan_create_ex(dims, perm, elem, align_out=1, cache_policy=4)
+    _check(case, plan, offset=1)
+    _check(case, plan, offset=0)
     plan.destroy()
 
 
@@ -353,7 +370,7 @@ def test_vec2_plans(dims, perm, in_off, out_off, elem):
 
 @pytest.mark.parametrize("dims,perm,tin,tout", [((258, 130), (1, 0), 32, 32), ((258, 130), (1, 0), 100, 6),
                                                 ((70, 46, 34), (2, 1, 0), 14, 8), ((20, 7, 34, 6), (2, 1, 3, 0), 4, 10)])
-@pytest.mark.parametrize("cache_policy", [1, 2, 3])
+@pytest.mark.parametrize("cache_policy", [1, 2, 3, 4])
 @pytest.mark.parametrize("elem", [4, 8])
 def test_vec2_explicit_tiles(dims, perm, tin, tout, cache_policy, elem):
     case = wl.make_case(0, 14, dims, perm, elem)
