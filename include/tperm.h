@@ -178,6 +178,20 @@ tperm_status_t tperm_plan_create_measured(tperm_plan_t *plan, int rank, const in
                                           const int *perm, size_t elem_size, const void *in,
                                           void *out, void *hip_stream, int max_candidates);
 
+/* The same, timed as the data would arrive from HBM: `scratch` is caller-owned device memory
+ * (16-byte aligned, not overlapping in or out: TPERM_ERR_ALIGN / TPERM_ERR_ALIAS) of
+ * scratch_bytes bytes, ideally twice the last-level cache (512 MiB on MI355X).  Before every
+ * timed execution the library copies one half of it onto the other, outside the timed
+ * interval, which pushes the tensors out of the caches; its contents are overwritten.
+ * scratch == NULL behaves as tperm_plan_create_measured.  Use it for tensors that fit the
+ * last-level cache and will not be cache-resident when the plan is used.  Each candidate's
+ * fastest of five such runs counts.  (Kernels of a few tens of microseconds timed one by one
+ * still need not rank as they do inside a pipeline of launches.) */
+tperm_status_t tperm_plan_create_measured_cold(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                               const int *perm, size_t elem_size, const void *in,
+                                               void *out, void *hip_stream, int max_candidates,
+                                               void *scratch, size_t scratch_bytes);
+
 /* Enqueue the transpose on hip_stream (a hipStream_t; NULL = the default stream) and
  * return without synchronising.  in: device pointer to volume*elem_size bytes, read
  * only.  out: device pointer to volume*elem_size bytes, fully overwritten; must not

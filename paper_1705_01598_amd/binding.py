@@ -24,6 +24,7 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
                 KERNEL_TILED: "tiled", KERNEL_PACKED: "packed", KERNEL_NAIVE: "naive"}
 
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
+           "tperm_plan_create_measured_cold",
            "tperm_plan_candidate_count", "tperm_plan_create_candidate",
            "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes", "tperm_transpose", "tperm_transpose_accumulate",
@@ -81,6 +82,9 @@ def lib() -> ctypes.CDLL:
                                            ctypes.c_size_t, ctypes.POINTER(PlanOpts)]
         L.tperm_plan_create_measured.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
                                                  ctypes.c_size_t, vp, vp, vp, ctypes.c_int]
+        L.tperm_plan_create_measured_cold.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
+                                                      ctypes.c_size_t, vp, vp, vp, ctypes.c_int,
+                                                      vp, ctypes.c_size_t]
         L.tperm_plan_candidate_count.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, ip]
         L.tperm_plan_create_candidate.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
                                                   ctypes.c_size_t, ctypes.c_int]
@@ -184,6 +188,20 @@ def tperm_plan_create_measured(dims: Sequence[int], perm: Sequence[int], elem_si
                                           ctypes.c_void_p(stream), int(max_candidates))
     if st != OK:
         raise TpermError(st, "tperm_plan_create_measured")
+    return Plan(h)
+
+
+def tperm_plan_create_measured_cold(dims: Sequence[int], perm: Sequence[int], elem_size: int,
+                                    in_ptr: int, out_ptr: int, stream: int, scratch_ptr: int,
+                                    scratch_bytes: int, max_candidates: int = 0) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create_measured_cold(ctypes.byref(h), rank, cd, cp, int(elem_size),
+                                               ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                               ctypes.c_void_p(stream), int(max_candidates),
+                                               ctypes.c_void_p(scratch_ptr), int(scratch_bytes))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create_measured_cold")
     return Plan(h)
 
 

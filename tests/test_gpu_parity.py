@@ -446,6 +446,32 @@ def test_measured_plan_matches_oracle():
     assert guards and np.array_equal(got, np_uint(oracle.transpose(a, dims, perm)))
 
 
+@pytest.mark.parametrize("elem", [8, 4])
+def test_measured_cold_plan_matches_oracle(elem):
+    """Measurement-based selection with a scratch buffer swept between the timed runs."""
+    dims, perm = (64, 30, 129, 5), (2, 0, 3, 1)
+    case = wl.make_case(0, 25, dims, perm, elem)
+    a = wl.bitpattern_values(case)
+    a_dev = to_device(a)
+    out = torch.empty_like(a_dev)
+    sweep = torch.empty(8 << 20, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    plan = B.tperm_plan_create_measured_cold(dims, perm, elem, a_dev.data_ptr(), out.data_ptr(), stream,
+                                             sweep.data_ptr(), sweep.numel(), 16)
+    got, guards = run_plan(plan, a_dev, case.volume, elem)
+    assert guards and np.array_equal(got, np_uint(oracle.transpose(np_uint(a), dims, perm)))
+    plan.destroy()
+    # a scratch that overlaps a tensor, or is not 16-byte aligned, is refused
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_measured_cold(dims, perm, elem, a_dev.data_ptr(), out.data_ptr(), stream,
+                                          out.data_ptr() + 64, 4096, 4)
+    assert e.value.status == B.ERR_ALIAS
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_measured_cold(dims, perm, elem, a_dev.data_ptr(), out.data_ptr(), stream,
+                                          sweep.data_ptr() + 4, 4096, 4)
+    assert e.value.status == B.ERR_ALIGN
+
+
 def test_copy_bytes():
     n = 1 << 20
     a = torch.arange(n + 3, dtype=torch.int32, device="cuda")
