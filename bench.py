@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--plan", choices=["heuristic", "measured"], default="heuristic")
     ap.add_argument("--also-measured", action="store_true",
                     help="after the main pass, time the same step with measurement-selected plans")
+    ap.add_argument("--also-graph", action="store_true",
+                    help="additionally replay one step captured in a HIP graph (reported as graph_value)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cases-out", default="", help="write per-case results (JSON lines) here")
     return ap.parse_args()
@@ -261,6 +263,26 @@ def main():
             one_step(s)
         torch.cuda.synchronize()
         result["measured_plans_value"] = round(step_bytes * args.steps / (time.perf_counter() - t0) / 1e9, 1)
+    if args.also_graph:
+        # the same step as a HIP graph: what a caller with a fixed sequence of transposes gets
+        # once the gaps between dependent launches are gone (one buffer pair per launch as in
+        # the eager loop; the first use of every plan happened above, outside the capture)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            gs = torch.cuda.current_stream().cuda_stream
+            for i, plan in enumerate(plans):
+                a, b = pairs[i % n_pairs]
+                run(plan, a.data_ptr(), b.data_ptr(), gs)
+        for w in range(max(1, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["graph_value"] = round(step_bytes * args.steps / (time.perf_counter() - t0) / 1e9, 1)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cases)
     print(json.dumps(result))

@@ -472,6 +472,42 @@ def test_measured_cold_plan_matches_oracle(elem):
     assert e.value.status == B.ERR_ALIGN
 
 
+def test_launches_capture_into_a_hip_graph():
+    """A fixed sequence of transposes captured once and replayed: every replay, with eager work
+    and synchronisation in between, gives what the eager launches give (the library's launches
+    are plain kernel nodes: descriptor by value, no memset nodes)."""
+    problems = [((257, 131), (1, 0), 8), ((70, 45, 33), (2, 0, 1), 4), ((1001, 15, 203), (2, 1, 0), 8)]
+    plans, ins, outs, cases = [], [], [], []
+    for dims, perm, elem in problems:
+        case = wl.make_case(0, 26, dims, perm, elem)
+        cases.append(case)
+        plans.append(B.tperm_plan_create(dims, perm, elem))
+        ins.append(to_device(wl.bitpattern_values(case)))
+        outs.append(torch.zeros_like(ins[-1]))
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for p, a, b in zip(plans, ins, outs):         # first use outside the capture
+            B.tperm_execute(p, a.data_ptr(), b.data_ptr(), side.cuda_stream)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for p, a, b in zip(plans, ins, outs):
+            B.tperm_execute(p, a.data_ptr(), b.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for replay in range(3):
+        for i, case in enumerate(cases):               # new input bits, stale output, eagerly
+            ins[i].copy_(to_device(wl.bitpattern_values(wl.make_case(0, 27 + replay, case.dims, case.perm, case.elem_size))))
+            outs[i].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, case in enumerate(cases):
+            a = np_uint(ins[i].cpu().numpy())
+            ref = np_uint(oracle.transpose(a, case.dims, case.perm))
+            assert np.array_equal(np_uint(outs[i].cpu().numpy()), ref), (replay, case.dims)
+    for p in plans:
+        p.destroy()
+
+
 def test_copy_bytes():
     n = 1 << 20
     a = torch.arange(n + 3, dtype=torch.int32, device="cuda")
