@@ -249,7 +249,9 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // output runs keep paying off up to a few KiB (overhead worth 128 bytes, misalignment
     // weighted 2x: a partially written line costs more than a partially read one, cf.
     // Eq. (13)), input runs are flat from 128 bytes on (overhead worth 16 bytes).
-    double cost_in = (rin + (cd->align ? kAlignInOverhead : 16.0) + 0.5 * (128.0 - gin)) / rin;
+    // (the LDS-free row copy reads its rows one by one: misaligned short rows weigh double
+    // there; measured over all candidates of the 125 benchmark cases that keep dim 0 in front)
+    double cost_in = (rin + (cd->align ? kAlignInOverhead : 16.0) + (cd->use_lds ? 0.5 : 1.0) * (128.0 - gin)) / rin;
     if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
     if (cd->align) cost_in *= 1.0 + kAlignHaloWeight * std::pow((double)line_elems / (double)cd->t[q0], kAlignHaloPower);
     const double cost_out = (rout + (cd->align ? kAlignOutOverhead : 128.0) + 2.0 * (128.0 - gout)) / rout;
