@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--set2-perms", type=int, default=30, help="random permutations per shape for --config 6")
     ap.add_argument("--stride", type=int, default=1, help="take every n-th case of the family")
     ap.add_argument("--plan", choices=["heuristic", "measured"], default="heuristic")
+    ap.add_argument("--max-candidates", type=int, default=48,
+                    help="--plan measured: time this many of the best-scored candidates per case")
     ap.add_argument("--also-measured", action="store_true",
                     help="after the main pass, time the same step with measurement-selected plans")
     ap.add_argument("--also-graph", action="store_true",
@@ -145,7 +147,7 @@ def main():
     plans = []
     for c in cases:
         if args.plan == "measured":
-            plans.append(measured_plan(c, 48))
+            plans.append(measured_plan(c, args.max_candidates))
         else:
             plans.append(B.tperm_plan_create(c.dims, c.perm, c.elem_size))
     infos = [p.describe() for p in plans]
