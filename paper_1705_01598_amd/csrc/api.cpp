@@ -166,10 +166,15 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
     if ((a % elem) != 0 || (b % elem) != 0) return TPERM_ERR_ALIGN;
     PlanSlot* slot = &plan->base;
     const uintptr_t pair_mask = 2u * elem - 1u;  // the twin moves two elements per access
-    if (plan->wide.p != nullptr && !accumulate && ((a | b) & pair_mask) == 0) slot = &plan->wide;
+    // pairs inside line-aligned windows are formed on absolute addresses (written pairs) or
+    // read with element alignment (read pairs): no demand on the pointers
+    const auto any_alignment = [](const Plan* q) { return q->vec2 && q->align_out; };
+    if (plan->wide.p != nullptr && !accumulate &&
+        (((a | b) & pair_mask) == 0 || any_alignment(plan->wide.p)))
+        slot = &plan->wide;
     const Plan& p = *slot->p;
     // a plan that moves pairs by itself (forced through the options) has no plain twin
-    if (p.vec2 && (accumulate || ((a | b) & pair_mask) != 0))
+    if (p.vec2 && (accumulate || (((a | b) & pair_mask) != 0 && !any_alignment(&p))))
         return accumulate ? TPERM_ERR_KERNEL : TPERM_ERR_ALIGN;
     const size_t nbytes = (size_t)p.c.volume * (size_t)p.elem;
     if ((a < b && a + nbytes > b) || (b < a && b + nbytes > a)) return TPERM_ERR_ALIAS;

@@ -223,17 +223,19 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     const int64_t line_elems = 128 / elem;
     int64_t read_vol = vol;
     if (cd->align) {
-        // 8-byte elements only: measured over 87 ragged cases, no 4-byte candidate of this form
-        // came within 10 % of the best plain one (its accesses are single 4-byte elements)
-        // and not when the shifted dim is itself part of the input run (the halo then
-        // lengthens the rows read; measured: such candidates win in 5 % of the cases, by 5 %)
+        // Not when the shifted dim is itself part of the input run (the halo then lengthens
+        // the rows read; measured: such candidates win in 5 % of the cases, by 5 %).
         bool q0_in_input_run = true;  // all dims in front of it are taken whole
         for (int z = 0; z < q0; ++z) q0_in_input_run = q0_in_input_run && cd->t[z] == c.dims[z];
-        if (!cd->use_lds || elem != 8 || q0 == 0 || q0_in_input_run || cd->k != 1 || cd->t[q0] >= c.dims[q0] ||
+        if (!cd->use_lds || q0 == 0 || q0_in_input_run || cd->k != 1 || cd->t[q0] >= c.dims[q0] ||
             cd->t[q0] % line_elems != 0 || gout >= 128.0)
             return false;
+        // 4-byte elements only where the kernel can move them in pairs (see build_tile_plan)
+        if (elem == 4 && !(cd->t[0] % 2 == 0 && (c.dims[0] % 2 == 0 || cd->t[0] < c.dims[0]))) return false;
         read_vol = vol / cd->t[q0] * (cd->t[q0] + line_elems);
-        if (read_vol > 16 * TPERM_MAX_THREADS) return false;  // beyond 16 slots the kernel's registers allow one workgroup per CU only
+        // beyond 16 slots (of pairs, for 4-byte elements, as long as the single-element form
+        // still exists) the kernel's registers allow one workgroup per CU only
+        if (read_vol > (elem == 4 ? 24 : 16) * TPERM_MAX_THREADS) return false;
         if (read_vol * elem > kMaxLdsBytes - 8192) return false;
         gout = 128.0;
     }
@@ -251,10 +253,13 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // Eq. (13)), input runs are flat from 128 bytes on (overhead worth 16 bytes).
     // (the LDS-free row copy reads its rows one by one: misaligned short rows weigh double
     // there; measured over all candidates of the 125 benchmark cases that keep dim 0 in front)
-    double cost_in = (rin + (cd->align ? kAlignInOverhead : 16.0) + (cd->use_lds ? 0.5 : 1.0) * (128.0 - gin)) / rin;
+    const bool al4 = cd->align && elem == 4;
+    double cost_in = (rin + (cd->align ? (al4 ? kAlign4InOverhead : kAlignInOverhead) : 16.0) + (cd->use_lds ? 0.5 : 1.0) * (128.0 - gin)) / rin;
     if (rin < 128.0) cost_in += (128.0 - rin) / 64.0;  // below one line per run reads collapse
-    if (cd->align) cost_in *= 1.0 + kAlignHaloWeight * std::pow((double)line_elems / (double)cd->t[q0], kAlignHaloPower);
-    const double cost_out = (rout + (cd->align ? kAlignOutOverhead : 128.0) + 2.0 * (128.0 - gout)) / rout;
+    if (cd->align)
+        cost_in *= 1.0 + (al4 ? kAlign4HaloWeight : kAlignHaloWeight) *
+                             std::pow((double)line_elems / (double)cd->t[q0], al4 ? kAlign4HaloPower : kAlignHaloPower);
+    const double cost_out = (rout + (cd->align ? (al4 ? kAlign4OutOverhead : kAlignOutOverhead) : 128.0) + 2.0 * (128.0 - gout)) / rout;
     double cost = (cost_in + cost_out) / util;
     // Tile size, by slots per thread of a 256-thread workgroup: a table fitted with the rest.
     // Three to eight slots are the sweet spot (enough loads in flight per wave, several
@@ -268,7 +273,8 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     // the slots and behaves like the 8-byte kernel of the same tile bytes.
     const bool pairs = elem == 4 && cd->use_lds && !cd->align && q0 != 0 && c.dims[0] % 2 == 0 &&
                        c.dims[q0] % 2 == 0 && cd->t[0] % 2 == 0 && cd->t[q0] % 2 == 0;
-    const int64_t slots_needed = pairs ? vol / 2 : read_vol;
+    const bool window_pairs = elem == 4 && cd->align;
+    const int64_t slots_needed = pairs ? vol / 2 : (window_pairs ? read_vol / 2 : read_vol);
     const int64_t need = (slots_needed + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
     int bucket = 9;
     for (int i = 0; i < 10; ++i)
@@ -276,7 +282,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
             bucket = i;
             break;
         }
-    cost *= (elem == 4 && !pairs ? kWeight4 : kWeight8)[bucket];
+    cost *= (elem == 4 && !pairs && !window_pairs ? kWeight4 : kWeight8)[bucket];
     // A tile that does not fill the 256 lanes of its workgroup wastes the rest of them.
     if (need == 1) cost /= std::pow((double)slots_needed / TPERM_MAX_THREADS, 0.75);
     // Pipeline fill and drain: a persistent workgroup spends about four tile times without
@@ -288,7 +294,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     cost *= 1.0 + 4.0 / std::max(rounds, 4.0);
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.1;
-    if (cd->align) cost *= kAlignWeight;
+    if (cd->align) cost *= al4 ? kAlign4Weight : kAlignWeight;
     // Tiny tensors (a few rounds of tiles at most) are bound by latency, not bandwidth: what
     // counts is how long one workgroup needs for its tiles, about 1 us per slot of a thread
     // and a little more per tile dim (the prologue evaluates every slot's position), spread
@@ -831,9 +837,17 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         // line-aligned ones, which do better with single elements (and loads first).
         const double rounds = (double)d.num_tiles / (256.0 * std::max(2.0, std::min(8.0, std::round(20480.0 / ((double)cand.tile_vol * elem)))));
         const bool worth_it = elem == 4 || !cand.aligned || rounds < 16.0;
-        if (opts.vec2 == 1 && worth_it && cand.use_lds && !align_out && threads == 256 && q != 0 &&
-            nreg2 > 0 && c.dims[0] % 2 == 0 && c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 &&
-            cand.t[q] % 2 == 0 && dim_of_in[0] == 0 && dim_of_out[0] == q) {
+        // In line-aligned windows (4-byte elements only) the written pairs are 8-byte aligned
+        // whatever the extents, and an odd row length on the read side is allowed as long as
+        // dim 0 is chunked: the tile that holds the odd end reads element by element.
+        const int nreg2w = pick_nreg(read_vol / 2, threads);
+        const bool pair_windows = align_out && elem == 4 && nreg2w > 0 && cand.t[0] % 2 == 0 &&
+                                  (c.dims[0] % 2 == 0 || cand.t[0] < c.dims[0]) &&
+                                  (split_dim[0] == 0 || cand.t[0] == c.dims[0]);
+        const bool pair_plain = !align_out && worth_it && nreg2 > 0 && c.dims[0] % 2 == 0 &&
+                                c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 && cand.t[q] % 2 == 0;
+        if (opts.vec2 == 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
+            dim_of_in[0] == 0 && dim_of_out[0] == q) {
             TileDim& a = d.in_order[0];
             a.ext /= 2;
             a.div = make_fastdiv(a.ext);
@@ -848,8 +862,12 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
             o.lstride *= 2;
             o.xshift = 1;
             d.tile_vol /= 2;
+            if (align_out) {
+                d.oa.total_slots /= 2;
+                d.pair_a_split = split_dim[0] == 0 ? 1u : 0u;
+            }
             d.vec2 = 1;
-            nreg_final = nreg2;
+            nreg_final = align_out ? nreg2w : nreg2;
             plan->vec2 = true;
         }
     }
@@ -1060,7 +1078,41 @@ static tperm_status_t index_map_at_phase(const Plan& plan, int64_t* out_to_in, u
             }
             uint32_t rem_a = 0, rem_b = 0, lo_b = 0;
             tile_remaining(d, [&](uint32_t l) { return coord[l]; }, &rem_a, &rem_b, &lo_b);
-            if (plan.use_lds && d.vec2) {
+            if (plan.use_lds && d.vec2 && d.oa.enabled) {
+                // pairs of 4-byte elements in line-aligned windows: read pairs along input dim
+                // 0 (halo included), written pairs along the shifted window
+                const OutAlign& oa = d.oa;
+                const uint32_t span_b = rem_b > lo_b ? rem_b - lo_b : 0u;
+                std::fill(lds.begin(), lds.end(), -1);
+                for (uint32_t k = 0; k < d.tile_vol; ++k) {
+                    const Slot s = tile_slot(d.in_order, d.n_tile_dims, k);
+                    for (uint32_t e = 0; e < 2; ++e) {
+                        const uint32_t xa = d.pair_a_split ? s.xa + e : s.xa;
+                        if (!(xa < rem_a && (s.xb - lo_b) < span_b)) continue;
+                        const int64_t gi = (int64_t)maj_in + (int64_t)s.goff + e - (int64_t)oa.in_halo_elems;
+                        if (gi < 0 || gi >= vol || s.loff + e >= d.lds_elems) return TPERM_ERR_INTERNAL;
+                        if (lds[s.loff + e] != -1) return TPERM_ERR_INTERNAL;
+                        lds[s.loff + e] = gi;
+                    }
+                }
+                const uint32_t phi = (uint32_t)((maj_out + out_phase) & (oa.line_elems - 1u));
+                for (uint32_t k = 0; k < oa.total_slots; ++k) {
+                    const Slot so = tile_slot(d.out_order, d.n_tile_dims, k);
+                    const uint32_t p = so.xb;  // even position in the chunk
+                    const uint32_t rho = (so.goff - p) & (oa.line_elems - 1u);
+                    const uint32_t shift = (phi + rho) & (oa.line_elems - 1u);
+                    for (uint32_t e = 0; e < 2; ++e) {
+                        const uint32_t xb = p + e + oa.line_elems - shift;
+                        if (!(so.xa < rem_a && (xb - lo_b) < span_b)) continue;
+                        const int64_t go = (int64_t)maj_out + (int64_t)so.goff + e - (int64_t)shift;
+                        const int64_t li = (int64_t)so.loff + (int64_t)(oa.line_elems - shift + e) * oa.lstride_b;
+                        if (go < 0 || go >= vol || li < 0 || li >= (int64_t)d.lds_elems) return TPERM_ERR_INTERNAL;
+                        if (lds[li] == -1) return TPERM_ERR_INTERNAL;
+                        if (out_to_in[go] != -1) return TPERM_ERR_INTERNAL;
+                        out_to_in[go] = lds[li];
+                    }
+                }
+            } else if (plan.use_lds && d.vec2) {
                 // pairs: two neighbours along input dim 0 in, two along output dim 0 out
                 std::fill(lds.begin(), lds.end(), -1);
                 for (uint32_t k = 0; k < d.tile_vol; ++k) {

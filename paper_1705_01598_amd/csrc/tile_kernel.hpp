@@ -165,9 +165,17 @@ __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
     // VEC2: a slot is a pair of elements, moved through global memory with one access of
     // twice the element size; the LDS image stays in single elements.
-    static_assert(!VEC2 || (USE_LDS && !ALIGN && !ACC), "vec2 is a plain LDS-staged form");
+    static_assert(!VEC2 || (USE_LDS && !ACC), "vec2 is an LDS-staged, non-accumulating form");
+    static_assert(!(VEC2 && ALIGN) || sizeof(T) == 4, "pairs in line-aligned windows: 4-byte elements");
+    // PAIRWIN: pairs of 4-byte elements in line-aligned output windows.  Read pairs run along
+    // input dim 0 (8-byte loads from 4-byte aligned addresses when rows have odd lengths),
+    // written pairs along the window, where they are always 8-byte aligned.  A tile that
+    // holds the odd end of an input row, or a window clipped by the ends of an output row,
+    // moves that side element by element instead (a wave-uniform choice per tile and side).
+    constexpr bool PAIRWIN = VEC2 && ALIGN;
     typedef typename std::conditional<sizeof(T) == 4, uint64_t, Pair64>::type pair_t;
     typedef Elem<typename std::conditional<VEC2, pair_t, T>::type, NT> io;
+    typedef Elem<T, NT> io1;  // single elements
     typedef typename io::reg reg_t;
     typedef typename Elem<T, NT>::reg lds_t;  // one element
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -293,12 +301,31 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         return ALIGN ? slot_valid_from(rd_mask[j], t.rem_a, t.lo_b, t.span_b)
                      : slot_valid(rd_mask[j], t.rem_a, t.rem_b);
     };
-    if (b < d.num_tiles) {
-        pos = major_position(d, ml, b);
-        const uint32_t soff = pos.in * (uint32_t)sizeof(T);
+    // PAIRWIN: the second element of read-side pair j exists in tile t / the tile holds the odd
+    // end of an input row (remaining extent of split dim A is odd)
+    auto read_ok_second = [&](int j, const MajorPos& t) {
+        return read_ok(j, t) && slot_valid_from(rd_mask[j] + 1u, t.rem_a, t.lo_b, t.span_b);
+    };
+    auto odd_row_end = [&](const MajorPos& t) { return PAIRWIN && d.pair_a_split != 0u && (t.rem_a & 1u) != 0u; };
+    auto load_tile = [&](const MajorPos& t) {
+        const uint32_t soff = t.in * (uint32_t)sizeof(T);
+        if constexpr (PAIRWIN) {
+            if (odd_row_end(t)) {
+#pragma unroll
+                for (int j = 0; j < NREG; ++j) {
+                    v[j].x = io1::load(rsrc_in, read_ok(j, t) ? rd_off[j] : kDroppedOffset, soff);
+                    v[j].y = io1::load(rsrc_in, read_ok_second(j, t) ? rd_off[j] + 4u : kDroppedOffset, soff);
+                }
+                return;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NREG; ++j)
-            v[j] = io::load(rsrc_in, read_ok(j, pos) ? rd_off[j] : kDroppedOffset, soff);
+            v[j] = io::load(rsrc_in, read_ok(j, t) ? rd_off[j] : kDroppedOffset, soff);
+    };
+    if (b < d.num_tiles) {
+        pos = major_position(d, ml, b);
+        load_tile(pos);
     }
     // As many dropped stores as a tile has real ones: every pass through the loop below then
     // starts with the same queue of memory operations behind it (one tile of loads, one of
@@ -352,12 +379,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         //                 96^4 set); explicit waits in the other form did not reproduce it.
         // After the last tile the stores-first form issues the reads all the same, with
         // every lane dropped (nxt then has remaining extents 0).
-        auto issue_next_loads = [&]() {
-            const uint32_t soff = nxt.in * (uint32_t)sizeof(T);
-#pragma unroll
-            for (int j = 0; j < NREG; ++j)
-                v[j] = io::load(rsrc_in, read_ok(j, nxt) ? rd_off[j] : kDroppedOffset, soff);
-        };
+        auto issue_next_loads = [&]() { load_tile(nxt); };
         if (USE_LDS) {
             // with two LDS images the tiles alternate between them and one barrier per
             // tile is enough: a wave can only overwrite an image two tiles later, after
@@ -370,7 +392,8 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                         // neighbours along input dim 0 are neighbours in the image
                         if constexpr (sizeof(T) == 4) {
                             img[lds_pos[j] & 0xFFFFu] = v[j].x;
-                            img[(lds_pos[j] & 0xFFFFu) + 1u] = v[j].y;
+                            if (!odd_row_end(pos) || read_ok_second(j, pos))
+                                img[(lds_pos[j] & 0xFFFFu) + 1u] = v[j].y;
                         } else {
                             img[lds_pos[j] & 0xFFFFu] = lds_t{v[j].x, v[j].y};
                             img[(lds_pos[j] & 0xFFFFu) + 1u] = lds_t{v[j].z, v[j].w};
@@ -381,11 +404,18 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                 }
             __syncthreads();
             if (ALIGN) {
-                if constexpr (!VEC2) {
 #pragma unroll
-                    for (int j = 0; j < NREG; ++j)
-                        if (write_at(j) != kDroppedOffset)
-                            w[j] = img[(lds_pos[j] >> 16) - row_shift(j) * d.oa.lstride_b];
+                for (int j = 0; j < NREG; ++j) {
+                    const uint32_t at = (lds_pos[j] >> 16) - row_shift(j) * d.oa.lstride_b;
+                    if constexpr (PAIRWIN) {
+                        // both elements of the pair lie inside the image whenever the row does
+                        if ((wr_mask[j] & 0xFFFFu) < pos.rem_a) {
+                            w[j].x = img[at];
+                            w[j].y = img[at + d.oa.lstride_b];
+                        }
+                    } else if constexpr (!VEC2) {
+                        if (write_at(j) != kDroppedOffset) w[j] = img[at];
+                    }
                 }
             } else {
 #pragma unroll
@@ -425,8 +455,26 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
 #pragma unroll
             for (int j = 0; j < NREG; ++j) w[j] = io::add(old[j], w[j]);
         }
+        bool stored = false;
+        if constexpr (PAIRWIN) {
+            // a window clipped by the ends of its output row: element by element
+            if (pos.lo_b != 0u || pos.rem_b != d.split_tile[1]) {
 #pragma unroll
-        for (int j = 0; j < NREG; ++j) io::store(w[j], rsrc_out, write_at(j), soff_out);
+                for (int j = 0; j < NREG; ++j) {
+                    const uint32_t sh = row_shift(j);
+                    const uint32_t xb = (wr_aux[j] & 0xFFFFu) - sh;
+                    const bool row_ok = (wr_mask[j] & 0xFFFFu) < pos.rem_a;
+                    const uint32_t at = wr_off[j] - sh * (uint32_t)sizeof(T);
+                    io1::store(w[j].x, rsrc_out, row_ok && (xb - pos.lo_b) < pos.span_b ? at : kDroppedOffset, soff_out);
+                    io1::store(w[j].y, rsrc_out, row_ok && (xb + 1u - pos.lo_b) < pos.span_b ? at + 4u : kDroppedOffset, soff_out);
+                }
+                stored = true;
+            }
+        }
+        if (!stored) {
+#pragma unroll
+            for (int j = 0; j < NREG; ++j) io::store(w[j], rsrc_out, write_at(j), soff_out);
+        }
         if (!LOADS_FIRST) issue_next_loads();
         b = bn;
         pos = nxt;
@@ -477,6 +525,20 @@ template <typename T, int THREADS>
 static const void* tile_kernel_select(int nreg, bool use_lds, int nt, bool align, bool acc,
                                       bool loads_first, bool vec2) {
     if constexpr (THREADS == 256) {
+        if (vec2 && align) {
+            // pairs of 4-byte elements in line-aligned windows
+            if constexpr (sizeof(T) == 4) {
+                if (!use_lds || acc) return nullptr;
+                switch (nt) {
+                    case 0: return tile_kernel_ptr<T, 256, true, 0, true, false, false, true>(nreg);
+                    case 1: return tile_kernel_ptr<T, 256, true, 1, true, false, false, true>(nreg);
+                    case 2: return tile_kernel_ptr<T, 256, true, 2, true, false, false, true>(nreg);
+                    default: return tile_kernel_ptr<T, 256, true, 3, true, false, false, true>(nreg);
+                }
+            } else {
+                return nullptr;
+            }
+        }
         if (nt == 3) {
             // nontemporal loads only: plain stores-first forms
             if (acc || loads_first) return nullptr;

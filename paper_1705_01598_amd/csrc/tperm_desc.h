@@ -101,6 +101,8 @@ struct TileDesc {
                             // of in_order counts pairs along input dim 0, entry 0 of out_order
                             // pairs along output dim 0; tile_vol is in pairs
     uint32_t pair_lstride;  // vec2: LDS distance of the two elements of an output-side pair
+    uint32_t pair_a_split;  // vec2 in line-aligned windows: 1 if input dim 0, along which the read
+                            // pairs run, is split dim A (its remaining extent may then be odd)
     uint32_t grid_mode;     // how workgroups walk the tiles, see tile_of()
     uint32_t tiles_per_xcd; // grid_mode 1: ceil(num_tiles / 8)
     uint32_t group_log2;    // grid_mode 2: log2 of the tile group dealt to one XCD

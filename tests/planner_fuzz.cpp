@@ -13,7 +13,7 @@
 int main(int argc, char** argv) {
     const int iters = argc > 1 ? atoi(argv[1]) : 400;
     std::mt19937_64 rng(12345);
-    int made = 0, rejected = 0, windows = 0;
+    int made = 0, rejected = 0, windows = 0, pair_windows = 0;
     for (int it = 0; it < iters; ++it) {
         const int rank = 1 + (int)(rng() % 16);
         int64_t dims[TPERM_MAX_RANK];
@@ -65,6 +65,7 @@ int main(int argc, char** argv) {
                 // tile, chunked in whole 128-byte lines
                 o.k = 1;
                 o.tile_out = (int64_t)(128 / (int)elem) * (1 + (int64_t)(rng() % 3));
+                if (rng() % 2) o.tile_in &= ~(int64_t)1;  // pairs need an even tile extent
                 o.threads = 256;
                 o.vec2 = 0;
             }
@@ -98,10 +99,11 @@ int main(int argc, char** argv) {
             seen[(size_t)map[(size_t)i]] = 1;
         }
         if (p->align_out) ++windows;
+        if (p->align_out && p->vec2) ++pair_windows;
         delete p;
         ++made;
     }
-    std::printf("ok: %d plans checked (%d with line-aligned windows), %d option sets rejected\n", made, windows,
+    std::printf("ok: %d plans checked (%d with line-aligned windows, %d of them in pairs), %d option sets rejected\n", made, windows, pair_windows,
                 rejected);
     return 0;
 }

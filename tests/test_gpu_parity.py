@@ -152,6 +152,39 @@ def test_line_aligned_windows_match_oracle(dims, perm, m, tin, k, lines, offset,
     plan.destroy()
 
 
+PAIR_WINDOW_TILES = [
+    # dims, perm, tile_in (even), lines per chunk: 4-byte elements moved in pairs
+    ((258, 331), (1, 0), 32, 1),
+    ((257, 331), (1, 0), 32, 2),               # odd rows: the last chunk of dim 0 reads singly
+    ((101, 1003), (1, 0), 16, 4),
+    ((71, 45, 333), (2, 1, 0), 16, 2),
+    ((38, 130, 5), (1, 0, 2), 38, 2),          # dim 0 whole (even), the shifted dim alone is split
+    ((1001, 999), (1, 0), 64, 2),
+    ((5, 7, 301), (2, 0, 1), 4, 1),
+]
+
+
+@pytest.mark.parametrize("in_offset", [0, 1])
+@pytest.mark.parametrize("offset", [0, 1, 2, 7, 16, 31])
+@pytest.mark.parametrize("dims,perm,tin,lines", PAIR_WINDOW_TILES)
+def test_pair_windows_match_oracle(dims, perm, tin, lines, offset, in_offset):
+    """Pairs of 4-byte elements inside line-aligned output windows: any phase of the output
+    pointer, input pointers aligned to one element only, rows of odd length."""
+    case = wl.make_case(0, 25, dims, perm, 4)
+    plan = B.tperm_plan_create_ex(dims, perm, 4, m=1, tile_in=tin, k=1, tile_out=32 * lines,
+                                  align_out=2, vec2=2, cache_policy=1 + (offset + in_offset) % 4)
+    info = plan.describe()
+    assert info.align_out == 1 and info.vec2 == 1, B.info_dict(info)
+    a = wl.bitpattern_values(case)
+    buf = torch.empty(case.volume + 64, dtype=torch.int32, device="cuda")
+    a_dev = buf[32 + in_offset:32 + in_offset + case.volume]
+    a_dev.copy_(to_device(a))
+    got, guards = run_plan(plan, a_dev, case.volume, 4, offset)
+    assert guards
+    assert np.array_equal(got, np_uint(oracle.transpose(np_uint(a), dims, perm)))
+    plan.destroy()
+
+
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("dims,perm", [((4001, 3777), (1, 0)), ((1001, 15, 1003), (2, 1, 0))])
 def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
@@ -159,7 +192,8 @@ def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
     plain execution and accumulation both go through it."""
     case = wl.make_case(0, 22, dims, perm, elem)
     plan = B.tperm_plan_create(dims, perm, elem)
-    assert plan.describe().align_out == (1 if elem == 8 else 0), B.info_dict(plan.describe())
+    assert plan.describe().align_out == 1, B.info_dict(plan.describe())
+    assert plan.describe().vec2 == (1 if elem == 4 else 0)
     _check(case, plan, offset=3)
     a = wl.uniform_values(case)
     b = wl.uniform_values(wl.make_case(0, 23, dims, perm, elem)) * 3

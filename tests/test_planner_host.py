@@ -258,8 +258,14 @@ def test_line_aligned_windows_maps():
             assert info.align_out == 1
             # the read side carries one line's worth of halo coordinates along the chunk
             assert info.nreg * info.threads >= math.prod(t for t in B.info_dict(info)["tile"])
-    # the selector takes the form by itself for misaligned low-rank transposes of 8-byte elements ...
+    # 4-byte elements in pairs inside the windows
+    for dims, perm, tin, lines in G.PAIR_WINDOW_TILES:
+        info = _map_ok(dims, perm, 4, m=1, tile_in=tin, k=1, tile_out=32 * lines, align_out=2, vec2=2).describe()
+        assert info.align_out == 1 and info.vec2 == 1
+    # the selector takes the form by itself for misaligned low-rank transposes ...
     assert _map_ok((4001, 3777), (1, 0), 8).describe().align_out == 1
+    info = _map_ok((4001, 3777), (1, 0), 4).describe()
+    assert info.align_out == 1 and info.vec2 == 1
     # ... and not when rows are line-aligned or the leading output dim is short
     assert _map_ok((4096, 3072), (1, 0), 8).describe().align_out == 0
     assert _map_ok((9, 11, 13, 12, 7), (4, 3, 2, 1, 0), 8).describe().align_out == 0
