@@ -144,6 +144,17 @@ def test_paper_set2_shapes_sampled(which):
         _stamp_check(case, stamp, out)
 
 
+@pytest.mark.parametrize("side", [13952, 13953, 13966, 13967])
+def test_figure8_squares_sampled(side):
+    """The square 4-byte matrices of the alignment sweep (Section 3.1, Figure 8): whole lines
+    per row, and rows that start anywhere in a line (pairs inside line-aligned windows; odd
+    sides end every input row with a single element)."""
+    case = next(c for c in wl.square_sweep() if c.dims[0] == side)
+    stamp = torch.arange(case.volume, dtype=torch.int32, device="cuda")
+    out = torch.empty(case.volume + 2 * GUARD, dtype=torch.int32, device="cuda")
+    _stamp_check(case, stamp, out, sort_check=(side == 13953))
+
+
 def test_accumulate_full_size():
     """out = out + transpose(in) on two C2 permutations, element by element."""
     for case in (wl.config2()[3], wl.config2()[22]):
