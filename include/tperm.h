@@ -95,7 +95,9 @@ typedef struct {
     int vec2;           /* transposing 4-byte plans with 8-byte global accesses (see `vec2`  *
                          * below): 0 = default (a twin plan is kept for 8-byte aligned       *
                          * pointers), 1 = off, 2 = in this plan itself where the shape       *
-                         * allows, which then requires 8-byte aligned pointers               */
+                         * allows, which then requires 8-byte aligned pointers (except with  *
+                         * line-aligned output windows, which form their pairs on absolute  *
+                         * addresses and take any element-aligned pointer)                   */
     int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (see `paired` below): *
                          * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
 } tperm_plan_opts_t;
@@ -142,7 +144,12 @@ typedef struct {
                                             * along both); nreg counts pairs per thread.      *
                                             * Used by tperm_execute when both pointers are  *
                                             * 8-byte aligned; otherwise, and for            *
-                                            * accumulation, the plan's plain twin runs.     */
+                                            * accumulation, the plan's plain twin runs.     *
+                                            * Together with align_out: pairs inside the     *
+                                            * line-aligned windows (even tile extent along  *
+                                            * input dim 0, any extents, any element-aligned *
+                                            * pointers; odd row ends and clipped windows    *
+                                            * move single elements).                         */
     int reserved[2];
 } tperm_plan_info_t;
 
