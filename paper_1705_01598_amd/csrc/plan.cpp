@@ -269,6 +269,11 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     static const int kSlots[10] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     static const double kWeight8[10] = {1.4, 1.05, 0.95, 0.95, 1.1, 1.0, 1.06, 1.1, 1.16, 1.2};
     static const double kWeight4[10] = {1.4, 1.0, 1.0, 0.8, 1.0, 1.0, 1.0, 1.0, 1.06, 1.1};
+    // The LDS-free row copy keeps few registers per slot and has no barrier: four to six
+    // slots do better there than the LDS-staged table says when they come from more rows
+    // (measured on every candidate of the benchmark cases that keep dim 0 in front; making a
+    // single row longer instead loses 1-5 %).
+    static const double kWeightRc[10] = {1.4, 1.05, 0.95, 0.9, 0.9, 1.0, 1.06, 1.1, 1.16, 1.2};
     // A 4-byte candidate that can move its elements in pairs (see build_tile_plan) has half
     // the slots and behaves like the 8-byte kernel of the same tile bytes.
     const bool pairs = elem == 4 && cd->use_lds && !cd->align && q0 != 0 && c.dims[0] % 2 == 0 &&
@@ -282,7 +287,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
             bucket = i;
             break;
         }
-    cost *= (elem == 4 && !pairs && !window_pairs ? kWeight4 : kWeight8)[bucket];
+    cost *= (!cd->use_lds && n_tile_dims >= 2 ? kWeightRc : (elem == 4 && !pairs && !window_pairs ? kWeight4 : kWeight8))[bucket];
     // A tile that does not fill the 256 lanes of its workgroup wastes the rest of them.
     if (need == 1) cost /= std::pow((double)slots_needed / TPERM_MAX_THREADS, 0.75);
     // Pipeline fill and drain: a persistent workgroup spends about four tile times without
