@@ -297,6 +297,26 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
         std::max(2.0, std::min(8.0, std::round((cd->use_lds ? 20480.0 : 14336.0) / bytes)));
     const double rounds = (double)tiles / (256.0 * wg_per_cu);
     cost *= 1.0 + 4.0 / std::max(rounds, 4.0);
+    // Rows a large power of two apart land in the same memory channels: when the pitch of the
+    // rows a tile reads (the input stride of its first dim beyond the input run) is a multiple
+    // of 8 KiB, more than 32 of them per tile cost (measured on the 96^4 permutations, whose
+    // pitches are 2^13 * 9 and 2^18 * 27 bytes: 32 x 32 tiles beat 32 x 96 ones by 2-13 %
+    // there although their output runs are short; no other benchmark set has such pitches).
+    if (cd->use_lds && !cd->align) {
+        int z = 0;
+        while (z < r) {  // skip the input run
+            const bool cut = cd->t[z] < c.dims[z];
+            ++z;
+            if (cut) break;
+        }
+        int64_t rows = 1, pitch = 0;
+        for (; z < r; ++z)
+            if (cd->t[z] > 1) {
+                rows *= cd->t[z];
+                if (pitch == 0) pitch = sI[z] * elem;
+            }
+        if (pitch != 0 && pitch % 8192 == 0 && rows > 32) cost *= 1.0 + 0.15 * std::log2((double)rows / 32.0);
+    }
     // The LDS stage itself is not free.
     if (cd->use_lds) cost *= 1.1;
     if (cd->align) cost *= al4 ? kAlign4Weight : kAlignWeight;
