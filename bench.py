@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # plain copy of known size (see profiles/tile_kernel_c2_96x96x96x96_fp64.txt, and
 # profiles/tile_kernel_c7_square_sweep_fp32.txt for the square sweep: rows that start anywhere in
 # a line fetch the partial lines at both ends of every row segment).  None = not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c2": 1359045700, "c7": 1921306400}
+TRAFFIC_BYTES_PER_LAUNCH = {"c2": 1358868800, "c7": 1921306400}
 
 
 def parse_args():
