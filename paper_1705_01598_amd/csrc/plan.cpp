@@ -238,6 +238,10 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
         if (elem == 4 && !(cd->t[0] % 2 == 0 && (c.dims[0] % 2 == 0 || cd->t[0] < c.dims[0]))) return false;
         if (elem == 4 && gin >= 128.0 && std::fmod(rin, 128.0) == 0.0) return false;
         read_vol = vol / cd->t[q0] * (cd->t[q0] + line_elems);
+        // the shifted windows need chunks for d + L - 1 coordinates, not d: with a short leading
+        // output dim that is one chunk more out of a few
+        util *= (double)ceil_div(c.dims[q0], cd->t[q0]) /
+                (double)ceil_div(c.dims[q0] + line_elems - 1, cd->t[q0]);
         // beyond 16 slots (of pairs, for 4-byte elements, as long as the single-element form
         // still exists) the kernel's registers allow one workgroup per CU only
         if (read_vol > (elem == 4 ? 24 : 16) * TPERM_MAX_THREADS) return false;
