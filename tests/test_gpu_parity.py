@@ -186,7 +186,7 @@ def test_pair_windows_match_oracle(dims, perm, tin, lines, offset, in_offset):
 
 
 @pytest.mark.parametrize("elem", [8, 4])
-@pytest.mark.parametrize("dims,perm", [((4001, 3777), (1, 0)), ((1001, 15, 1003), (2, 1, 0))])
+@pytest.mark.parametrize("dims,perm", [((5001, 4777), (1, 0)), ((2001, 15, 2003), (2, 1, 0))])
 def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
     """Misaligned low-rank transposes: the selector takes the aligned-window form by itself;
     plain execution and accumulation both go through it."""

@@ -264,7 +264,7 @@ def test_line_aligned_windows_maps():
         assert info.align_out == 1 and info.vec2 == 1
     # the selector takes the form by itself for misaligned low-rank transposes ...
     assert _map_ok((4001, 3777), (1, 0), 8).describe().align_out == 1
-    info = _map_ok((4001, 3777), (1, 0), 4).describe()
+    info = _map_ok((5001, 4777), (1, 0), 4).describe()
     assert info.align_out == 1 and info.vec2 == 1
     # ... and not when rows are line-aligned or the leading output dim is short
     assert _map_ok((4096, 3072), (1, 0), 8).describe().align_out == 0
