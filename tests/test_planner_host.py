@@ -347,6 +347,28 @@ def test_selected_tiles_are_sane_for_the_benchmark_shapes():
             assert info.run_in * info.elem_size >= 128, B.info_dict(info)
 
 
+def test_selector_rules_fitted_to_measurements():
+    """The measured rules of the selector, pinned on the shapes they came from."""
+    d = lambda dims, perm, e, **kw: B.info_dict(B.tperm_plan_create_ex(dims, perm, e, **kw).describe())
+    # rows a multiple of 8 KiB apart: at most 32 of them per tile (96^4, permutations 2013 and 3012)
+    for perm in ((2, 0, 1, 3), (3, 0, 1, 2)):
+        info = d((96, 96, 96, 96), perm, 8)
+        rows = math.prod(info["tile"][1:])
+        assert info["kernel"] == "tiled" and rows <= 32, info
+    # ... while rows 768 bytes apart may be many (permutation 1023)
+    assert math.prod(d((96, 96, 96, 96), (1, 0, 2, 3), 8)["tile"][1:]) >= 64
+    # the LDS-free row copy takes four to six slots per thread when they come from several rows
+    info = d((96, 96, 96, 96), (0, 2, 3, 1), 8)
+    assert info["kernel"] == "rowcopy" and info["nreg"] in (4, 6), info
+    # 4-byte elements: windows with pairs for misaligned rows, not when the input rows are line-aligned
+    assert d((13953, 13953), (1, 0), 4)["align_out"] == 1 and d((13953, 13953), (1, 0), 4)["vec2"] == 1
+    assert d((6560, 6103), (1, 0), 4)["align_out"] == 0
+    assert d((6560, 6103), (1, 0), 4)["cache_policy"] == 4     # nontemporal loads only
+    # a short leading output dim needs one window chunk more out of a few: plain tiles there
+    assert d((224, 367, 191), (2, 1, 0), 8)["align_out"] == 0
+    assert d((12688, 11907), (1, 0), 8)["align_out"] == 1
+
+
 def test_planner_under_address_and_ub_sanitizers(tmp_path):
     """The planner (pure host C++) is built with ASan + UBSan and driven with random problems
     and options; every plan's index map must be a bijection and no sanitizer may fire."""
