@@ -71,6 +71,12 @@ int main(int argc, char** argv) {
             }
             o.lds_pad = (int)(rng() % 8) - 1;
             o.vec2 = (int)(rng() % 3);
+            if (long_q0 && elem == 4 && (rng() % 2)) {
+                // pairs inside the windows: one input dim in the tile, even extent along it
+                o.vec2 = 2;
+                o.m = 1;
+                o.tile_in = 2 + 2 * (int64_t)(rng() % 24);
+            }
             o.loads_first = (int)(rng() % 3);
             o.tile_order = (int)(rng() % 3);
         }

@@ -384,7 +384,7 @@ def test_planner_under_address_and_ub_sanitizers(tmp_path):
                     *src, "-o", exe], check=True)
     env = dict(os.environ)
     env["ASAN_OPTIONS"] = "verify_asan_link_order=0:detect_leaks=1"
-    r = subprocess.run([exe, "300"], capture_output=True, text=True, env=env)
+    r = subprocess.run([exe, "1500"], capture_output=True, text=True, env=env)
     assert r.returncode == 0 and r.stdout.startswith("ok:"), r.stdout + r.stderr
 
 
