@@ -2,15 +2,21 @@
 """Benchmark of the rank-n tensor transpose hot path on one MI355X.
 
 A step is one pass over one batch of synthetic input: every permutation of the workload
-(default: the rank-4 fp64 96^4 tensor with all 23 non-identity permutations) is executed
+(headline: the rank-4 fp64 96^4 tensor with all 23 non-identity permutations) is executed
 once through the C ABI, from a device-resident input into a device-resident output.  The
 metric is the paper's bandwidth formula, 2 * vol * E / t (Section 3.1), in GB/s
 (GB = 1e9 bytes), over the whole step.
 
-Prints ONE JSON line.  `roofline` prices the tile kernel (the kernel every staged
-transpose runs through) against the 8 TB/s HBM peak using its per-launch durations taken
-with HIP events inside the timed region; `cpu_baseline` is the CPU oracle timed on this
-box's host cores on a bounded sample of the same workload.
+Prints ONE JSON line.  `value` and the top-level fields describe the headline workload.
+Without --config the other four workload families are timed as well, each with the same
+harness, and reported under `per_config` (aggregate, per-case median / minimum, median per
+rank and the ratio between the best and the worst rank median, event-timed fraction of the
+HBM peak), and one case of every family is compared with the CPU oracle over the whole
+tensor after the timed region (`bit_exact`).  `roofline` prices the tile kernel (the kernel
+every staged transpose runs through) against the 8 TB/s HBM peak using its per-launch
+durations taken with HIP events inside the timed region; `cpu_baseline` is the CPU oracle
+timed on this machine's host cores on a bounded sample of the headline workload, with all the
+threads it uses and with one.
 """
 from __future__ import annotations
 
@@ -25,13 +31,28 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+HEADLINE = 2
 
-# HBM traffic per launch of the tile kernel on the default workload, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs scaled by what the same counters read for the library's
-# plain copy of known size (see profiles/tile_kernel_c2_96x96x96x96_fp64.txt, and
-# profiles/tile_kernel_c7_square_sweep_fp32.txt for the square sweep: rows that start anywhere in
-# a line fetch the partial lines at both ends of every row segment).  None = not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c2": 1358868800, "c7": 1921306400}
+# HBM traffic per launch of the tile kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by what the same counters read for the library's plain copy of known size.  These are
+# figures copied from the named summaries, not something this run measures.
+TRAFFIC = {
+    2: (1358868800, "profiles/tile_kernel_c2_96x96x96x96_fp64.txt"),
+    7: (1921306400, "profiles/tile_kernel_c7_square_sweep_fp32.txt"),
+}
+
+WORKLOAD_NAMES = {
+    1: "rank-2 fp64 2048x2048 transpose",
+    2: "rank-4 fp64 96^4, all 23 non-identity permutations",
+    3: "rank-6 fp64 ~2^26 elements, 20 seeded cases",
+    4: "rank sweep 2..12 fp64 ~2^26 elements, 330 seeded cases",
+    5: "fp32 contraction-feeding transposes 8^8 and 16^6, 80 seeded permutations",
+    6: "the paper's rank-8 (205M el) and rank-12 (328M el) fp64 shapes, seeded permutations + trivial + reverse",
+    7: "square fp32 matrices, side 13952..13968",
+    8: "held-out selector check: ranks 2..12, 2^25 and 2^27 elements, both element sizes, fresh seeds",
+}
+# steps / warm-up of the families timed beside the headline one (their steps take 0.02-70 ms)
+SIDE_STEPS = {1: (200, 20), 3: (10, 2), 4: (5, 1), 5: (20, 3)}
 
 
 def parse_args():
@@ -39,9 +60,11 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2,
-                    help="workload family 1..5 (default 2); 6 = the paper's printed rank-8/rank-12 "
-                         "shapes (Section 3.2), 7 = its square fp32 matrices of side 13952..13968")
+    ap.add_argument("--config", type=int, default=0,
+                    help="time one workload family only: 1..5; 6 = the paper's printed rank-8/rank-12 "
+                         "shapes (Section 3.2), 7 = its square fp32 matrices of side 13952..13968, "
+                         "8 = held-out shapes for the selector check.  Default: family 2 as the "
+                         "headline, families 1, 3, 4, 5 beside it under per_config")
     ap.add_argument("--accumulate", action="store_true",
                     help="time out = out + transpose(in) (Section 3.3); bytes = 3 * vol * E")
     ap.add_argument("--set2-perms", type=int, default=30, help="random permutations per shape for --config 6")
@@ -54,21 +77,22 @@ def parse_args():
     ap.add_argument("--also-graph", action="store_true",
                     help="additionally replay one step captured in a HIP graph (reported as graph_value)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-verify", action="store_true", help="skip the whole-tensor oracle comparison")
     ap.add_argument("--cases-out", default="", help="write per-case results (JSON lines) here")
     return ap.parse_args()
 
 
 def cpu_baseline(cases, budget_s=12.0):
-    """Time the CPU oracle (all host threads it uses) on a bounded sample of the cases."""
-    import numpy as np
-
+    """Time the CPU oracle on a bounded sample of the cases: with all the host threads it
+    uses, and (on the first two cases of the sample) with one thread."""
     import oracle
     from paper_1705_01598_amd import workloads as wl
 
     sample = cases[:: max(1, len(cases) // 8)][:8]
     total_bytes, total_t, names = 0, 0.0, []
+    one_bytes, one_t, one_names = 0, 0.0, []
     t_begin = time.perf_counter()
-    for case in sample:
+    for n, case in enumerate(sample):
         a = wl.uniform_values(case)
         best = None
         for _ in range(2):
@@ -81,12 +105,208 @@ def cpu_baseline(cases, budget_s=12.0):
         total_bytes += case.bytes_moved
         total_t += best
         names.append(case.name)
+        if n < 2:
+            t0 = time.perf_counter()
+            oracle.transpose(a, case.dims, case.perm, nthreads=1)
+            one_t += time.perf_counter() - t0
+            one_bytes += case.bytes_moved
+            one_names.append(case.name)
         if time.perf_counter() - t_begin > budget_s:
             break
     return {"value": round(total_bytes / total_t / 1e9, 3), "unit": "GB/s",
             "cores": oracle.max_threads(), "kind": "oracle",
             "sample": f"{len(names)} of {len(cases)} cases ({', '.join(names)}), best of 2 each, "
-                      f"2*vol*E/t summed over the sample"}
+                      f"2*vol*E/t summed over the sample",
+            "single_thread": {"value": round(one_bytes / one_t / 1e9, 3), "unit": "GB/s", "cores": 1,
+                              "sample": f"{', '.join(one_names)}, one run each"}}
+
+
+def family(args, config):
+    from paper_1705_01598_amd import workloads as wl
+    if config == 6:
+        return wl.set2(args.set2_perms)[:: args.stride]
+    if config == 7:
+        return wl.square_sweep()[:: args.stride]
+    if config == 8:
+        return wl.heldout()[:: args.stride]
+    return wl.all_configs()[config][:: args.stride]
+
+
+class Harness:
+    """Device buffers, plans and the timed loop of one workload family."""
+
+    def __init__(self, args, config, cases):
+        import numpy as np
+        import torch
+        from paper_1705_01598_amd import binding as B
+        from paper_1705_01598_amd import workloads as wl
+        self.np, self.torch, self.B, self.wl = np, torch, B, wl
+        self.args, self.config, self.cases = args, config, cases
+        self.mem_ops = 3 if args.accumulate else 2
+        self.run = B.tperm_execute_accumulate if args.accumulate else B.tperm_execute
+        self.stream = torch.cuda.current_stream().cuda_stream
+        dev = torch.device("cuda:0")
+        # device-resident input (uniform values of the family's first seed) and output: one
+        # buffer each, at least 512 MiB, so that a small tensor rotates through up to 16
+        # places in them and no launch finds its data in the 256 MB last-level cache
+        max_bytes = max(c.volume * c.elem_size for c in cases)
+        buf_bytes = max(max_bytes, 512 << 20)
+        fp32 = all(c.elem_size == 4 for c in cases)
+        host = wl.uniform_values(wl.make_case(config, 0, (buf_bytes // (4 if fp32 else 8),), (0,), 4 if fp32 else 8))
+        self.a = torch.from_numpy(host.view(np.int32 if fp32 else np.int64)).to(dev)
+        self.b = torch.empty_like(self.a)
+        del host
+        # byte distance between the places of case i, and how many there are
+        self.place = [(c.volume * c.elem_size + 4095) // 4096 * 4096 for c in cases]
+        self.places = [max(1, min(16, buf_bytes // p)) for p in self.place]
+        self.n_pairs = self.places[0]
+        # measurement-based selection of tensors that fit the last-level cache is timed with a
+        # 512 MiB scratch swept between executions, as the data will arrive from HBM in the timed loop
+        self.scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev) \
+            if (self.n_pairs > 1 and (args.plan == "measured" or args.also_measured)) else None
+        self.plans = [self.measured_plan(c, args.max_candidates) if args.plan == "measured"
+                      else B.tperm_plan_create(c.dims, c.perm, c.elem_size) for c in cases]
+        self.infos = [p.describe() for p in self.plans]
+
+    def measured_plan(self, c, max_candidates):
+        B = self.B
+        a, b = self.a, self.b
+        if self.scratch is not None:
+            return B.tperm_plan_create_measured_cold(c.dims, c.perm, c.elem_size, a.data_ptr(), b.data_ptr(),
+                                                     self.stream, self.scratch.data_ptr(), self.scratch.numel(),
+                                                     max_candidates)
+        return B.tperm_plan_create_measured(c.dims, c.perm, c.elem_size, a.data_ptr(), b.data_ptr(),
+                                            self.stream, max_candidates)
+
+    def one_step(self, step_idx, events=None, stream=None):
+        stream = self.stream if stream is None else stream
+        pa, pb = self.a.data_ptr(), self.b.data_ptr()
+        for i, plan in enumerate(self.plans):
+            off = ((step_idx * len(self.plans) + i) % self.places[i]) * self.place[i]
+            if events is not None:
+                events[i].record()
+            self.run(plan, pa + off, pb + off, stream)
+        if events is not None:
+            events[len(self.plans)].record()
+
+    def timed(self, steps, warmup, with_events=True):
+        """K steps between two synchronisations; returns (seconds, per-launch ms [steps x cases])."""
+        torch, np = self.torch, self.np
+        for w in range(warmup):
+            self.one_step(w)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(self.plans) + 1)]
+              for _ in range(steps)] if with_events else None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            self.one_step(s, ev[s] if ev else None)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        dur = None
+        if ev:
+            # per-launch durations from the events recorded inside the timed region
+            dur = np.array([[ev[s][i].elapsed_time(ev[s][i + 1]) for i in range(len(self.plans))]
+                            for s in range(steps)])
+        return elapsed, dur
+
+    def copy_ceiling(self):
+        """Plain-copy rate of this machine at the family's first size (the paper normalises by a
+        measured STREAM figure, Section 3)."""
+        torch, B = self.torch, self.B
+        nbytes = self.cases[0].volume * self.cases[0].elem_size
+        pa, pb = self.a.data_ptr(), self.b.data_ptr()
+        for _ in range(3):
+            B.tperm_copy_bytes(pa, pb, nbytes, self.stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(10):
+            off = (i % self.places[0]) * self.place[0]
+            B.tperm_copy_bytes(pa + off, pb + off, nbytes, self.stream)
+        e1.record()
+        e1.synchronize()
+        return 2 * nbytes * 10 / e0.elapsed_time(e1) / 1e6
+
+    def verify(self, index):
+        """Whole-tensor, bit-for-bit comparison of one case with the CPU oracle (scrambled index
+        stamps as input; outside every timed region)."""
+        import oracle
+        torch, np, wl = self.torch, self.np, self.wl
+        case, plan = self.cases[index], self.plans[index]
+        a = wl.scrambled_stamp_values(case.volume, case.elem_size)
+        sign = np.int64 if case.elem_size == 8 else np.int32
+        a_dev = torch.from_numpy(a.view(sign)).cuda()
+        if self.args.accumulate:
+            b = wl.uniform_values(case)
+            out = torch.from_numpy(b.view(sign)).cuda()
+            ref = oracle.transpose_accumulate(a.view(b.dtype), b, case.dims, case.perm)
+        else:
+            out = torch.full((case.volume,), -1, dtype=a_dev.dtype, device="cuda")
+            ref = oracle.transpose(a, case.dims, case.perm)
+        self.run(plan, a_dev.data_ptr(), out.data_ptr(), self.stream)
+        torch.cuda.synchronize()
+        ok = bool(torch.equal(out, torch.from_numpy(ref.view(sign)).cuda()))
+        return {"case": case.name, "elements": case.volume, "bit_exact": ok}
+
+    def summary(self, steps, warmup):
+        """Time the family and condense the result."""
+        np, B = self.np, self.B
+        elapsed, dur_ms = self.timed(steps, warmup)
+        cases, infos = self.cases, self.infos
+        case_ms = np.median(dur_ms, axis=0)
+        case_bytes = np.array([c.bytes_moved // 2 * self.mem_ops for c in cases], dtype=np.float64)
+        case_gbs = case_bytes / case_ms / 1e6
+        step_bytes = int(case_bytes.sum())
+        value = step_bytes * steps / elapsed / 1e9
+        tile_mask = np.array([i.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
+                              for i in infos])
+        achieved, avg_us = 0.0, None
+        if tile_mask.any():
+            achieved = float(case_bytes[tile_mask].mean() / dur_ms[:, tile_mask].mean() / 1e6)
+            avg_us = round(float(dur_ms[:, tile_mask].mean()) * 1e3, 2)
+        by_rank = {}
+        for c, g in zip(cases, case_gbs):
+            by_rank.setdefault(c.rank, []).append(float(g))
+        rank_median = {str(r): round(float(np.median(v)), 1) for r, v in sorted(by_rank.items())}
+        med = list(rank_median.values())
+        out = {
+            "workload": WORKLOAD_NAMES[self.config], "cases": len(cases), "steps": steps, "warmup": warmup,
+            "dtype": "f64" if cases[0].elem_size == 8 else "f32",
+            "value": round(value, 1), "ms_per_step": round(elapsed / steps * 1e3, 4),
+            "bytes_per_step": step_bytes, "buffer_pairs": self.n_pairs,
+            "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+            "case_median_GBs": round(float(np.median(case_gbs)), 1),
+            "case_min_GBs": round(float(case_gbs.min()), 1),
+            "case_max_GBs": round(float(case_gbs.max()), 1),
+            "median_pct_hbm_peak": round(100.0 * float(np.median(case_gbs)) / HBM_PEAK_GBS, 2),
+            "rank_median_GBs": rank_median,
+            "rank_median_max_over_min": round(max(med) / min(med), 3),
+            "tile_kernel_achieved_GBs": round(achieved, 1),
+            "tile_kernel_frac": round(achieved / HBM_PEAK_GBS, 4),
+            "tile_kernel_avg_launch_us": avg_us,
+            "kernels": {B.KERNEL_NAMES[k]: int(sum(1 for i in infos if i.kernel_class == k))
+                        for k in sorted({i.kernel_class for i in infos})},
+        }
+        lo, hi = str(min(by_rank)), str(max(by_rank))
+        if lo != hi:
+            out["lowest_vs_highest_rank"] = {"rank": [int(lo), int(hi)], "median_GBs": [rank_median[lo], rank_median[hi]],
+                                             "ratio": round(max(rank_median[lo], rank_median[hi]) /
+                                                            min(rank_median[lo], rank_median[hi]), 3)}
+        self.case_gbs, self.case_ms = case_gbs, case_ms
+        return out
+
+
+def device_memory_figures(torch):
+    """What the device itself reports about its memory system, next to the vendor's 8 TB/s."""
+    p = torch.cuda.get_device_properties(0)
+    width = getattr(p, "memory_bus_width", None)
+    clock_khz = getattr(p, "memory_clock_rate", None)
+    out = {"name": p.name, "memory_bus_width_bits": width, "memory_clock_kHz": clock_khz,
+           "compute_units": p.multi_processor_count, "l2_cache_bytes": getattr(p, "L2_cache_size", None)}
+    if width and clock_khz:
+        # double data rate: two transfers per reported clock
+        out["bus_width_x_clock_x2_GBs"] = round(width / 8 * clock_khz * 1e3 * 2 / 1e9, 1)
+    return out
 
 
 def main():
@@ -96,177 +316,81 @@ def main():
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     from paper_1705_01598_amd import binding as B
-    from paper_1705_01598_amd import workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     B.lib()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
 
-    if args.config == 6:
-        cases = wl.set2(args.set2_perms)[:: args.stride]
-    elif args.config == 7:
-        cases = wl.square_sweep()[:: args.stride]
-    else:
-        cases = wl.all_configs()[args.config][:: args.stride]
-    mem_ops = 3 if args.accumulate else 2
-    run = B.tperm_execute_accumulate if args.accumulate else B.tperm_execute
-    elem = cases[0].elem_size
-    max_vol = max(c.volume for c in cases)
-    stream = torch.cuda.current_stream().cuda_stream
-
-    # device-resident input (uniform values of the first case's seed) and output; small
-    # tensors rotate through several buffer pairs so that no launch finds its data in the
-    # 256 MB last-level cache
-    n_pairs = max(1, min(16, int((1 << 30) // (2 * max_vol * elem))))
-    host = wl.uniform_values(wl.make_case(args.config, 0, (max_vol,), (0,), elem))
-    bits = host.view(np.int64 if elem == 8 else np.int32)
-    pairs = []
-    for _ in range(n_pairs):
-        a = torch.from_numpy(bits).to(dev)
-        b = torch.empty_like(a)
-        pairs.append((a, b))
-    del host
-
-    # measurement-based selection of tensors that fit the last-level cache is timed with a
-    # 512 MiB scratch swept between executions, as the data will arrive from HBM in the timed loop
-    scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev) if n_pairs > 1 else None
-
-    def measured_plan(c, max_candidates):
-        a, b = pairs[0]
-        if scratch is not None:
-            return B.tperm_plan_create_measured_cold(c.dims, c.perm, c.elem_size, a.data_ptr(), b.data_ptr(),
-                                                     stream, scratch.data_ptr(), scratch.numel(), max_candidates)
-        return B.tperm_plan_create_measured(c.dims, c.perm, c.elem_size, a.data_ptr(), b.data_ptr(),
-                                            stream, max_candidates)
-
-    plans = []
-    for c in cases:
-        if args.plan == "measured":
-            plans.append(measured_plan(c, args.max_candidates))
-        else:
-            plans.append(B.tperm_plan_create(c.dims, c.perm, c.elem_size))
-    infos = [p.describe() for p in plans]
-
-    def one_step(step_idx, events=None):
-        for i, plan in enumerate(plans):
-            a, b = pairs[(step_idx * len(plans) + i) % n_pairs]
-            if events is not None:
-                events[i].record()
-            run(plan, a.data_ptr(), b.data_ptr(), stream)
-        if events is not None:
-            events[len(plans)].record()
-
-    for w in range(args.warmup):
-        one_step(w)
-    torch.cuda.synchronize()
-
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(plans) + 1)]
-          for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        one_step(s, ev[s])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    # per-launch durations from the events recorded inside the timed region
-    dur_ms = np.array([[ev[s][i].elapsed_time(ev[s][i + 1]) for i in range(len(plans))]
-                       for s in range(args.steps)])
-    case_ms = np.median(dur_ms, axis=0)
-    case_bytes = np.array([c.bytes_moved // 2 * mem_ops for c in cases], dtype=np.float64)
-    case_gbs = case_bytes / case_ms / 1e6
-    step_bytes = int(case_bytes.sum())
-    value = step_bytes * args.steps / elapsed / 1e9
-
-    tile_mask = np.array([i.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
-                          for i in infos])
-    tile_bytes = case_bytes[tile_mask]
-    tile_ms = dur_ms[:, tile_mask]
-    achieved = float(tile_bytes.mean() / tile_ms.mean() / 1e6) if tile_mask.any() else 0.0
-    traffic = TRAFFIC_BYTES_PER_LAUNCH.get(f"c{args.config}")
-
-    # plain-copy ceiling of this machine, same size, for context (the paper normalises by a
-    # measured STREAM figure, Section 3)
-    a, b = pairs[0]
-    nbytes = cases[0].volume * elem
-    for _ in range(3):
-        B.tperm_copy_bytes(a.data_ptr(), b.data_ptr(), nbytes, stream)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(10):
-        a, b = pairs[i % n_pairs]
-        B.tperm_copy_bytes(a.data_ptr(), b.data_ptr(), nbytes, stream)
-    e1.record()
-    e1.synchronize()
-    copy_gbs = 2 * nbytes * 10 / e0.elapsed_time(e1) / 1e6
-
-    by_rank = {}
-    for c, g in zip(cases, case_gbs):
-        by_rank.setdefault(c.rank, []).append(float(g))
-    rank_median = {str(r): round(float(np.median(v)), 1) for r, v in sorted(by_rank.items())}
+    config = args.config or HEADLINE
+    cases = family(args, config)
+    h = Harness(args, config, cases)
+    s = h.summary(args.steps, args.warmup)
+    copy_gbs = h.copy_ceiling()
+    traffic, traffic_source = TRAFFIC.get(config, (None, None))
+    if args.plan != "heuristic" or args.accumulate or args.stride != 1:
+        traffic, traffic_source = None, None
 
     if args.cases_out:
         with open(args.cases_out, "w") as fh:
-            for c, g, ms, info in zip(cases, case_gbs, case_ms, infos):
-                fh.write(json.dumps({"case": c.name, "dims": c.dims, "perm": c.perm,
+            for c, g, ms, info in zip(cases, h.case_gbs, h.case_ms, h.infos):
+                fh.write(json.dumps({"case": c.name, "dims": c.dims, "perm": c.perm, "elem": c.elem_size,
                                      "GBs": float(g), "us": float(ms) * 1e3,
                                      **B.info_dict(info)}) + "\n")
 
-    workload_names = {1: "rank-2 fp64 2048x2048 transpose", 2: "rank-4 fp64 96^4, all 23 non-identity permutations",
-                      3: "rank-6 fp64 ~2^26 elements, 20 seeded cases", 4: "rank sweep 2..12 fp64 ~2^26 elements, 330 seeded cases",
-                      5: "fp32 contraction-feeding transposes 8^8 and 16^6, 80 seeded permutations",
-                      6: "the paper's rank-8 (205M el) and rank-12 (328M el) fp64 shapes, seeded permutations + trivial + reverse",
-                      7: "square fp32 matrices, side 13952..13968"}
     result = {
         "metric": "transpose GB/s (read+write bytes / time) and % of MI355X HBM peak, median/rank",
-        "value": round(value, 1),
+        "value": s["value"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "ms_per_step": s["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f64" if elem == 8 else "f32",
+        "dtype": s["dtype"],
         "data": "synthetic",
-        "config": {"workload": workload_names[args.config], "cases": len(cases),
-                   "bytes_per_step": step_bytes, "plan": args.plan, "buffer_pairs": n_pairs,
+        "config": {"workload": s["workload"], "cases": len(cases),
+                   "bytes_per_step": s["bytes_per_step"], "plan": args.plan, "buffer_pairs": h.n_pairs,
                    "mode": "accumulate (3 memory ops per element)" if args.accumulate else "transpose"},
-        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "case_median_GBs": round(float(np.median(case_gbs)), 1),
-        "case_min_GBs": round(float(case_gbs.min()), 1),
-        "case_max_GBs": round(float(case_gbs.max()), 1),
-        "median_pct_hbm_peak": round(100.0 * float(np.median(case_gbs)) / HBM_PEAK_GBS, 2),
-        "rank_median_GBs": rank_median,
+        "pct_hbm_peak": s["pct_hbm_peak"],
+        "case_median_GBs": s["case_median_GBs"],
+        "case_min_GBs": s["case_min_GBs"],
+        "case_max_GBs": s["case_max_GBs"],
+        "median_pct_hbm_peak": s["median_pct_hbm_peak"],
+        "rank_median_GBs": s["rank_median_GBs"],
         "copy_ceiling_GBs": round(copy_gbs, 1),
-        "kernels": {B.KERNEL_NAMES[k]: int(sum(1 for i in infos if i.kernel_class == k))
-                    for k in sorted({i.kernel_class for i in infos})},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "kernel": "tperm::tile_kernel",
-                     "avg_launch_us": round(float(tile_ms.mean()) * 1e3, 2) if tile_mask.any() else None},
+        "kernels": s["kernels"],
+        "device": device_memory_figures(torch),
+        "roofline": {"bound": "hbm", "achieved": s["tile_kernel_achieved_GBs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": s["tile_kernel_frac"],
+                     "traffic": traffic, "traffic_source": traffic_source, "kernel": "tperm::tile_kernel",
+                     "avg_launch_us": s["tile_kernel_avg_launch_us"]},
     }
+    if config == 8 and args.plan == "heuristic":
+        # selector check: the same cases with measurement-selected plans, case by case
+        heur = h.case_gbs.copy()
+        h.plans[:] = [h.measured_plan(c, 0) for c in cases]
+        h.infos = [p.describe() for p in h.plans]
+        h.summary(args.steps, args.warmup)
+        ratio = heur / h.case_gbs
+        import numpy as np
+        result["heuristic_over_measured"] = {"mean": round(float(ratio.mean()), 4), "median": round(float(np.median(ratio)), 4),
+                                             "min": round(float(ratio.min()), 4),
+                                             "worst_case": cases[int(ratio.argmin())].name}
     if args.also_measured and args.plan == "heuristic":
         # Section 2.3's other selection scheme, for comparison: plans chosen by timing every
         # candidate once at plan creation (outside any timed region)
-        mplans = [measured_plan(c, 64) for c in cases]
-        plans[:] = mplans
-        for w in range(args.warmup):
-            one_step(w)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for s in range(args.steps):
-            one_step(s)
-        torch.cuda.synchronize()
-        result["measured_plans_value"] = round(step_bytes * args.steps / (time.perf_counter() - t0) / 1e9, 1)
+        if h.n_pairs > 1 and h.scratch is None:
+            h.scratch = torch.empty(512 << 20, dtype=torch.uint8, device="cuda:0")
+        h.plans[:] = [h.measured_plan(c, 64) for c in cases]
+        elapsed, _ = h.timed(args.steps, args.warmup, with_events=False)
+        result["measured_plans_value"] = round(s["bytes_per_step"] * args.steps / elapsed / 1e9, 1)
     if args.also_graph:
         # the same step as a HIP graph: what a caller with a fixed sequence of transposes gets
         # once the gaps between dependent launches are gone (one buffer pair per launch as in
@@ -275,18 +399,41 @@ def main():
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            gs = torch.cuda.current_stream().cuda_stream
-            for i, plan in enumerate(plans):
-                a, b = pairs[i % n_pairs]
-                run(plan, a.data_ptr(), b.data_ptr(), gs)
+            h.one_step(0, stream=torch.cuda.current_stream().cuda_stream)
         for w in range(max(1, args.warmup)):
             graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(args.steps):
+        for _ in range(args.steps):
             graph.replay()
         torch.cuda.synchronize()
-        result["graph_value"] = round(step_bytes * args.steps / (time.perf_counter() - t0) / 1e9, 1)
+        result["graph_value"] = round(s["bytes_per_step"] * args.steps / (time.perf_counter() - t0) / 1e9, 1)
+
+    checks = []
+    if not args.no_verify and args.plan == "heuristic":
+        checks.append(h.verify(len(cases) // 2))
+    if args.config == 0:
+        # the other four families, same harness, each with its own buffers
+        per = {f"c{HEADLINE}": {k: v for k, v in s.items()}}
+        del h
+        torch.cuda.empty_cache()
+        for other, (steps, warmup) in SIDE_STEPS.items():
+            oc = family(args, other)
+            oh = Harness(args, other, oc)
+            per[f"c{other}"] = oh.summary(steps, warmup)
+            per[f"c{other}"]["copy_ceiling_GBs"] = round(oh.copy_ceiling(), 1)
+            if not args.no_verify and args.plan == "heuristic":
+                checks.append(oh.verify(len(oc) // 2))
+            del oh
+            torch.cuda.empty_cache()
+        result["per_config"] = dict(sorted(per.items()))
+        medians = [v["case_median_GBs"] for v in per.values()]
+        result["all_configs_min_case_median_pct_hbm_peak"] = round(100.0 * min(medians) / HBM_PEAK_GBS, 2)
+    if checks:
+        result["verified"] = checks
+        if not all(c["bit_exact"] for c in checks):
+            print("bench.py: a timed plan does not reproduce the CPU oracle: " + json.dumps(checks), file=sys.stderr)
+            sys.exit(1)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cases)
     print(json.dumps(result))

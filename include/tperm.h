@@ -63,45 +63,6 @@ typedef enum {
     TPERM_KERNEL_NAIVE = 5    /* one thread per output element, no staging (debug anchor)      */
 } tperm_kernel_class_t;
 
-/* Optional overrides for plan creation.  Zero-initialise; 0 always means "let the
- * selector decide". */
-typedef struct {
-    int kernel_class;   /* tperm_kernel_class_t                                              */
-    int m;              /* number of leading INPUT dims (canonical) taken into the tile      */
-    int64_t tile_in;    /* tile extent of the last of those m dims (0 = full extent)         */
-    int k;              /* number of leading OUTPUT dims (canonical) taken into the tile     */
-    int64_t tile_out;   /* tile extent of the last of those k dims (0 = full extent)         */
-    int lds_pad;        /* -1 = search; >= 0 forces the LDS row padding (elements)           */
-    int grid_mode;      /* 0 = default; -1 = tiles in launch order; 1 = one contiguous tile   */
-                        /* range per XCD; 2 + g = groups of 2^g consecutive tiles dealt to    */
-                        /* the XCDs in turn                                                   */
-    int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
-    int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal loads and stores; */
-                        /* 3 = nontemporal stores only; 4 = nontemporal loads only            */
-    int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
-    int window_out;     /* on the input / output side; 1 = no window; 0 = default (none on    */
-                        /* the output side; on the input side only a few ragged chunks of the */
-                        /* input run are kept together)                                       */
-    int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
-    int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
-    int align_out;      /* line-aligned output windows (tiles read a one-line halo along the  *
-                         * output's leading dim, every row writes a window shifted to whole  *
-                         * 128-byte lines): 0 = the selector decides, 1 = off, 2 = on where   *
-                         * the tile allows it (k = 1, tile_out a multiple of one line)        */
-    int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
-    int loads_first;    /* order in which a workgroup issues the next tile's loads and this  *
-                         * tile's stores: 0 = selector's default; 1 = stores first; 2 = loads *
-                         * first                                                              */
-    int vec2;           /* transposing 4-byte plans with 8-byte global accesses (see `vec2`  *
-                         * below): 0 = default (a twin plan is kept for 8-byte aligned       *
-                         * pointers), 1 = off, 2 = in this plan itself where the shape       *
-                         * allows, which then requires 8-byte aligned pointers (except with  *
-                         * line-aligned output windows, which form their pairs on absolute  *
-                         * addresses and take any element-aligned pointer)                   */
-    int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (see `paired` below): *
-                         * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
-} tperm_plan_opts_t;
-
 /* What a plan decided.  Canonical = after dropping extent-1 dims and fusing input dims
  * that stay adjacent and in order in the output. */
 typedef struct {
@@ -124,8 +85,12 @@ typedef struct {
     int lds_pad;
     double score;                          /* selector's estimate (relative, lower = better)*/
     int blocks_per_cu;                     /* cap on resident workgroups per CU (0 = none)  */
-    int cache_policy;                      /* 1 = cached, 2 = nontemporal, 3 = nt stores,   *
-                                            * 4 = nt loads                                  */
+    int cache_policy;                      /* policy of the kernel variant tperm_execute    *
+                                            * launches when `out` is 32-byte aligned:       *
+                                            * 1 = cached, 2 = nontemporal loads and stores, *
+                                            * 3 = nontemporal stores, 4 = nontemporal loads *
+                                            * (from any other `out` the stores are cached:  *
+                                            * 2 runs as 4, 3 as 1); accumulation is cached   */
     int align_out;                         /* 1 if the plan writes line-aligned windows     */
     int paired;                            /* 1: a 4-byte problem whose stride-1 dimension  *
                                             * stays in front and has an even extent is run  *
@@ -153,30 +118,28 @@ typedef struct {
     int reserved[2];
 } tperm_plan_info_t;
 
-/* Create a plan.  dims[rank] and perm[rank] are host arrays, copied.  On failure *plan is
- * set to NULL.  elem_size is in bytes (4 or 8). */
+/* Create a plan: the first call of the create / execute / destroy triple of Section 2.3.  The
+ * plan selector validates the problem, brings it to canonical form and chooses a kernel class
+ * and a tile with its cost estimate (the paper's heuristic selection, Section 2.3; its
+ * classes are those of Section 2.2).  dims[rank] and perm[rank] are host arrays, copied; the
+ * caller keeps ownership.  elem_size is in bytes (4 or 8, the two widths of Section 3).  Host
+ * only.  On failure *plan is set to NULL and the status says why: NULL (plan, dims or perm),
+ * RANK, DIMS, PERM, ELEM_SIZE, TOO_LARGE, NOMEM. */
 tperm_status_t tperm_plan_create(tperm_plan_t *plan, int rank, const int64_t *dims,
                                  const int *perm, size_t elem_size);
 
-/* Same, with overrides (tests, sweeps).  opts may be NULL.  A kernel class that cannot
- * legally run the problem gives TPERM_ERR_KERNEL. */
-tperm_status_t tperm_plan_create_ex(tperm_plan_t *plan, int rank, const int64_t *dims,
-                                    const int *perm, size_t elem_size,
-                                    const tperm_plan_opts_t *opts);
+/* The same with the kernel class chosen by the caller instead of the selector (Section 2.2's
+ * classes run side by side on one problem: tests, comparisons); the tile inside the class is
+ * still the selector's best.  kernel_class is a tperm_kernel_class_t; TPERM_KERNEL_AUTO
+ * behaves as tperm_plan_create.  A class that cannot legally run the problem (a plain copy for
+ * a real permutation, a row copy when the stride-1 dimension moves, ...) gives
+ * TPERM_ERR_KERNEL. */
+tperm_status_t tperm_plan_create_forced(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                        const int *perm, size_t elem_size, int kernel_class);
 
-/* Enumeration of the feasible staged plans (Section 2.3: every plan that can run is
- * created, then one is kept).  tperm_plan_candidate_count returns how many tile candidates
- * the selector sees for the problem, best estimate first; tperm_plan_create_candidate
- * builds the plan for candidate `index`.  Host only.  Problems whose canonical form is a
- * copy have no candidates. */
-tperm_status_t tperm_plan_candidate_count(int rank, const int64_t *dims, const int *perm,
-                                          size_t elem_size, int *count);
-tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const int64_t *dims,
-                                           const int *perm, size_t elem_size, int index);
-
-/* Measurement-based plan selection (Section 2.3): every candidate plan the selector
- * enumerates is executed on (in, out) on `hip_stream` and timed with HIP events; the
- * fastest is kept.  in/out are device buffers of at least volume*elem_size bytes; out is
+/* Measurement-based plan selection (Section 2.3: all feasible plans are created and run once,
+ * the fastest is kept): every candidate plan the selector enumerates is executed on (in, out)
+ * on `hip_stream` and timed with HIP events; the fastest is kept.  in/out are device buffers of at least volume*elem_size bytes; out is
  * overwritten.  Synchronises the stream.  max_candidates <= 0 means all.  The candidates
  * are timed back to back on these buffers as they are: a tensor small enough to stay in the
  * last-level cache is timed cache-hot, which need not rank the plans as HBM-resident data
@@ -199,10 +162,14 @@ tperm_status_t tperm_plan_create_measured_cold(tperm_plan_t *plan, int rank, con
                                                void *out, void *hip_stream, int max_candidates,
                                                void *scratch, size_t scratch_bytes);
 
-/* Enqueue the transpose on hip_stream (a hipStream_t; NULL = the default stream) and
- * return without synchronising.  in: device pointer to volume*elem_size bytes, read
- * only.  out: device pointer to volume*elem_size bytes, fully overwritten; must not
- * overlap in.  A plan is immutable: concurrent executes on several streams are allowed. */
+/* Execute: the second call of the triple of Section 2.3.  Performs the transpose of Section 2
+ * (Eq. (1)) with the plan's kernel: enqueues it on hip_stream (a hipStream_t; NULL = the
+ * default stream) and returns without synchronising.  in: DEVICE pointer to volume*elem_size
+ * bytes, read only.  out: DEVICE pointer to volume*elem_size bytes, fully overwritten; must not
+ * overlap in.  Both stay owned by the caller and need only be aligned to the element size.  A
+ * plan is immutable: concurrent executes on several streams are allowed.  Statuses: NULL,
+ * ALIAS (in == out or overlapping ranges), ALIGN, HIP (no device, launch failure); no device
+ * memory is allocated or freed. */
 tperm_status_t tperm_execute(tperm_plan_t plan, const void *in, void *out, void *hip_stream);
 
 /* Accumulating variant (the mode the paper uses for its third benchmark set, Section 3.3:
@@ -213,22 +180,18 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void *in, void *out, void 
 tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void *in, void *out,
                                         void *hip_stream);
 
-/* Fill *info from the plan (host only). */
+/* What the selector decided for this plan (Section 2.3: kernel class, tile, launch shape),
+ * written to *info, which the caller owns.  Host only.  NULL plan or info: TPERM_ERR_NULL. */
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);
 
-/* Host-only self check of a plan's index arithmetic: runs, on the CPU, the very offset
- * computations the kernel performs (tile enumeration, major/minor offsets, LDS slots,
- * edge masks) and records, for every output scalar position o, the input scalar position
- * whose element the kernel would store there.  out_to_in has volume entries; entries
- * never written are -1.  Returns TPERM_ERR_INTERNAL if an output position is written
- * twice, an LDS slot is read before it is written, or an offset leaves the tensor.
- * Moves no tensor data; meant for volumes small enough to enumerate.  For a paired plan
- * (see tperm_plan_info_t.paired) the map evaluated is that of the 8-byte twin, written out
- * per 4-byte element. */
-tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
-
+/* Destroy: the third call of the triple of Section 2.3.  Frees the plan's host memory (a plan
+ * owns no device memory).  The caller must not destroy a plan whose launches have not been
+ * enqueued yet on another thread; launches already enqueued are unaffected (the descriptor
+ * travels with each launch).  NULL: TPERM_ERR_NULL. */
 tperm_status_t tperm_plan_destroy(tperm_plan_t plan);
 
+/* Static, NUL-terminated description of a status code (the error reporting that the paper's
+ * interface of Section 2.3 leaves open); never NULL, "unknown status" for other values. */
 const char *tperm_status_string(tperm_status_t s);
 
 /*
@@ -262,8 +225,10 @@ tperm_status_t tperm_cache_tune(int rank, const int64_t *dims, const int *perm, 
 tperm_status_t tperm_cache_stats(int64_t *entries, int64_t *hits, int64_t *misses);
 tperm_status_t tperm_cache_clear(void);
 
-/* Plain device-to-device copy of nbytes with the library's copy kernel (the bandwidth
- * ceiling the transposes are compared with, in the way Section 3 uses a STREAM figure). */
+/* Plain device-to-device copy of nbytes with the library's copy kernel: the measured bandwidth
+ * ceiling the transposes are compared with, in the way Section 3 normalises by a STREAM
+ * figure.  in / out: DEVICE pointers, 4-byte aligned, nbytes a multiple of 4 (ALIGN otherwise),
+ * not equal (ALIAS); asynchronous on hip_stream. */
 tperm_status_t tperm_copy_bytes(const void *in, void *out, size_t nbytes, void *hip_stream);
 
 #ifdef __cplusplus

@@ -1,0 +1,91 @@
+/*
+ * tperm -- tuning and test interface.
+ *
+ * Everything a sweep, a test or a tuning tool needs beyond the product boundary of tperm.h:
+ * plan creation with explicit overrides of every choice the selector makes (Section 2.2's
+ * kernel classes and tiles, and the launch details this implementation adds), the list of
+ * candidate plans behind Section 2.3's "create every feasible plan, keep one", and a host-side
+ * evaluation of a plan's index maps (Eqs. (2)-(6) as the kernel computes them).  Nothing here
+ * is needed to transpose a tensor; the layout of tperm_plan_opts_t may grow between versions.
+ */
+#ifndef TPERM_TUNING_H
+#define TPERM_TUNING_H
+
+#include "tperm.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Optional overrides for plan creation.  Zero-initialise; 0 always means "let the
+ * selector decide". */
+typedef struct {
+    int kernel_class;   /* tperm_kernel_class_t                                              */
+    int m;              /* number of leading INPUT dims (canonical) taken into the tile      */
+    int64_t tile_in;    /* tile extent of the last of those m dims (0 = full extent)         */
+    int k;              /* number of leading OUTPUT dims (canonical) taken into the tile     */
+    int64_t tile_out;   /* tile extent of the last of those k dims (0 = full extent)         */
+    int lds_pad;        /* -1 = search; >= 0 forces the LDS row padding (elements)           */
+    int grid_mode;      /* 0 = default; -1 = tiles in launch order; 1 = one contiguous tile   */
+                        /* range per XCD; 2 + g = groups of 2^g consecutive tiles dealt to    */
+                        /* the XCDs in turn                                                   */
+    int blocks_per_cu;  /* > 0 caps the resident workgroups per compute unit                 */
+    int cache_policy;   /* 0 = selector's default; 1 = cached; 2 = nontemporal loads and stores; */
+                        /* 3 = nontemporal stores only; 4 = nontemporal loads only            */
+    int window_in;      /* tiles in flight are grouped into windows of this many neighbours   */
+    int window_out;     /* on the input / output side; 1 = no window; 0 = default (none on    */
+                        /* the output side; on the input side only a few ragged chunks of the */
+                        /* input run are kept together)                                       */
+    int threads;        /* workgroup size of the tile kernel: 0 = default, 64 or 256          */
+    int lds_buffers;    /* 0 = default; 1 or 2 LDS images (2: one barrier per tile)           */
+    int align_out;      /* line-aligned output windows (tiles read a one-line halo along the  *
+                         * output's leading dim, every row writes a window shifted to whole  *
+                         * 128-byte lines): 0 = the selector decides, 1 = off, 2 = on where   *
+                         * the tile allows it (k = 1, tile_out a multiple of one line)        */
+    int tile_order;     /* 0 = default, 1 = input-major, 2 = output-major walk over the tiles */
+    int loads_first;    /* order in which a workgroup issues the next tile's loads and this  *
+                         * tile's stores: 0 = selector's default; 1 = stores first; 2 = loads *
+                         * first                                                              */
+    int vec2;           /* transposing 4-byte plans with 8-byte global accesses (vec2 in      *
+                         * tperm_plan_info_t): 0 = default (a twin plan is kept for 8-byte aligned       *
+                         * pointers), 1 = off, 2 = in this plan itself where the shape       *
+                         * allows, which then requires 8-byte aligned pointers (except with  *
+                         * line-aligned output windows, which form their pairs on absolute  *
+                         * addresses and take any element-aligned pointer)                   */
+    int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (paired in plan info): *
+                         * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
+} tperm_plan_opts_t;
+
+/* tperm_plan_create with overrides.  opts may be NULL (then it is tperm_plan_create).  A
+ * kernel class or tile that cannot legally run the problem gives TPERM_ERR_KERNEL.  Host only;
+ * opts is read during the call and not kept. */
+tperm_status_t tperm_plan_create_ex(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                    const int *perm, size_t elem_size,
+                                    const tperm_plan_opts_t *opts);
+
+/* Enumeration of the feasible staged plans (Section 2.3: every plan that can run is
+ * created, then one is kept).  tperm_plan_candidate_count returns how many tile candidates
+ * the selector sees for the problem, best estimate first; tperm_plan_create_candidate
+ * builds the plan for candidate `index` (TPERM_ERR_KERNEL if out of range).  Host only.
+ * Problems whose canonical form is a copy have no candidates. */
+tperm_status_t tperm_plan_candidate_count(int rank, const int64_t *dims, const int *perm,
+                                          size_t elem_size, int *count);
+tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const int64_t *dims,
+                                           const int *perm, size_t elem_size, int index);
+
+/* Host-only self check of a plan's index arithmetic: runs, on the CPU, the very offset
+ * computations the kernel performs (tile enumeration, major/minor offsets, LDS slots,
+ * edge masks) and records, for every output scalar position o, the input scalar position
+ * whose element the kernel would store there.  out_to_in has volume entries; entries
+ * never written are -1.  Returns TPERM_ERR_INTERNAL if an output position is written
+ * twice, an LDS slot is read before it is written, or an offset leaves the tensor.
+ * Moves no tensor data; meant for volumes small enough to enumerate.  For a paired plan
+ * (see tperm_plan_info_t.paired) the map evaluated is that of the 8-byte twin, written out
+ * per 4-byte element. */
+tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
+
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPERM_TUNING_H */

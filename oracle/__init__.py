@@ -18,6 +18,7 @@ Four independent forms of the same definition live here:
                          Fortran-ordered view
 ``transpose_bruteforce`` pure-Python nested loops over every multi-index
 ``transpose_accumulate`` C, out + transposed in (the paper's accumulate mode)
+``contract``             C, D + L * R as a direct loop nest (the contraction of Section 3.4)
 
 All forms move raw bytes (arrays are viewed as unsigned integers of the element
 size), so results are compared bit for bit.
@@ -68,6 +69,10 @@ def _load():
         lib.tto_sample.argtypes = [ctypes.c_int, i64p, i32p, ctypes.c_size_t, ctypes.c_void_p,
                                    ctypes.c_int64, i64p, ctypes.c_void_p]
         lib.tto_sample.restype = ctypes.c_int
+        lib.tto_contract.argtypes = [ctypes.c_int, i64p, ctypes.c_int, i32p, ctypes.c_int, i32p,
+                                     ctypes.c_int, i32p, ctypes.c_size_t, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_void_p]
+        lib.tto_contract.restype = ctypes.c_int
         lib.tto_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -151,6 +156,35 @@ def transpose_accumulate(a: np.ndarray, b: np.ndarray, dims: Sequence[int],
     rc = lib.tto_transpose_accumulate(rank, cd, cp, a.dtype.itemsize, a.ctypes.data, out.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return out
+
+
+def contract(d_labels: str, l_labels: str, r_labels: str, extents: dict, l: np.ndarray,
+             r: np.ndarray, d: np.ndarray) -> np.ndarray:
+    """Binary tensor contraction as a direct loop nest: returns d + l * r.
+
+    Tensors are flat float64 (or float32) buffers; the label strings name their dimensions,
+    first label = stride-1 dimension.  Labels shared by ``l_labels`` and ``r_labels`` and absent
+    from ``d_labels`` are summed over, in double precision and in a fixed order; every other
+    label occurs in ``d_labels`` and in exactly one input.  ``d`` is not modified."""
+    lib = _load()
+    names = sorted(set(d_labels + l_labels + r_labels))
+    num = {c: i for i, c in enumerate(names)}
+    ext = (ctypes.c_int64 * len(names))(*[int(extents[c]) for c in names])
+    idx = lambda s: (ctypes.c_int * len(s))(*[num[c] for c in s])
+    l = np.ascontiguousarray(l).reshape(-1)
+    r = np.ascontiguousarray(r).reshape(-1)
+    out = np.array(d, copy=True).reshape(-1)
+    if not (l.dtype == r.dtype == out.dtype) or out.dtype not in (np.float32, np.float64):
+        raise ValueError("contract needs float32 or float64 buffers of one dtype")
+    vol = lambda s: int(np.prod([int(extents[c]) for c in s], dtype=object))
+    if l.size != vol(l_labels) or r.size != vol(r_labels) or out.size != vol(d_labels):
+        raise ValueError("buffer size does not match the labels' extents")
+    rc = lib.tto_contract(len(names), ext, len(d_labels), idx(d_labels), len(l_labels), idx(l_labels),
+                          len(r_labels), idx(r_labels), out.dtype.itemsize, l.ctypes.data, r.ctypes.data,
+                          out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle rejected the contraction (code {rc})")
     return out
 
 

@@ -206,6 +206,91 @@ int tto_sample(int rank, const int64_t *dims, const int *perm, size_t elem,
     return TTO_OK;
 }
 
+/*
+ * Binary tensor contraction D = D + L * R (the operation of Section 3.4, written as the
+ * direct loop nest that Section 1 calls the direct approach): every element of D receives the
+ * sum, over all values of the contracted labels, of the product of the matching elements of L
+ * and R.
+ *
+ * Labels are numbered 0..nlab-1 with extents ext[].  Each tensor is a flat buffer whose
+ * dimensions are the labels listed in dl / ll / rl, first one = stride-1 dimension.  Labels
+ * that occur in both ll and rl and not in dl are summed over; the products of one output
+ * element are added in double precision in a fixed order (summed labels in the order they
+ * appear in ll, the first of them running fastest), then that sum is added to D once.
+ * elem = 8: buffers are double; elem = 4: buffers are float, widened for the arithmetic and
+ * rounded to float once at the end.  No blocking, no reordering, one output element at a time.
+ */
+int tto_contract(int nlab, const int64_t *ext, int nd, const int *dl, int nl, const int *ll,
+                 int nr, const int *rl, size_t elem, const void *l, const void *r, void *d)
+{
+    int in_d[TTO_MAX_RANK], in_l[TTO_MAX_RANK], in_r[TTO_MAX_RANK];
+    int64_t sd[TTO_MAX_RANK], sl[TTO_MAX_RANK], sr[TTO_MAX_RANK];   /* stride of a label, 0 if absent */
+    int summed[TTO_MAX_RANK], ns = 0;
+    if (nlab < 1 || nlab > TTO_MAX_RANK || nd < 1 || nl < 1 || nr < 1) return TTO_BAD_RANK;
+    if (nd > nlab || nl > nlab || nr > nlab) return TTO_BAD_RANK;
+    if (elem != 4 && elem != 8) return TTO_BAD_ELEM;
+    for (int a = 0; a < nlab; ++a) {
+        if (ext[a] < 1) return TTO_BAD_DIMS;
+        in_d[a] = in_l[a] = in_r[a] = 0;
+        sd[a] = sl[a] = sr[a] = 0;
+    }
+    int64_t c = 1;
+    for (int j = 0; j < nd; ++j) {
+        if (dl[j] < 0 || dl[j] >= nlab || in_d[dl[j]]) return TTO_BAD_PERM;
+        in_d[dl[j]] = 1; sd[dl[j]] = c; c *= ext[dl[j]];
+    }
+    c = 1;
+    for (int j = 0; j < nl; ++j) {
+        if (ll[j] < 0 || ll[j] >= nlab || in_l[ll[j]]) return TTO_BAD_PERM;
+        in_l[ll[j]] = 1; sl[ll[j]] = c; c *= ext[ll[j]];
+    }
+    c = 1;
+    for (int j = 0; j < nr; ++j) {
+        if (rl[j] < 0 || rl[j] >= nlab || in_r[rl[j]]) return TTO_BAD_PERM;
+        in_r[rl[j]] = 1; sr[rl[j]] = c; c *= ext[rl[j]];
+    }
+    /* every label: either summed (in L and R, not in D) or free (in D and exactly one input) */
+    for (int a = 0; a < nlab; ++a) {
+        const int s = in_l[a] && in_r[a] && !in_d[a];
+        const int f = in_d[a] && (in_l[a] != in_r[a]);
+        if (!s && !f) return TTO_BAD_PERM;
+    }
+    for (int j = 0; j < nl; ++j)
+        if (in_r[ll[j]]) summed[ns++] = ll[j];
+    int64_t vol_d = 1, vol_s = 1;
+    for (int j = 0; j < nd; ++j) vol_d *= ext[dl[j]];
+    for (int j = 0; j < ns; ++j) vol_s *= ext[summed[j]];
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < vol_d; ++o) {
+        int64_t coord[TTO_MAX_RANK];
+        int64_t rem = o;
+        for (int j = 0; j < nd; ++j) {          /* coordinates of the free labels from o */
+            coord[dl[j]] = rem % ext[dl[j]];
+            rem /= ext[dl[j]];
+        }
+        double acc = 0.0;
+        for (int64_t q = 0; q < vol_s; ++q) {
+            int64_t t = q;
+            for (int j = 0; j < ns; ++j) {      /* coordinates of the summed labels from q */
+                coord[summed[j]] = t % ext[summed[j]];
+                t /= ext[summed[j]];
+            }
+            int64_t pl = 0, pr = 0;
+            for (int a = 0; a < nlab; ++a) {
+                if (in_l[a]) pl += coord[a] * sl[a];
+                if (in_r[a]) pr += coord[a] * sr[a];
+            }
+            const double x = elem == 8 ? ((const double *)l)[pl] : (double)((const float *)l)[pl];
+            const double y = elem == 8 ? ((const double *)r)[pr] : (double)((const float *)r)[pr];
+            volatile double prod = x * y;       /* a rounded product, then a rounded sum */
+            acc = acc + prod;
+        }
+        if (elem == 8) ((double *)d)[o] = ((double *)d)[o] + acc;
+        else ((float *)d)[o] = (float)((double)((float *)d)[o] + acc);
+    }
+    return TTO_OK;
+}
+
 int tto_max_threads(void)
 {
 #ifdef _OPENMP

@@ -1,4 +1,6 @@
-"""ctypes binding of libtperm.so: same names as the C ABI in include/tperm.h.
+"""ctypes binding of libtperm.so: same names as the C ABI in include/tperm.h (the product
+boundary) and include/tperm_tuning.h (overrides, candidate enumeration and the host-side index
+map, for tests and sweeps).
 
 Argument marshalling only.  Every step of the transpose runs in the library's kernels;
 there is no Python or CPU fallback: if the shared library is missing, loading fails.
@@ -23,12 +25,15 @@ KERNEL_AUTO, KERNEL_COPY, KERNEL_ROWCOPY, KERNEL_TILED, KERNEL_PACKED, KERNEL_NA
 KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowcopy",
                 KERNEL_TILED: "tiled", KERNEL_PACKED: "packed", KERNEL_NAIVE: "naive"}
 
-EXPORTS = ["tperm_plan_create", "tperm_plan_create_ex", "tperm_plan_create_measured",
+# include/tperm.h
+EXPORTS = ["tperm_plan_create", "tperm_plan_create_forced", "tperm_plan_create_measured",
            "tperm_plan_create_measured_cold",
-           "tperm_plan_candidate_count", "tperm_plan_create_candidate",
-           "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_index_map", "tperm_plan_destroy",
+           "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes", "tperm_transpose", "tperm_transpose_accumulate",
            "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
+# include/tperm_tuning.h
+TUNING_EXPORTS = ["tperm_plan_create_ex", "tperm_plan_candidate_count", "tperm_plan_create_candidate",
+                  "tperm_plan_index_map"]
 
 
 class PlanOpts(ctypes.Structure):
@@ -78,6 +83,8 @@ def lib() -> ctypes.CDLL:
         i64p = ctypes.POINTER(ctypes.c_int64)
         ip = ctypes.POINTER(ctypes.c_int)
         L.tperm_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip, ctypes.c_size_t]
+        L.tperm_plan_create_forced.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip, ctypes.c_size_t,
+                                               ctypes.c_int]
         L.tperm_plan_create_ex.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
                                            ctypes.c_size_t, ctypes.POINTER(PlanOpts)]
         L.tperm_plan_create_measured.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ip,
@@ -101,7 +108,7 @@ def lib() -> ctypes.CDLL:
         L.tperm_cache_clear.argtypes = []
         L.tperm_status_string.argtypes = [ctypes.c_int]
         L.tperm_status_string.restype = ctypes.c_char_p
-        for name in EXPORTS:
+        for name in EXPORTS + TUNING_EXPORTS:
             if name != "tperm_status_string":
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -153,6 +160,16 @@ def tperm_plan_create(dims: Sequence[int], perm: Sequence[int], elem_size: int) 
     st = lib().tperm_plan_create(ctypes.byref(h), rank, cd, cp, int(elem_size))
     if st != OK:
         raise TpermError(st, "tperm_plan_create")
+    return Plan(h)
+
+
+def tperm_plan_create_forced(dims: Sequence[int], perm: Sequence[int], elem_size: int,
+                             kernel_class: int) -> Plan:
+    rank, cd, cp = _marshal(dims, perm)
+    h = ctypes.c_void_p()
+    st = lib().tperm_plan_create_forced(ctypes.byref(h), rank, cd, cp, int(elem_size), int(kernel_class))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_create_forced")
     return Plan(h)
 
 

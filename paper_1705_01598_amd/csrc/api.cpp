@@ -1,4 +1,4 @@
-// C-ABI entry points declared in include/tperm.h.
+// C-ABI entry points declared in include/tperm.h and include/tperm_tuning.h.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -7,7 +7,7 @@
 #include <mutex>
 #include <vector>
 
-#include "../../include/tperm.h"
+#include "../../include/tperm_tuning.h"
 #include "kernels.hpp"
 #include "plan.hpp"
 
@@ -16,7 +16,9 @@ using tperm::Plan;
 // One executable plan plus the launch geometry resolved for it on first use.
 struct PlanSlot {
     Plan* p = nullptr;
-    std::atomic<int> max_blocks{0};  // resident workgroups on the whole device; 0 = unknown
+    // (device ordinal + 1) << 32 | resident workgroups of this plan's kernel on that whole
+    // device; 0 = not resolved yet.  Resolved again when the current device is another one.
+    std::atomic<uint64_t> geometry{0};
 };
 
 struct tperm_plan_s {
@@ -25,7 +27,7 @@ struct tperm_plan_s {
     // and has an even extent: the same bytes described as 8-byte elements with that extent
     // halved.  Half the memory instructions per byte; needs 8-byte aligned pointers.
     PlanSlot wide;
-    std::atomic<int> num_cu{0};
+    std::atomic<uint64_t> cu_count{0};  // (device ordinal + 1) << 32 | compute units, for the copy class
     ~tperm_plan_s() {
         delete base.p;
         delete wide.p;
@@ -36,18 +38,49 @@ namespace {
 
 tperm_status_t device_cu_count(int* num_cu) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return TPERM_ERR_HIP;
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
         return TPERM_ERR_HIP;
+    }
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
     *num_cu = n;
     return TPERM_OK;
 }
 
-// Number of workgroups to launch for a tile plan: as many as the device keeps resident.
-tperm_status_t resolve_grid(tperm_plan_s* handle, PlanSlot* h, int* grid) {
-    int mb = h->max_blocks.load(std::memory_order_acquire);
-    if (mb == 0) {
+// Compute units of the current device, remembered per plan for the device it was asked on.
+tperm_status_t cached_cu_count(tperm_plan_s* handle, int* num_cu) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    const uint64_t seen = handle->cu_count.load(std::memory_order_acquire);
+    if ((seen >> 32) == (uint64_t)dev + 1u) {
+        *num_cu = (int)(seen & 0xFFFFFFFFu);
+        return TPERM_OK;
+    }
+    tperm_status_t st = device_cu_count(num_cu);
+    if (st != TPERM_OK) return st;
+    handle->cu_count.store((((uint64_t)dev + 1u) << 32) | (uint64_t)*num_cu, std::memory_order_release);
+    return TPERM_OK;
+}
+
+// Number of workgroups to launch for a tile plan: as many as the current device keeps resident.
+tperm_status_t resolve_grid(PlanSlot* h, int* grid) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    const uint64_t seen = h->geometry.load(std::memory_order_acquire);
+    int mb = 0;
+    if ((seen >> 32) == (uint64_t)dev + 1u) {
+        mb = (int)(seen & 0xFFFFFFFFu);
+    } else {
         int num_cu = 0;
         tperm_status_t st = device_cu_count(&num_cu);
         if (st != TPERM_OK) return st;
@@ -58,8 +91,7 @@ tperm_status_t resolve_grid(tperm_plan_s* handle, PlanSlot* h, int* grid) {
         }
         if (h->p->blocks_per_cu > 0 && per_cu > h->p->blocks_per_cu) per_cu = h->p->blocks_per_cu;
         mb = per_cu * num_cu;
-        handle->num_cu.store(num_cu, std::memory_order_release);
-        h->max_blocks.store(mb, std::memory_order_release);
+        h->geometry.store((((uint64_t)dev + 1u) << 32) | (uint64_t)mb, std::memory_order_release);
     }
     int64_t g = h->p->tile.num_tiles;
     if (g > mb) g = mb;
@@ -151,6 +183,15 @@ tperm_status_t tperm_plan_create(tperm_plan_t* plan, int rank, const int64_t* di
     return tperm_plan_create_ex(plan, rank, dims, perm, elem_size, nullptr);
 }
 
+tperm_status_t tperm_plan_create_forced(tperm_plan_t* plan, int rank, const int64_t* dims,
+                                        const int* perm, size_t elem_size, int kernel_class) {
+    tperm_plan_opts_t o;
+    std::memset(&o, 0, sizeof(o));
+    o.lds_pad = -1;
+    o.kernel_class = kernel_class;
+    return tperm_plan_create_ex(plan, rank, dims, perm, elem_size, &o);
+}
+
 tperm_status_t tperm_plan_destroy(tperm_plan_t plan) {
     if (plan == nullptr) return TPERM_ERR_NULL;
     delete plan;
@@ -185,12 +226,9 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
     hipError_t err = hipSuccess;
     switch (p.kclass) {
         case TPERM_KERNEL_COPY: {
-            int num_cu = plan->num_cu.load(std::memory_order_acquire);
-            if (num_cu == 0) {
-                tperm_status_t st = device_cu_count(&num_cu);
-                if (st != TPERM_OK) return st;
-                plan->num_cu.store(num_cu, std::memory_order_release);
-            }
+            int num_cu = 0;
+            tperm_status_t st = cached_cu_count(plan, &num_cu);
+            if (st != TPERM_OK) return st;
             err = accumulate ? tperm::launch_accumulate_copy(in, out, nbytes, p.elem, num_cu, stream)
                              : tperm::launch_copy(in, out, nbytes, p.elem, num_cu, stream);
             break;
@@ -201,8 +239,9 @@ static tperm_status_t execute_impl(tperm_plan_t plan, const void* in, void* out,
         case TPERM_KERNEL_ROWCOPY:
         case TPERM_KERNEL_TILED:
         case TPERM_KERNEL_PACKED: {
+            if (!tperm::tile_kernel_exists(p, accumulate)) return TPERM_ERR_KERNEL;
             int grid = 0;
-            tperm_status_t st = resolve_grid(plan, slot, &grid);
+            tperm_status_t st = resolve_grid(slot, &grid);
             if (st != TPERM_OK) return st;
             err = tperm::launch_tile(p, in, out, stream, grid, accumulate);
             break;
@@ -257,7 +296,7 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
         info->lds_pad = p.lds_pad;
         info->score = p.cand.score;
         info->blocks_per_cu = p.blocks_per_cu;
-        info->cache_policy = p.cache_policy;
+        info->cache_policy = tperm::tile_launch_policy(p, false, true);
         info->align_out = p.align_out ? 1 : 0;
         info->loads_first = p.loads_first ? 1 : 0;
         info->vec2 = p.vec2 ? 1 : 0;
@@ -361,21 +400,31 @@ static tperm_status_t measure_best(int rank, const int64_t* dims, const int* per
         tperm_plan_t h = nullptr;
         if (wrap(p, &h) != TPERM_OK) continue;
         float ms = 0.f;
-        bool ok = tperm_execute(h, in, out, hip_stream) == TPERM_OK;  // warm-up
-        if (half == 0) {
-            ok = ok && hipEventRecord(e0, stream) == hipSuccess;
-            for (int rep = 0; ok && rep < 3; ++rep) ok = tperm_execute(h, in, out, hip_stream) == TPERM_OK;
+        // warm-up; its status tells whether this candidate can run at all
+        tperm_status_t est = tperm_execute(h, in, out, hip_stream);
+        if (est == TPERM_ERR_KERNEL) {  // no kernel variant for this candidate: not a failure
+            tperm_plan_destroy(h);
+            continue;
+        }
+        bool ok = est == TPERM_OK;
+        auto run = [&]() {
+            est = tperm_execute(h, in, out, hip_stream);
+            return est == TPERM_OK;
+        };
+        if (ok && half == 0) {
+            ok = hipEventRecord(e0, stream) == hipSuccess;
+            for (int rep = 0; ok && rep < 3; ++rep) ok = run();
             ok = ok && hipEventRecord(e1, stream) == hipSuccess;
             ok = ok && hipEventSynchronize(e1) == hipSuccess;
             ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-        } else {
+        } else if (ok) {
             ms = 1e30f;  // the fastest of five: single short launches are noisy
             for (int rep = 0; ok && rep < 5; ++rep) {
                 float one = 0.f;
                 ok = tperm::launch_copy(scratch.p, static_cast<char*>(scratch.p) + half, half, 4, num_cu,
                                         stream) == hipSuccess;
                 ok = ok && hipEventRecord(e0, stream) == hipSuccess;
-                ok = ok && tperm_execute(h, in, out, hip_stream) == TPERM_OK;
+                ok = ok && run();
                 ok = ok && hipEventRecord(e1, stream) == hipSuccess;
                 ok = ok && hipEventSynchronize(e1) == hipSuccess;
                 ok = ok && hipEventElapsedTime(&one, e0, e1) == hipSuccess;
@@ -385,7 +434,8 @@ static tperm_status_t measure_best(int rank, const int64_t* dims, const int* per
         if (!ok) {
             (void)hipGetLastError();
             tperm_plan_destroy(h);
-            result = TPERM_ERR_HIP;
+            // the status tperm_execute gave (aliasing, alignment, ...) if that is what failed
+            result = est != TPERM_OK ? est : TPERM_ERR_HIP;
             break;
         }
         if (best == nullptr || ms < best_ms) {
@@ -432,23 +482,27 @@ tperm_status_t tperm_plan_create_measured_cold(tperm_plan_t* plan, int rank, con
     }
     const tperm_status_t vst = tperm::validate(rank, dims, perm, elem_size);
     if (vst != TPERM_OK) return vst;
+    size_t nbytes = elem_size;
+    for (int z = 0; z < rank; ++z) nbytes *= (size_t)dims[z];
+    {
+        // the two tensors must not overlap (the same rule as tperm_execute)
+        const uintptr_t i0 = reinterpret_cast<uintptr_t>(in), o0 = reinterpret_cast<uintptr_t>(out);
+        if (i0 < o0 + nbytes && o0 < i0 + nbytes) return TPERM_ERR_ALIAS;
+    }
     if (sweep.p != nullptr) {
         // the scratch must not touch the tensors it is meant to push out of the caches
-        size_t nbytes = elem_size;
-        for (int z = 0; z < rank; ++z) nbytes *= (size_t)dims[z];
         const uintptr_t s0 = reinterpret_cast<uintptr_t>(scratch), s1 = s0 + scratch_bytes;
         for (const void* t : {in, (const void*)out}) {
             const uintptr_t t0 = reinterpret_cast<uintptr_t>(t), t1 = t0 + nbytes;
             if (s0 < t1 && t0 < s1) return TPERM_ERR_ALIAS;
         }
     }
-    tperm_status_t st = tperm::validate(rank, dims, perm, elem_size);
-    if (st != TPERM_OK) return st;
+    tperm_status_t st = TPERM_OK;
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if ((a % elem_size) != 0 || (b % elem_size) != 0) return TPERM_ERR_ALIGN;
     tperm::Canonical c;
     tperm::canonicalise(rank, dims, perm, &c);
     if (c.rank < 2) return tperm_plan_create(plan, rank, dims, perm, elem_size);
-    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
-    if ((a % elem_size) != 0 || (b % elem_size) != 0) return TPERM_ERR_ALIGN;
     auto trimmed = [&](std::vector<tperm::Candidate> v) {
         if (max_candidates > 0 && (int)v.size() > max_candidates) v.resize(max_candidates);
         return v;

@@ -80,20 +80,35 @@ accumulate_kernel(const F* __restrict__ in, F* __restrict__ out, uint64_t n) {
 // dispatch
 // ---------------------------------------------------------------------------------------
 
-// sector_aligned_out: the output base pointer is a multiple of 32 bytes.  The planner's
-// choice of nontemporal stores assumes it; from any other base the written pieces end
-// inside sectors and the cached policy is the right one.
+// Cache policy (1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores, 4 =
+// nontemporal loads) of the kernel variant that runs the plan.  It is the plan's policy unless:
+// the run accumulates (cached only); the output base pointer is not a multiple of 32 bytes
+// (sector_aligned_out false: the planner's choice of nontemporal stores assumes whole sectors,
+// from any other base the written pieces end inside sectors and cached stores are the right
+// ones; line-aligned windows follow the pointer's phase by themselves); or the variant is not
+// instantiated (nontemporal loads alone exist for stores-first 256-thread kernels; 64-thread
+// kernels have cached and fully nontemporal forms).
+int tile_launch_policy(const Plan& plan, bool acc, bool sector_aligned_out) {
+    int pol = acc ? 1 : plan.cache_policy;
+    if (!sector_aligned_out && !plan.align_out) pol = (pol == 2 || pol == 4) ? 4 : 1;
+    if (pol == 4 && (plan.loads_first || plan.threads != 256)) pol = 1;
+    if (pol == 3 && plan.threads != 256) pol = 2;
+    return pol;
+}
+
 static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_aligned_out) {
-    // plan policy 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores
-    int nt = acc ? 0 : (plan.cache_policy == 2 ? 2 : (plan.cache_policy == 3 ? 1 : (plan.cache_policy == 4 ? 3 : 0)));
-    if (!sector_aligned_out && !plan.align_out) nt = (nt == 2 || nt == 3) ? 3 : 0;  // aligned windows follow the pointer's phase
-    if (nt == 3 && (plan.loads_first || plan.threads != 256)) nt = 0;
+    const int pol = tile_launch_policy(plan, acc, sector_aligned_out);
+    const int nt = pol == 2 ? 2 : (pol == 3 ? 1 : (pol == 4 ? 3 : 0));  // template parameter NT
     const bool align = plan.align_out;
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)
                                   : tile_kernel_u64_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2);
     return plan.threads == 64 ? tile_kernel_u32_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)
                               : tile_kernel_u32_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2);
+}
+
+bool tile_kernel_exists(const Plan& plan, bool acc) {
+    return tile_kernel_for(plan, acc, true) != nullptr && tile_kernel_for(plan, acc, false) != nullptr;
 }
 
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks) {

@@ -9,6 +9,12 @@ namespace tperm {
 // Workgroups of this plan's tile kernel that fit one compute unit (occupancy query).
 hipError_t tile_blocks_per_cu(const Plan& plan, int* blocks);
 
+// Cache policy of the kernel variant that launch_tile picks for the plan (see kernels.hip).
+int tile_launch_policy(const Plan& plan, bool acc, bool sector_aligned_out);
+
+// Whether a tile kernel is instantiated for the plan's combination of options.
+bool tile_kernel_exists(const Plan& plan, bool acc);
+
 // Enqueue the tile kernel (ROWCOPY / TILED / PACKED classes) with `grid` workgroups.
 // accumulate: out = out + transposed in (elements are IEEE floats of the element size).
 hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t stream, int grid,

@@ -5,7 +5,7 @@
 
 #include <vector>
 
-#include "../../include/tperm.h"
+#include "../../include/tperm_tuning.h"
 #include "tperm_desc.h"
 
 namespace tperm {

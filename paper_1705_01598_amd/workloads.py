@@ -86,6 +86,17 @@ def stamp_values(case: Case) -> np.ndarray:
     return np.arange(case.volume, dtype=np.int64 if case.elem_size == 8 else np.int32)
 
 
+def scrambled_stamp_values(n: int, elem_size: int) -> np.ndarray:
+    """n distinct unsigned words of elem_size bytes: element i holds i times an odd constant,
+    modulo the word size.  Multiplication by an odd number is a bijection of the words, so the
+    values are pairwise different (any two elements that trade places show up in a bit-for-bit
+    comparison) and every byte of a word, the high half included, varies from element to
+    element."""
+    if elem_size == 8:
+        return np.arange(n, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+    return np.arange(n, dtype=np.uint32) * np.uint32(0x9E3779B1)
+
+
 def bitpattern_values(case: Case) -> np.ndarray:
     """Random raw bit patterns (NaN payloads, -0.0, denormals included) as unsigned ints."""
     rng = np.random.default_rng(case.seed ^ 0x5A5A5A5A)
@@ -257,6 +268,25 @@ def set2(n_random: int = 500) -> List[Case]:
 def square_sweep() -> List[Case]:
     """Figure 8 shapes: fp32 square matrices with side 13952..13968."""
     return [make_case(7, s - 13952, (s, s), (1, 0), 4, f"side{s}") for s in range(13952, 13969)]
+
+
+def heldout(per_cell: int = 2) -> List[Case]:
+    """Shapes that no constant of the plan selector was fitted on: ranks 2..12, volumes of
+    about 2^25 and 2^27 elements, both element sizes, `per_cell` cases each, extents drawn as in
+    the rank sweep but from seeds of their own.  Used to compare the selector's picks with
+    measurement-selected plans on shapes it has never seen."""
+    cases = []
+    index = 0
+    for r in range(2, 13):
+        for log2_vol in (25, 27):
+            for elem in (8, 4):
+                for _ in range(per_cell):
+                    rng = np.random.default_rng(case_seed(8, index) ^ 0x8E1D0)
+                    dims = _random_dims(rng, r, 1.0, log2_vol / r + 1.0, log2_vol=log2_vol)
+                    perm = (1, 0) if r == 2 else _random_non_identity_perm(rng, r)
+                    cases.append(make_case(8, index, dims, perm, elem, f"r{r}v{log2_vol}e{elem}"))
+                    index += 1
+    return cases
 
 
 def contraction_cases(n_cases: int = 24, target_volume: int = 1 << 24) -> list:

@@ -1,10 +1,16 @@
 """Tensor contraction through transposes + GEMM (application layer on top of the library).
 
+The checker is the oracle's direct loop nest (oracle.contract: one output element at a time,
+products summed in double precision in a fixed order; pinned in test_oracle_pins.py on a
+hand-computed case, the matrix product, nested Python loops and the transpose oracle).
 CPU part: the label bookkeeping is checked by emulating the four steps with the oracle's
-transposes and numpy's matrix product against numpy.einsum.  GPU part: the real path (tperm
-transposes, vendor GEMM through torch.mm, accumulating transpose) against the same einsum in
-float64; a GEMM sums in a different order than einsum, so this comparison has a tolerance, unlike
-every transpose test: |difference| <= 8 * K * eps * sum_k |l||r| per output element."""
+transposes and numpy's matrix product.  GPU part: the real path (tperm transposes, vendor GEMM
+through torch.mm, accumulating transpose) against the oracle; a GEMM sums in another order
+than the loop nest, so this comparison has a tolerance, unlike every transpose test: with K
+products per output element, each rounded in the working precision (unit roundoff eps), the
+error of either summation order is at most about K * eps * sum_k |l||r| (the standard bound
+for recursive summation), so |difference| <= 2 * 8 * K * eps * sum_k |l||r| + 8 * eps * |ref|
+per output element (factor 8: slack for fused multiply-adds and blocked partial sums)."""
 import math
 
 import numpy as np
@@ -23,16 +29,13 @@ SMALL = [
 ]
 
 
-def _einsum_ref(lay, l, r, d):
-    """numpy.einsum on Fortran-ordered views: first label = stride-1 dimension."""
-    L = l.reshape(lay.dims(lay.l_labels), order="F")
-    R = r.reshape(lay.dims(lay.r_labels), order="F")
-    out = np.einsum(f"{lay.l_labels},{lay.r_labels}->{lay.d_labels}", L, R)
-    return d + out.ravel(order="F")
+def _oracle_ref(lay, l, r, d):
+    """d + l * r by the oracle's loop nest (first label = stride-1 dimension)."""
+    return oracle.contract(lay.d_labels, lay.l_labels, lay.r_labels, dict(lay.extents), l, r, d)
 
 
 @pytest.mark.parametrize("d,l,r,ext", SMALL)
-def test_layout_bookkeeping_reproduces_einsum(d, l, r, ext):
+def test_layout_bookkeeping_reproduces_the_oracle(d, l, r, ext):
     lay = C.layout(d, l, r, ext)
     rng = np.random.default_rng(3)
     lv = rng.standard_normal(math.prod(lay.dims(l)))
@@ -42,7 +45,7 @@ def test_layout_bookkeeping_reproduces_einsum(d, l, r, ext):
     rp = oracle.transpose(rv, lay.dims(r), lay.r_perm)                 # (summed, free_r): k x n
     t = (lp.reshape((lay.m, lay.k), order="F") @ rp.reshape((lay.k, lay.n), order="F")).ravel(order="F")
     got = oracle.transpose_accumulate(t, dv, lay.dims(lay.free_l + lay.free_r), lay.t_perm)
-    assert np.allclose(got, _einsum_ref(lay, lv, rv, dv), rtol=1e-12, atol=1e-12)
+    assert np.allclose(got, _oracle_ref(lay, lv, rv, dv), rtol=1e-12, atol=1e-12)
     assert lay.flops == 2 * lay.m * lay.n * lay.k
 
 
@@ -69,7 +72,7 @@ def test_arithmetic_intensity_formula():
     ("ebfa", "cadb", "fdce", dict(a=30, b=14, c=12, d=9, e=20, f=16)),
     ("dabfec", "aghcbi", "efdghi", dict(a=4, b=6, c=5, d=3, e=4, f=3, g=7, h=2, i=5)),
 ])
-def test_gpu_contraction_matches_einsum(d, l, r, ext, dtype_name):
+def test_gpu_contraction_matches_the_oracle(d, l, r, ext, dtype_name):
     torch = pytest.importorskip("torch")
     dtype = getattr(torch, dtype_name)
     lay = C.layout(d, l, r, ext)
@@ -84,8 +87,8 @@ def test_gpu_contraction_matches_einsum(d, l, r, ext, dtype_name):
     con.run(torch.from_numpy(lv).cuda(), torch.from_numpy(rv).cuda(), d_dev)      # accumulates twice
     torch.cuda.synchronize()
     l64, r64 = lv.astype(np.float64), rv.astype(np.float64)
-    ref = _einsum_ref(lay, l64, r64, _einsum_ref(lay, l64, r64, dv.astype(np.float64)))
-    bound = _einsum_ref(lay, np.abs(l64), np.abs(r64), np.zeros_like(ref))         # sum_k |l||r|
+    ref = _oracle_ref(lay, l64, r64, _oracle_ref(lay, l64, r64, dv.astype(np.float64)))
+    bound = _oracle_ref(lay, np.abs(l64), np.abs(r64), np.zeros_like(ref))         # sum_k |l||r|
     eps = np.finfo(npdt).eps
     err = np.abs(d_dev.cpu().numpy().astype(np.float64) - ref)
     assert np.all(err <= 2 * 8 * lay.k * eps * bound + 8 * eps * np.abs(ref) + 1e-300), float(err.max())

@@ -1,11 +1,17 @@
 """GPU parity at the full benchmark sizes, with the plans the benchmark times.
 
-Where the CPU oracle finishes a whole tensor in about a second the comparison is element by
-element; for the 330-case rank sweep the output is checked on seeded sampled positions that
-the oracle computes one by one, plus properties that hold at any size: every element is
-written (a sentinel pre-fill is gone), nothing is written outside the tensor (guard bands),
-and the result is a permutation of the input (index-stamp input: the sum of the output
-equals the sum of 0..vol-1; on a subset, the sorted output is exactly 0..vol-1).
+Every case of every workload family is compared with the CPU oracle element by element, bit
+for bit, over the whole tensor: the 2048^2 matrix, all 23 permutations of the 96^4 tensor, the
+20 rank-6 cases, the 330 cases of the rank sweep, the 80 contraction-feeding cases, the printed
+rank-8 / rank-12 shapes of Section 3.2 and the square matrices of Figure 8.
+
+Input values are distinct scrambled index stamps (element i holds i times an odd 64- or 32-bit
+constant): no two elements are equal, so elements that trade places cannot hide, and the high
+half of every word carries information, so a mix-up inside 8- or 16-byte accesses cannot
+either.  A subset is repeated with the values the workloads are defined with (uniform in
+[-1, 1) from the case's seed) and with raw random bit patterns.  The output buffer is
+pre-filled with a sentinel and fenced by guard bands: an element never written, or anything
+written outside the tensor, fails the comparison too.
 """
 import numpy as np
 import pytest
@@ -18,141 +24,135 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 from gpu_util import GUARD, np_uint, to_device  # noqa: E402
 
-N_SAMPLES = 4096
+SENT = -1  # all bits set
 
 
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
+class _Arena:
+    """Scrambled-stamp input on host and device, plus a guarded output buffer, per element
+    size; grown to the largest volume asked for and reused by every case (a case of volume v
+    takes the first v stamps)."""
+
+    def __init__(self):
+        self.host = {}
+        self.dev = {}
+        self.out = {}
+
+    def get(self, volume, elem):
+        if elem not in self.host or self.host[elem].size < volume:
+            self.dev.pop(elem, None)
+            self.out.pop(elem, None)
+            torch.cuda.empty_cache()
+            h = wl.scrambled_stamp_values(volume, elem)
+            assert not bool((h == np_uint(np.array([SENT], dtype=np.int64 if elem == 8 else np.int32))[0]).any())
+            self.host[elem] = h
+            self.dev[elem] = to_device(h)
+            self.out[elem] = torch.empty(volume + 2 * GUARD, dtype=self.dev[elem].dtype, device="cuda")
+        return self.host[elem][:volume], self.dev[elem][:volume], self.out[elem][:volume + 2 * GUARD]
+
+
+_arena = _Arena()
+
+
+def _assert_equal_to_oracle(out, ref_bits, case, plan):
+    """out: guarded device buffer; ref_bits: expected tensor as unsigned host words."""
+    vol = case.volume
+    desc = f"{case.name} dims={case.dims} perm={case.perm} plan={B.info_dict(plan.describe())}"
+    ref_dev = to_device(ref_bits)
+    body = out[GUARD:GUARD + vol]
+    if not torch.equal(body, ref_dev):
+        bad = torch.nonzero(body != ref_dev).flatten()
+        first = [int(x) for x in bad[:4].cpu()]
+        raise AssertionError(f"{desc}: {bad.numel()} of {vol} elements differ from the oracle, first at {first}")
+    assert bool((out[:GUARD] == SENT).all()) and bool((out[GUARD + vol:] == SENT).all()), \
+        "written outside the tensor: " + desc
+
+
+def _full_stamp_compare(case, plan=None):
+    """Whole-tensor, bit-for-bit comparison of one case on scrambled-stamp input."""
+    a, a_dev, out = _arena.get(case.volume, case.elem_size)
+    plan = plan or B.tperm_plan_create(case.dims, case.perm, case.elem_size)
+    out.fill_(SENT)
+    B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr() + GUARD * case.elem_size, _stream())
+    torch.cuda.synchronize()
+    _assert_equal_to_oracle(out, oracle.transpose(a, case.dims, case.perm), case, plan)
+
+
 def _full_compare(case, values="uniform"):
+    """The same on the workload's own values (uniform in [-1, 1)) or raw random bits."""
     a = wl.uniform_values(case) if values == "uniform" else wl.bitpattern_values(case)
     a_dev = to_device(a)
-    out = torch.full((case.volume + 2 * GUARD,), -1, dtype=a_dev.dtype, device="cuda")
+    out = torch.full((case.volume + 2 * GUARD,), SENT, dtype=a_dev.dtype, device="cuda")
     plan = B.tperm_plan_create(case.dims, case.perm, case.elem_size)
     B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr() + GUARD * case.elem_size, _stream())
     torch.cuda.synchronize()
-    got = np_uint(out[GUARD:GUARD + case.volume].cpu().numpy())
-    ref = np_uint(oracle.transpose(np_uint(a), case.dims, case.perm))
-    assert bool((out[:GUARD] == -1).all()) and bool((out[GUARD + case.volume:] == -1).all()), case.name
-    bad = np.nonzero(got != ref)[0]
-    assert bad.size == 0, f"{case.name}: {bad.size} wrong elements, first {bad[:4]}, plan {B.info_dict(plan.describe())}"
+    _assert_equal_to_oracle(out, np_uint(oracle.transpose(np_uint(a), case.dims, case.perm)), case, plan)
 
 
-def _stamp_check(case, stamp, out, sort_check=False):
-    """Index-stamp input already on the device in `stamp`; `out` is a guarded scratch."""
-    vol = case.volume
-    out.fill_(-1)
-    plan = B.tperm_plan_create(case.dims, case.perm, case.elem_size)
-    B.tperm_execute(plan, stamp.data_ptr(), out.data_ptr() + GUARD * case.elem_size, _stream())
-    torch.cuda.synchronize()
-    body = out[GUARD:GUARD + vol]
-    desc = f"{case.name} dims={case.dims} perm={case.perm} plan={B.info_dict(plan.describe())}"
-    assert bool((out[:GUARD] == -1).all()) and bool((out[GUARD + vol:GUARD + vol + GUARD] == -1).all()), desc
-    assert bool((body >= 0).all()), "unwritten elements: " + desc
-    assert int(body.sum(dtype=torch.int64)) == vol * (vol - 1) // 2, "not a permutation: " + desc
-    pos = wl.sample_positions(case, N_SAMPLES)
-    got = body[torch.from_numpy(pos).cuda()].cpu().numpy().astype(np.int64)
-    # the stamp at output position o is the input position the oracle assigns to o
-    expect = oracle.sample(np.arange(vol, dtype=np.int64), case.dims, case.perm, pos) \
-        if vol <= (1 << 24) else np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
-    assert np.array_equal(got, expect), "sampled positions differ: " + desc
-    if sort_check:
-        srt = torch.sort(body).values
-        assert bool((srt == torch.arange(vol, dtype=body.dtype, device="cuda")).all()), desc
-
+# --- config 1: 2048 x 2048 fp64 ------------------------------------------------------------
 
 def test_config1_full():
     _full_compare(wl.config1()[0])
+    _full_stamp_compare(wl.config1()[0])
+
+
+# --- config 2: 96^4 fp64, all 23 non-identity permutations -----------------------------------
+
+@pytest.mark.parametrize("idx", range(23))
+def test_config2_every_permutation_full(idx):
+    _full_stamp_compare(wl.config2()[idx])
 
 
 @pytest.mark.parametrize("idx", [0, 1, 8, 15, 22])
-def test_config2_full_compare(idx):
+def test_config2_uniform_values_full(idx):
     _full_compare(wl.config2()[idx])
 
 
-def test_config2_all_permutations_sampled():
-    cases = wl.config2()
-    vol = cases[0].volume
-    stamp = torch.arange(vol, dtype=torch.int64, device="cuda")
-    out = torch.empty(vol + 2 * GUARD, dtype=torch.int64, device="cuda")
-    for i, case in enumerate(cases):
-        _stamp_check(case, stamp, out, sort_check=(i % 8 == 0))
+# --- config 3: rank 6 fp64, 20 cases --------------------------------------------------------
+
+@pytest.mark.parametrize("idx", range(20))
+def test_config3_every_case_full(idx):
+    _full_stamp_compare(wl.config3()[idx])
 
 
 @pytest.mark.parametrize("idx", [1, 16])
-def test_config3_full_compare(idx):
+def test_config3_random_bits_full(idx):
     _full_compare(wl.config3()[idx], values="bits")
 
 
-def test_config3_all_cases_sampled():
-    cases = wl.config3()
-    big = max(c.volume for c in cases)
-    stamp = torch.arange(big, dtype=torch.int64, device="cuda")
-    out = torch.empty(big + 2 * GUARD, dtype=torch.int64, device="cuda")
-    for case in cases:
-        _stamp_check(case, stamp[:case.volume], out[:case.volume + 2 * GUARD])
-
+# --- config 4: rank sweep 2..12, 30 cases per rank ------------------------------------------
 
 @pytest.mark.parametrize("rank", list(range(2, 13)))
-def test_config4_rank_sweep_sampled(rank):
-    cases = wl.config4(ranks=(rank,))
-    big = max(c.volume for c in cases)
-    stamp = torch.arange(big, dtype=torch.int64, device="cuda")
-    out = torch.empty(big + 2 * GUARD, dtype=torch.int64, device="cuda")
-    for i, case in enumerate(cases):
-        _stamp_check(case, stamp[:case.volume], out[:case.volume + 2 * GUARD], sort_check=(i == 7))
+def test_config4_rank_sweep_every_case_full(rank):
+    for case in wl.config4(ranks=(rank,)):
+        _full_stamp_compare(case)
 
 
 @pytest.mark.parametrize("idx", [40, 171, 300, 329])
-def test_config4_full_compare(idx):
+def test_config4_uniform_values_full(idx):
     _full_compare(wl.config4()[idx])
 
 
+# --- config 5: fp32 contraction-feeding transposes, 80 cases --------------------------------
+
 def test_config5_all_cases_full_compare():
     for case in wl.config5():
+        _full_stamp_compare(case)
         _full_compare(case, values="uniform" if case.index % 2 else "bits")
 
+
+# --- plans chosen by measurement, accumulation, concurrency ---------------------------------
 
 def test_measured_plans_on_config2_subset():
     """Measurement-based selection (Section 2.3) returns a plan that is still exact."""
     for case in wl.config2()[::11]:
-        a = wl.stamp_values(case)
-        a_dev = torch.from_numpy(a).cuda()
-        out = torch.full((case.volume,), -1, dtype=torch.int64, device="cuda")
-        plan = B.tperm_plan_create_measured(case.dims, case.perm, 8, a_dev.data_ptr(), out.data_ptr(),
-                                            _stream(), 16)
-        out.fill_(-1)
-        B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr(), _stream())
-        torch.cuda.synchronize()
-        pos = wl.sample_positions(case, N_SAMPLES)
-        got = out[torch.from_numpy(pos).cuda()].cpu().numpy()
-        expect = np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
-        assert np.array_equal(got, expect) and int(out.sum()) == case.volume * (case.volume - 1) // 2
-
-
-@pytest.mark.parametrize("which", [0, 1])
-def test_paper_set2_shapes_sampled(which):
-    """The rank-8 (205 M elements) and rank-12 (328 M elements, 2.6 GB: byte offsets beyond
-    2^31) shapes printed in Section 3.2, with the trivial, the reverse and seeded random
-    permutations."""
-    cases = [c for c in wl.set2(6) if c.rank == (8, 12)[which]]
-    vol = cases[0].volume
-    stamp = torch.arange(vol, dtype=torch.int64, device="cuda")
-    out = torch.empty(vol + 2 * GUARD, dtype=torch.int64, device="cuda")
-    for case in cases:
-        _stamp_check(case, stamp, out)
-
-
-@pytest.mark.parametrize("side", [13952, 13953, 13966, 13967])
-def test_figure8_squares_sampled(side):
-    """The square 4-byte matrices of the alignment sweep (Section 3.1, Figure 8): whole lines
-    per row, and rows that start anywhere in a line (pairs inside line-aligned windows; odd
-    sides end every input row with a single element)."""
-    case = next(c for c in wl.square_sweep() if c.dims[0] == side)
-    stamp = torch.arange(case.volume, dtype=torch.int32, device="cuda")
-    out = torch.empty(case.volume + 2 * GUARD, dtype=torch.int32, device="cuda")
-    _stamp_check(case, stamp, out, sort_check=(side == 13953))
+        a, a_dev, out = _arena.get(case.volume, 8)
+        plan = B.tperm_plan_create_measured(case.dims, case.perm, 8, a_dev.data_ptr(),
+                                            out.data_ptr() + GUARD * 8, _stream(), 16)
+        _full_stamp_compare(case, plan)
 
 
 def test_accumulate_full_size():
@@ -173,16 +173,32 @@ def test_two_streams_share_one_plan():
     """A plan is immutable: the same plan executed concurrently on two streams."""
     case = wl.config3()[5]
     plan = B.tperm_plan_create(case.dims, case.perm, 8)
-    stamp = torch.arange(case.volume, dtype=torch.int64, device="cuda")
-    outs = [torch.full((case.volume,), -1, dtype=torch.int64, device="cuda") for _ in range(2)]
+    a, a_dev, _ = _arena.get(case.volume, 8)
+    outs = [torch.full((case.volume,), SENT, dtype=torch.int64, device="cuda") for _ in range(2)]
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     torch.cuda.synchronize()
     for rep in range(3):
         for s, o in zip(streams, outs):
-            B.tperm_execute(plan, stamp.data_ptr(), o.data_ptr(), s.cuda_stream)
+            B.tperm_execute(plan, a_dev.data_ptr(), o.data_ptr(), s.cuda_stream)
     torch.cuda.synchronize()
-    assert torch.equal(outs[0], outs[1])
-    pos = wl.sample_positions(case, N_SAMPLES)
-    got = outs[0][torch.from_numpy(pos).cuda()].cpu().numpy()
-    expect = np.array([oracle.input_position(case.dims, case.perm, int(o)) for o in pos])
-    assert np.array_equal(got, expect)
+    ref_dev = to_device(oracle.transpose(a, case.dims, case.perm))
+    assert torch.equal(outs[0], ref_dev) and torch.equal(outs[1], ref_dev)
+
+
+# --- shapes printed in the paper -------------------------------------------------------------
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_paper_set2_shapes_full(which):
+    """The rank-8 (205 M elements) and rank-12 (328 M elements, 2.6 GB: byte offsets beyond
+    2^31) shapes printed in Section 3.2, with the trivial, the reverse and seeded random
+    permutations, every element compared."""
+    for case in [c for c in wl.set2(6) if c.rank == (8, 12)[which]]:
+        _full_stamp_compare(case)
+
+
+@pytest.mark.parametrize("side", [13952, 13953, 13966, 13967])
+def test_figure8_squares_full(side):
+    """The square 4-byte matrices of the alignment sweep (Section 3.1, Figure 8): whole lines
+    per row, and rows that start anywhere in a line (pairs inside line-aligned windows; odd
+    sides end every input row with a single element)."""
+    _full_stamp_compare(next(c for c in wl.square_sweep() if c.dims[0] == side))

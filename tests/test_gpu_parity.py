@@ -73,7 +73,7 @@ def test_auto_plan_matches_oracle(dims, perm, elem):
 def test_forced_class_matches_oracle(dims, perm, kclass, elem):
     case = wl.make_case(0, 2, dims, perm, elem)
     try:
-        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=kclass)
+        plan = B.tperm_plan_create_forced(dims, perm, elem, kclass)
     except B.TpermError as e:
         assert e.status == B.ERR_KERNEL      # class not legal for this problem
         pytest.skip("class cannot run this shape")

@@ -259,3 +259,90 @@ def test_accumulate_form(dtype):
     once = oracle.transpose_accumulate(a, np.zeros(24, dtype=dtype), (2, 3, 4), (2, 0, 1))
     twice = oracle.transpose_accumulate(a, once, (2, 3, 4), (2, 0, 1))
     assert np.array_equal(twice, 2 * once)
+
+
+# -- 14. contraction D + L * R as a direct loop nest (Section 3.4) ----------------------------
+def test_contract_hand_computed_2x2x2():
+    """D[a,b] += sum_k L[a,k] R[k,b] with a, b, k of extent 2, worked by hand.  Flat buffers,
+    first label fastest: L = [L00, L10, L01, L11] = [1, 2, 3, 4], R = [R00, R10, R01, R11] =
+    [5, 6, 7, 8], D starts as [10, 20, 30, 40]."""
+    l = np.array([1.0, 2.0, 3.0, 4.0])
+    r = np.array([5.0, 6.0, 7.0, 8.0])
+    d = np.array([10.0, 20.0, 30.0, 40.0])
+    # D00 = 10 + 1*5 + 3*6 = 33   D10 = 20 + 2*5 + 4*6 = 54
+    # D01 = 30 + 1*7 + 3*8 = 61   D11 = 40 + 2*7 + 4*8 = 86
+    got = oracle.contract("ab", "ak", "kb", dict(a=2, b=2, k=2), l, r, d)
+    assert got.tolist() == [33.0, 54.0, 61.0, 86.0]
+    assert d.tolist() == [10.0, 20.0, 30.0, 40.0]            # the destination passed in is untouched
+    # the result stored transposed ("ba"): D[b,a], b fastest, starting from the same numbers
+    got_t = oracle.contract("ba", "ak", "kb", dict(a=2, b=2, k=2), l, r, np.array([10.0, 30.0, 20.0, 40.0]))
+    assert got_t.tolist() == [33.0, 61.0, 54.0, 86.0]
+    # an operand stored transposed ("ka": k fastest) holding the same matrix
+    got_l = oracle.contract("ab", "ka", "kb", dict(a=2, b=2, k=2), np.array([1.0, 3.0, 2.0, 4.0]), r, d)
+    assert got_l.tolist() == [33.0, 54.0, 61.0, 86.0]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_contract_is_the_matrix_product(dtype):
+    """One free label each and one summed label: the closed form is the matrix product; with
+    small integers every product and sum is exact, so the comparison is bit for bit."""
+    rng = np.random.default_rng(11)
+    for a, b, k in [(3, 5, 4), (1, 7, 2), (6, 1, 5), (4, 4, 1)]:
+        L = rng.integers(-4, 5, size=(a, k)).astype(dtype)
+        R = rng.integers(-4, 5, size=(k, b)).astype(dtype)
+        D = rng.integers(-9, 10, size=(a, b)).astype(dtype)
+        got = oracle.contract("ab", "ak", "kb", dict(a=a, b=b, k=k), L.ravel(order="F"), R.ravel(order="F"),
+                              D.ravel(order="F"))
+        assert got.dtype == dtype and np.array_equal(got, (D + L @ R).ravel(order="F"))
+
+
+def test_contract_matches_nested_python_loops():
+    """Several labels on every side, all tensors in scrambled layouts: pure-Python loops over
+    every combination of label values."""
+    ext = dict(a=2, b=3, c=2, d=3, e=2)
+    d_lab, l_lab, r_lab = "bea", "dacb", "ced"            # summed: d, c; free: a, b from L; e from R
+    rng = np.random.default_rng(12)
+    vol = lambda s: math.prod(ext[c] for c in s)
+    l = rng.integers(-3, 4, size=vol(l_lab)).astype(np.float64)
+    r = rng.integers(-3, 4, size=vol(r_lab)).astype(np.float64)
+    d = rng.integers(-3, 4, size=vol(d_lab)).astype(np.float64)
+
+    def pos(labels, val):
+        p, stride = 0, 1
+        for c in labels:
+            p += val[c] * stride
+            stride *= ext[c]
+        return p
+
+    want = d.copy()
+    names = sorted(ext)
+    for combo in itertools.product(*[range(ext[c]) for c in names]):
+        val = dict(zip(names, combo))
+        want[pos(d_lab, val)] += l[pos(l_lab, val)] * r[pos(r_lab, val)]
+    assert np.array_equal(oracle.contract(d_lab, l_lab, r_lab, ext, l, r, d), want)
+
+
+def test_contract_commutes_with_the_transpose_oracle():
+    """Storing an operand in another layout (the gather transpose of it) and relabelling
+    accordingly leaves the result unchanged; storing the result in another layout transposes
+    it.  Ties the contraction's layout convention to the transpose's."""
+    ext = dict(a=3, b=2, c=4, k=3, j=2)
+    rng = np.random.default_rng(13)
+    vol = lambda s: math.prod(ext[c] for c in s)
+    dims = lambda s: tuple(ext[c] for c in s)
+    l_lab, r_lab, d_lab = "akbj", "jck", "abc"
+    # small integers: every sum is exact whatever the order of the summed labels
+    l = rng.integers(-5, 6, size=vol(l_lab)).astype(np.float64)
+    r = rng.integers(-5, 6, size=vol(r_lab)).astype(np.float64)
+    d = rng.integers(-5, 6, size=vol(d_lab)).astype(np.float64)
+    base = oracle.contract(d_lab, l_lab, r_lab, ext, l, r, d)
+    l2_lab = "jbka"
+    l2 = oracle.transpose(l, dims(l_lab), tuple(l_lab.index(c) for c in l2_lab))
+    assert np.array_equal(oracle.contract(d_lab, l2_lab, r_lab, ext, l2, r, d), base)
+    d2_lab = "cab"
+    perm = tuple(d_lab.index(c) for c in d2_lab)
+    d2 = oracle.transpose(d, dims(d_lab), perm)
+    assert np.array_equal(oracle.contract(d2_lab, l_lab, r_lab, ext, l, r, d2), oracle.transpose(base, dims(d_lab), perm))
+    for bad in [("ab", "ak", "kk"), ("ab", "ak", "jb"), ("abk", "ak", "kb"), ("ab", "akc", "kb")]:
+        with pytest.raises(ValueError):
+            oracle.contract(*bad, dict(a=2, b=2, c=2, j=2, k=2), np.zeros(8), np.zeros(8), np.zeros(8))

@@ -18,13 +18,47 @@ from paper_1705_01598_amd import workloads as wl
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "tperm.h")).read()
-    declared = set(re.findall(r"\b(tperm_[a-z_]+)\s*\(", header))
-    assert declared == set(B.EXPORTS)
+@pytest.mark.parametrize("header,exports", [("tperm.h", "EXPORTS"), ("tperm_tuning.h", "TUNING_EXPORTS")])
+def test_library_exports_every_declared_symbol(header, exports):
+    """Both headers: every function they declare is bound and exported, and nothing else."""
+    text = open(os.path.join(ROOT, "include", header)).read()
+    declared = set(re.findall(r"\b(tperm_[a-z_]+)\s*\(", text))
+    assert declared == set(getattr(B, exports))
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), name
+
+
+def test_product_header_is_the_small_boundary():
+    """The product header holds the plan / execute / describe / destroy calls, the measured
+    and cached forms and the copy; overrides and self-check hooks live in the tuning header."""
+    text = open(os.path.join(ROOT, "include", "tperm.h")).read()
+    assert "tperm_plan_opts_t" not in text and "tperm_plan_index_map" not in text
+    for name in ("tperm_plan_create", "tperm_plan_create_forced", "tperm_execute", "tperm_execute_accumulate",
+                 "tperm_plan_describe", "tperm_plan_destroy", "tperm_status_string"):
+        assert re.search(r"\b" + name + r"\s*\(", text), name
+
+
+def test_forced_create_is_the_options_path_with_a_class():
+    for kc in (B.KERNEL_AUTO, B.KERNEL_TILED, B.KERNEL_PACKED, B.KERNEL_NAIVE):
+        a = B.info_dict(B.tperm_plan_create_forced((40, 9, 33), (2, 0, 1), 8, kc).describe())
+        b = B.info_dict(B.tperm_plan_create_ex((40, 9, 33), (2, 0, 1), 8, kernel_class=kc).describe())
+        assert a == b
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_forced((8, 9, 10), (2, 1, 0), 8, B.KERNEL_ROWCOPY)
+    assert e.value.status == B.ERR_KERNEL
+
+
+def test_describe_reports_the_policy_that_is_launched():
+    """Variants that are not instantiated fall back to another cache policy; describe() names
+    the one that runs."""
+    d = lambda **kw: B.tperm_plan_create_ex((64, 40, 64), (2, 1, 0), 8, **kw).describe()
+    assert d(cache_policy=4, loads_first=1).cache_policy == 4
+    assert d(cache_policy=4, loads_first=2).cache_policy == 1      # nontemporal loads alone: stores-first kernels only
+    assert d(cache_policy=3, threads=64).cache_policy == 2          # 64-thread kernels: cached or fully nontemporal
+    assert d(cache_policy=4, threads=64).cache_policy == 1
+    for pol in (1, 2, 3):
+        assert d(cache_policy=pol).cache_policy == pol
 
 
 def test_status_strings():
