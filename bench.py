@@ -13,8 +13,10 @@ harness, and reported under `per_config` (aggregate, per-case median / minimum, 
 rank and the ratio between the best and the worst rank median, event-timed fraction of the
 HBM peak), and one case of every family is compared with the CPU oracle over the whole
 tensor after the timed region (`bit_exact`).  `roofline` prices the tile kernel (the kernel
-every staged transpose runs through) against the 8 TB/s HBM peak using its per-launch
-durations taken with HIP events inside the timed region; `cpu_baseline` is the CPU oracle
+every staged transpose runs through) against the 8 TB/s HBM peak: algorithmic bytes per launch
+over its average launch duration, which is the time between two HIP events that bracket the
+timed region divided by the number of launches (per-case figures come from a second pass with
+an event between every two launches, outside the timed region); `cpu_baseline` is the CPU oracle
 timed on this machine's host cores on a bounded sample of the headline workload, with all the
 threads it uses and with one.
 """
@@ -189,26 +191,48 @@ class Harness:
         if events is not None:
             events[len(self.plans)].record()
 
-    def timed(self, steps, warmup, with_events=True):
-        """K steps between two synchronisations; returns (seconds, per-launch ms [steps x cases])."""
-        torch, np = self.torch, self.np
+    def timed(self, steps, warmup):
+        """K steps between two synchronisations, with one HIP event in front of the first launch
+        and one behind the last (on the stream the kernels run on).  Returns (wall seconds,
+        event milliseconds over the K steps)."""
+        torch = self.torch
         for w in range(warmup):
             self.one_step(w)
         torch.cuda.synchronize()
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(self.plans) + 1)]
-              for _ in range(steps)] if with_events else None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        e0.record()
         for s in range(steps):
-            self.one_step(s, ev[s] if ev else None)
+            self.one_step(s)
+        e1.record()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
-        dur = None
-        if ev:
-            # per-launch durations from the events recorded inside the timed region
-            dur = np.array([[ev[s][i].elapsed_time(ev[s][i + 1]) for i in range(len(self.plans))]
-                            for s in range(steps)])
-        return elapsed, dur
+        return elapsed, e0.elapsed_time(e1)
+
+    def per_case_ms(self, reps):
+        """Per-case launch durations [reps x cases], in a pass of its own outside the timed
+        region: every case is launched `batch` times back to back (rotating through its places
+        in the buffers) between two events, and the batch time is divided by `batch`.  An event
+        between every two launches would cost about 3 us per launch, which launches of 15-30 us
+        feel; batches keep that below 1 %."""
+        torch, np = self.torch, self.np
+        pa, pb = self.a.data_ptr(), self.b.data_ptr()
+        out = np.zeros((reps, len(self.plans)))
+        for r in range(reps):
+            evs = []
+            for i, plan in enumerate(self.plans):
+                batch = 4 if self.place[i] >= (256 << 20) else 16
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for k in range(batch):
+                    off = ((r * batch + k) % self.places[i]) * self.place[i]
+                    self.run(plan, pa + off, pb + off, self.stream)
+                e1.record()
+                evs.append((e0, e1, batch))
+            torch.cuda.synchronize()
+            out[r] = [e0.elapsed_time(e1) / batch for e0, e1, batch in evs]
+        return out
 
     def copy_ceiling(self):
         """Plain-copy rate of this machine at the family's first size (the paper normalises by a
@@ -251,7 +275,8 @@ class Harness:
     def summary(self, steps, warmup):
         """Time the family and condense the result."""
         np, B = self.np, self.B
-        elapsed, dur_ms = self.timed(steps, warmup)
+        elapsed, region_ms = self.timed(steps, warmup)
+        dur_ms = self.per_case_ms(3)
         cases, infos = self.cases, self.infos
         case_ms = np.median(dur_ms, axis=0)
         case_bytes = np.array([c.bytes_moved // 2 * self.mem_ops for c in cases], dtype=np.float64)
@@ -261,7 +286,14 @@ class Harness:
         tile_mask = np.array([i.kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
                               for i in infos])
         achieved, avg_us = 0.0, None
-        if tile_mask.any():
+        if tile_mask.all():
+            # every launch of the timed region is the tile kernel: its average duration is the
+            # event time over the region divided by the number of launches
+            avg_ms = region_ms / (steps * len(cases))
+            achieved = float(case_bytes.mean() / avg_ms / 1e6)
+            avg_us = round(avg_ms * 1e3, 2)
+        elif tile_mask.any():
+            # mixed with plain copies: take the tile kernel's share from the per-launch events
             achieved = float(case_bytes[tile_mask].mean() / dur_ms[:, tile_mask].mean() / 1e6)
             avg_us = round(float(dur_ms[:, tile_mask].mean()) * 1e3, 2)
         by_rank = {}
@@ -389,7 +421,7 @@ def main():
         if h.n_pairs > 1 and h.scratch is None:
             h.scratch = torch.empty(512 << 20, dtype=torch.uint8, device="cuda:0")
         h.plans[:] = [h.measured_plan(c, 64) for c in cases]
-        elapsed, _ = h.timed(args.steps, args.warmup, with_events=False)
+        elapsed, _ = h.timed(args.steps, args.warmup)
         result["measured_plans_value"] = round(s["bytes_per_step"] * args.steps / elapsed / 1e9, 1)
     if args.also_graph:
         # the same step as a HIP graph: what a caller with a fixed sequence of transposes gets
