@@ -180,6 +180,31 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void *in, void *out, void 
 tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void *in, void *out,
                                         void *hip_stream);
 
+/* Self-checking execute.  Section 2 defines the transpose as a one-to-one map of scalar
+ * positions (Eq. (1)): every input element lands at exactly one output position and nothing
+ * else is written, so the output holds the same multiset of element words as the input.  This
+ * call performs tperm_execute and then checks that invariant on the device: three
+ * order-independent 64-bit digests of the element words (sum, exclusive-or, sum of a scrambled
+ * image) are formed for both tensors and compared.  It catches lost, duplicated or altered
+ * elements; it cannot see elements that merely sit at wrong positions.
+ *
+ * verdict: DEVICE pointer, 8-byte aligned, to one 64-bit word owned by the caller; it is
+ * written by the last kernel of the call: 0 = the digests agree, otherwise a bit mask of the
+ * digests that differ.  Nothing is synchronised: read it after the stream has caught up.
+ * workspace: caller-owned DEVICE memory, 8-byte aligned, of workspace_bytes >=
+ * TPERM_VERIFY_WORKSPACE_BYTES(volume) bytes, holding the partial digests; it needs no
+ * initialisation, its contents are overwritten, and it must not overlap in, out or verdict.
+ * Two calls that use the same workspace at the same time race.  The call costs one more read
+ * of both tensors.  Statuses: those of tperm_execute, TPERM_ERR_NULL (verdict, workspace),
+ * TPERM_ERR_ALIGN (verdict or workspace not 8-byte aligned), TPERM_ERR_TOO_LARGE (workspace
+ * too small for this plan's tensor; nothing is launched). */
+#define TPERM_VERIFY_CHUNK_ELEMS 16384
+#define TPERM_VERIFY_WORKSPACE_BYTES(volume) \
+    ((size_t)64 * (size_t)(((volume) + TPERM_VERIFY_CHUNK_ELEMS - 1) / TPERM_VERIFY_CHUNK_ELEMS))
+tperm_status_t tperm_execute_verified(tperm_plan_t plan, const void *in, void *out,
+                                      void *hip_stream, uint64_t *verdict, void *workspace,
+                                      size_t workspace_bytes);
+
 /* What the selector decided for this plan (Section 2.3: kernel class, tile, launch shape),
  * written to *info, which the caller owns.  Host only.  NULL plan or info: TPERM_ERR_NULL. */
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);

@@ -84,6 +84,13 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const i
  * per 4-byte element. */
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
 
+/* The checking step of tperm_execute_verified on its own, for tests: compares the multisets of
+ * the `count` words of elem_size (4 or 8) bytes at a and at b (DEVICE pointers aligned to the
+ * word size; they may be equal).  verdict, workspace and workspace_bytes as for
+ * tperm_execute_verified, with `count` in place of the volume.  Asynchronous on hip_stream. */
+tperm_status_t tperm_multiset_compare(const void *a, const void *b, int64_t count, size_t elem_size,
+                                      uint64_t *verdict, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream);
 
 #ifdef __cplusplus
 }

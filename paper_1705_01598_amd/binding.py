@@ -28,12 +28,12 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
 # include/tperm.h
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_forced", "tperm_plan_create_measured",
            "tperm_plan_create_measured_cold",
-           "tperm_execute", "tperm_execute_accumulate", "tperm_plan_describe", "tperm_plan_destroy",
+           "tperm_execute", "tperm_execute_accumulate", "tperm_execute_verified", "tperm_plan_describe", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes", "tperm_transpose", "tperm_transpose_accumulate",
            "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
 # include/tperm_tuning.h
 TUNING_EXPORTS = ["tperm_plan_create_ex", "tperm_plan_candidate_count", "tperm_plan_create_candidate",
-                  "tperm_plan_index_map"]
+                  "tperm_plan_index_map", "tperm_multiset_compare"]
 
 
 class PlanOpts(ctypes.Structure):
@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
                                                   ctypes.c_size_t, ctypes.c_int]
         L.tperm_execute.argtypes = [vp, vp, vp, vp]
         L.tperm_execute_accumulate.argtypes = [vp, vp, vp, vp]
+        L.tperm_execute_verified.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_size_t]
+        L.tperm_multiset_compare.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_size_t, vp, vp, ctypes.c_size_t, vp]
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
         L.tperm_plan_destroy.argtypes = [vp]
@@ -253,6 +255,32 @@ def tperm_execute_accumulate(plan: Plan, in_ptr: int, out_ptr: int, stream: int 
                                         ctypes.c_void_p(stream))
     if st != OK:
         raise TpermError(st, "tperm_execute_accumulate")
+
+
+VERIFY_CHUNK_ELEMS = 16384
+
+
+def verify_workspace_bytes(volume: int) -> int:
+    """TPERM_VERIFY_WORKSPACE_BYTES of the header."""
+    return 64 * ((int(volume) + VERIFY_CHUNK_ELEMS - 1) // VERIFY_CHUNK_ELEMS)
+
+
+def tperm_execute_verified(plan: Plan, in_ptr: int, out_ptr: int, stream: int, verdict_ptr: int,
+                           workspace_ptr: int, workspace_bytes: int) -> None:
+    st = lib().tperm_execute_verified(plan.handle, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                      ctypes.c_void_p(stream), ctypes.c_void_p(verdict_ptr),
+                                      ctypes.c_void_p(workspace_ptr), int(workspace_bytes))
+    if st != OK:
+        raise TpermError(st, "tperm_execute_verified")
+
+
+def tperm_multiset_compare(a_ptr: int, b_ptr: int, count: int, elem_size: int, verdict_ptr: int,
+                           workspace_ptr: int, workspace_bytes: int, stream: int = 0) -> None:
+    st = lib().tperm_multiset_compare(ctypes.c_void_p(a_ptr), ctypes.c_void_p(b_ptr), int(count), int(elem_size),
+                                      ctypes.c_void_p(verdict_ptr), ctypes.c_void_p(workspace_ptr),
+                                      int(workspace_bytes), ctypes.c_void_p(stream))
+    if st != OK:
+        raise TpermError(st, "tperm_multiset_compare")
 
 
 def tperm_plan_describe(plan: Plan) -> PlanInfo:

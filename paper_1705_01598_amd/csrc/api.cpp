@@ -10,6 +10,7 @@
 #include "../../include/tperm_tuning.h"
 #include "kernels.hpp"
 #include "plan.hpp"
+#include "verify.hpp"
 
 using tperm::Plan;
 
@@ -263,6 +264,59 @@ tperm_status_t tperm_execute(tperm_plan_t plan, const void* in, void* out, void*
 tperm_status_t tperm_execute_accumulate(tperm_plan_t plan, const void* in, void* out,
                                         void* hip_stream) {
     return execute_impl(plan, in, out, hip_stream, true);
+}
+
+// Argument rules shared by the checking entry points: the verdict word and the scratch are
+// device pointers aligned to 8 bytes, and the scratch is large enough and apart from the data.
+static tperm_status_t check_verify_args(const void* a, const void* b, size_t nbytes, const uint64_t* verdict,
+                                        const void* scratch, size_t scratch_bytes, size_t needed) {
+    if (verdict == nullptr || scratch == nullptr) return TPERM_ERR_NULL;
+    if (((reinterpret_cast<uintptr_t>(verdict) | reinterpret_cast<uintptr_t>(scratch)) & 7u) != 0) return TPERM_ERR_ALIGN;
+    if (scratch_bytes < needed) return TPERM_ERR_TOO_LARGE;
+    const uintptr_t s0 = reinterpret_cast<uintptr_t>(scratch), s1 = s0 + needed;
+    const uintptr_t v0 = reinterpret_cast<uintptr_t>(verdict), v1 = v0 + 8;
+    if (s0 < v1 && v0 < s1) return TPERM_ERR_ALIAS;
+    for (const void* t : {a, b}) {
+        const uintptr_t t0 = reinterpret_cast<uintptr_t>(t), t1 = t0 + nbytes;
+        if ((s0 < t1 && t0 < s1) || (v0 < t1 && t0 < v1)) return TPERM_ERR_ALIAS;
+    }
+    return TPERM_OK;
+}
+
+tperm_status_t tperm_execute_verified(tperm_plan_t plan, const void* in, void* out, void* hip_stream,
+                                      uint64_t* verdict, void* workspace, size_t workspace_bytes) {
+    if (plan == nullptr || in == nullptr || out == nullptr) return TPERM_ERR_NULL;
+    const Plan& p = *plan->base.p;
+    const uint64_t vol = (uint64_t)p.c.volume;
+    tperm_status_t st = check_verify_args(in, out, (size_t)vol * (size_t)p.elem, verdict, workspace, workspace_bytes,
+                                          tperm::verify_scratch_bytes(vol));
+    if (st != TPERM_OK) return st;
+    st = execute_impl(plan, in, out, hip_stream, false);
+    if (st != TPERM_OK) return st;
+    if (tperm::launch_multiset_compare(in, out, vol, p.elem, workspace, verdict, (hipStream_t)hip_stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    return TPERM_OK;
+}
+
+tperm_status_t tperm_multiset_compare(const void* a, const void* b, int64_t count, size_t elem_size,
+                                      uint64_t* verdict, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+    if (a == nullptr || b == nullptr) return TPERM_ERR_NULL;
+    if (elem_size != 4 && elem_size != 8) return TPERM_ERR_ELEM_SIZE;
+    if (count < 1) return TPERM_ERR_DIMS;
+    if (count >= ((int64_t)1 << 31) || (uint64_t)count * elem_size >= ((uint64_t)1 << 32) - 256) return TPERM_ERR_TOO_LARGE;
+    if (((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) % elem_size) != 0) return TPERM_ERR_ALIGN;
+    tperm_status_t st = check_verify_args(a, b, (size_t)count * elem_size, verdict, workspace, workspace_bytes,
+                                          tperm::verify_scratch_bytes((uint64_t)count));
+    if (st != TPERM_OK) return st;
+    if (tperm::launch_multiset_compare(a, b, (uint64_t)count, (int)elem_size, workspace, verdict,
+                                       (hipStream_t)hip_stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    return TPERM_OK;
 }
 
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {

@@ -97,6 +97,20 @@ def test_null_arguments():
     assert L.tperm_plan_destroy(None) == B.ERR_NULL
     assert L.tperm_plan_describe(None, None) == B.ERR_NULL
     assert L.tperm_execute(None, None, None, None) == B.ERR_NULL
+    assert L.tperm_execute_verified(None, None, None, None, None, None, 0) == B.ERR_NULL
+    assert L.tperm_multiset_compare(None, None, 4, 8, None, None, 0, None) == B.ERR_NULL
+    # the checking calls validate everything on the host before anything is launched
+    plan = B.tperm_plan_create((4, 5), (1, 0), 8)
+    fake = ctypes.c_void_p(0x1000)
+    assert L.tperm_execute_verified(plan.handle, fake, ctypes.c_void_p(0x2000), None, None, fake, 64) == B.ERR_NULL
+    assert L.tperm_execute_verified(plan.handle, fake, ctypes.c_void_p(0x2000), None, ctypes.c_void_p(0x3004),
+                                    ctypes.c_void_p(0x4000), 64) == B.ERR_ALIGN
+    assert L.tperm_execute_verified(plan.handle, fake, ctypes.c_void_p(0x2000), None, ctypes.c_void_p(0x3000),
+                                    ctypes.c_void_p(0x4000), 8) == B.ERR_TOO_LARGE
+    assert L.tperm_multiset_compare(fake, fake, 4, 2, fake, fake, 64, None) == B.ERR_ELEM_SIZE
+    assert L.tperm_multiset_compare(fake, fake, 0, 8, fake, fake, 64, None) == B.ERR_DIMS
+    assert B.verify_workspace_bytes(1) == 64 and B.verify_workspace_bytes(16384) == 64
+    assert B.verify_workspace_bytes(16385) == 128
 
 
 def test_execute_without_device_reports_hip_error():
