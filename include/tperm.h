@@ -205,6 +205,27 @@ tperm_status_t tperm_execute_verified(tperm_plan_t plan, const void *in, void *o
                                       void *hip_stream, uint64_t *verdict, void *workspace,
                                       size_t workspace_bytes);
 
+/* tperm_execute_verified for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The partial digests go to a 512 KiB array that the library holds in the device
+ * memory of every GPU it runs on, from the time its code is loaded there until the process
+ * ends; the call allocates and frees nothing, on the host or on the device, and enqueues
+ * kernels only (no memset, no copy).  Same arguments, result and statuses as
+ * tperm_execute_verified, except:
+ *   - the array is sized for tensors of up to 2^27 elements (TPERM_VERIFY_STATIC_MAX_ELEMS); a
+ *     plan with a larger volume gives TPERM_ERR_TOO_LARGE and nothing is launched (use the
+ *     workspace form for those);
+ *   - all calls on one GPU share that GPU's array, whatever the stream or the plan: two calls
+ *     that are in flight on one GPU at the same time race on it and may report a wrong verdict
+ *     (the transposed tensor itself is unaffected).  Order them on one stream, or use the
+ *     workspace form.  The array keeps the last call's partial results; nothing in it needs
+ *     clearing, since a call reads only what it has written itself;
+ *   - the first call on a GPU looks up the array's device address (the only set-up there is);
+ *     make that call outside stream capture. */
+#define TPERM_VERIFY_STATIC_MAX_ELEMS ((int64_t)1 << 27)
+tperm_status_t tperm_execute_verified_static(tperm_plan_t plan, const void *in, void *out,
+                                             void *hip_stream, uint64_t *verdict);
+
 /* What the selector decided for this plan (Section 2.3: kernel class, tile, launch shape),
  * written to *info, which the caller owns.  Host only.  NULL plan or info: TPERM_ERR_NULL. */
 tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t *info);

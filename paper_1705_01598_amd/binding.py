@@ -28,7 +28,8 @@ KERNEL_NAMES = {KERNEL_AUTO: "auto", KERNEL_COPY: "copy", KERNEL_ROWCOPY: "rowco
 # include/tperm.h
 EXPORTS = ["tperm_plan_create", "tperm_plan_create_forced", "tperm_plan_create_measured",
            "tperm_plan_create_measured_cold",
-           "tperm_execute", "tperm_execute_accumulate", "tperm_execute_verified", "tperm_plan_describe", "tperm_plan_destroy",
+           "tperm_execute", "tperm_execute_accumulate", "tperm_execute_verified", "tperm_execute_verified_static",
+           "tperm_plan_describe", "tperm_plan_destroy",
            "tperm_status_string", "tperm_copy_bytes", "tperm_transpose", "tperm_transpose_accumulate",
            "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
 # include/tperm_tuning.h
@@ -98,6 +99,7 @@ def lib() -> ctypes.CDLL:
         L.tperm_execute.argtypes = [vp, vp, vp, vp]
         L.tperm_execute_accumulate.argtypes = [vp, vp, vp, vp]
         L.tperm_execute_verified.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_size_t]
+        L.tperm_execute_verified_static.argtypes = [vp, vp, vp, vp, vp]
         L.tperm_multiset_compare.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_size_t, vp, vp, ctypes.c_size_t, vp]
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
@@ -272,6 +274,16 @@ def tperm_execute_verified(plan: Plan, in_ptr: int, out_ptr: int, stream: int, v
                                       ctypes.c_void_p(workspace_ptr), int(workspace_bytes))
     if st != OK:
         raise TpermError(st, "tperm_execute_verified")
+
+
+VERIFY_STATIC_MAX_ELEMS = 1 << 27
+
+
+def tperm_execute_verified_static(plan: Plan, in_ptr: int, out_ptr: int, stream: int, verdict_ptr: int) -> None:
+    st = lib().tperm_execute_verified_static(plan.handle, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                             ctypes.c_void_p(stream), ctypes.c_void_p(verdict_ptr))
+    if st != OK:
+        raise TpermError(st, "tperm_execute_verified_static")
 
 
 def tperm_multiset_compare(a_ptr: int, b_ptr: int, count: int, elem_size: int, verdict_ptr: int,

@@ -300,6 +300,19 @@ tperm_status_t tperm_execute_verified(tperm_plan_t plan, const void* in, void* o
     return TPERM_OK;
 }
 
+tperm_status_t tperm_execute_verified_static(tperm_plan_t plan, const void* in, void* out,
+                                             void* hip_stream, uint64_t* verdict) {
+    if (plan == nullptr || in == nullptr || out == nullptr || verdict == nullptr) return TPERM_ERR_NULL;
+    // the library's own scratch holds the partial results of tensors up to this size only
+    if ((uint64_t)plan->base.p->c.volume > tperm::kVerifyStaticMaxElems) return TPERM_ERR_TOO_LARGE;
+    void* scratch = nullptr;
+    if (tperm::verify_static_scratch(&scratch) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    return tperm_execute_verified(plan, in, out, hip_stream, verdict, scratch, tperm::kVerifyStaticBytes);
+}
+
 tperm_status_t tperm_multiset_compare(const void* a, const void* b, int64_t count, size_t elem_size,
                                       uint64_t* verdict, void* workspace, size_t workspace_bytes,
                                       void* hip_stream) {

@@ -16,6 +16,13 @@
 
 #include "verify.hpp"
 
+// Scratch of the entry point that allocates nothing: one copy of this array lives on every GPU
+// the library runs on, from the moment its code is loaded there until the process ends.  Host
+// code never passes the array's name to a kernel (on the host that name is only a handle for
+// the symbol): verify_static_scratch() asks the runtime for the array's device address, once per
+// device, and every kernel argument is built from that address.
+static __device__ __align__(256) unsigned char scratch[tperm::kVerifyStaticBytes];
+
 namespace tperm {
 
 struct MultisetPartial {
@@ -101,6 +108,27 @@ multiset_verdict_kernel(const MultisetPartial* __restrict__ pa, const MultisetPa
     if (threadIdx.x == 0)
         *verdict = (tot[0][0] != tot[1][0] ? 1u : 0u) | (tot[0][1] != tot[1][1] ? 2u : 0u) |
                    (tot[0][2] != tot[1][2] ? 4u : 0u);
+}
+
+hipError_t verify_static_scratch(void** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void* address[kMaxDevices] = {};  // per device ordinal; nullptr = not asked yet
+    *ptr = nullptr;
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (address[dev] == nullptr) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // the current device's copy
+        if (err != hipSuccess) return err;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    return hipSuccess;
 }
 
 size_t verify_scratch_bytes(uint64_t n_elems) {

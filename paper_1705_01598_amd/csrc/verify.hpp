@@ -9,6 +9,15 @@ namespace tperm {
 constexpr uint64_t kVerifyChunk = 16384;       // elements digested by one workgroup
 constexpr size_t kVerifyPartialBytes = 32;     // one partial result
 
+// The entry point that allocates nothing keeps its partial results in a file-scope device
+// array sized for tensors of up to kVerifyStaticMaxElems elements (512 KiB per GPU).
+constexpr uint64_t kVerifyStaticMaxElems = (uint64_t)1 << 27;
+constexpr size_t kVerifyStaticBytes = 2 * (size_t)(kVerifyStaticMaxElems / kVerifyChunk) * kVerifyPartialBytes;
+
+// Device address of that array on the current device (resolved on the first call per device,
+// then remembered).  The memory keeps whatever the last call left in it.
+hipError_t verify_static_scratch(void** ptr);
+
 // Scratch bytes the check of two tensors of n_elems elements needs: one partial result per
 // chunk and tensor.
 size_t verify_scratch_bytes(uint64_t n_elems);
