@@ -72,6 +72,9 @@ def parse_args():
     ap.add_argument("--set2-perms", type=int, default=30, help="random permutations per shape for --config 6")
     ap.add_argument("--stride", type=int, default=1, help="take every n-th case of the family")
     ap.add_argument("--plan", choices=["heuristic", "measured"], default="heuristic")
+    ap.add_argument("--selector", choices=["fitted", "model"], default="fitted",
+                    help="--plan heuristic: which host-side selector picks the tile: the fitted cost estimate "
+                         "(default) or the analytical model of Section 2.3 re-derived for MI355X")
     ap.add_argument("--max-candidates", type=int, default=48,
                     help="--plan measured: time this many of the best-scored candidates per case")
     ap.add_argument("--also-measured", action="store_true",
@@ -81,6 +84,11 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-verify", action="store_true", help="skip the whole-tensor oracle comparison")
     ap.add_argument("--cases-out", default="", help="write per-case results (JSON lines) here")
+    ap.add_argument("--profile-pass", action="store_true",
+                    help="for runs under rocprofv3: launch every case of the family once, in order, in two "
+                         "passes (the second is the one to read), then the library's plain copy of the first "
+                         "case's size three times (the known-size launch that counter readings are scaled "
+                         "by), write the cases' plans to --cases-out and stop; no timing, no JSON line")
     return ap.parse_args()
 
 
@@ -166,8 +174,12 @@ class Harness:
         # 512 MiB scratch swept between executions, as the data will arrive from HBM in the timed loop
         self.scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev) \
             if (self.n_pairs > 1 and (args.plan == "measured" or args.also_measured)) else None
-        self.plans = [self.measured_plan(c, args.max_candidates) if args.plan == "measured"
-                      else B.tperm_plan_create(c.dims, c.perm, c.elem_size) for c in cases]
+        def heuristic(c):
+            if args.selector == "model":
+                return B.tperm_plan_create_ex(c.dims, c.perm, c.elem_size, selector=1)
+            return B.tperm_plan_create(c.dims, c.perm, c.elem_size)
+        self.plans = [self.measured_plan(c, args.max_candidates) if args.plan == "measured" else heuristic(c)
+                      for c in cases]
         self.infos = [p.describe() for p in self.plans]
 
     def measured_plan(self, c, max_candidates):
@@ -361,6 +373,20 @@ def main():
     config = args.config or HEADLINE
     cases = family(args, config)
     h = Harness(args, config, cases)
+    if args.profile_pass:
+        for p in range(2):
+            h.one_step(p)
+            torch.cuda.synchronize()
+        nbytes = cases[0].volume * cases[0].elem_size
+        for _ in range(3):
+            B.tperm_copy_bytes(h.a.data_ptr(), h.b.data_ptr(), nbytes, h.stream)
+        torch.cuda.synchronize()
+        if args.cases_out:
+            with open(args.cases_out, "w") as fh:
+                for c, info in zip(cases, h.infos):
+                    fh.write(json.dumps({"case": c.name, "dims": c.dims, "perm": c.perm, "elem": c.elem_size,
+                                         **B.info_dict(info)}) + "\n")
+        return
     s = h.summary(args.steps, args.warmup)
     copy_gbs = h.copy_ceiling()
     traffic, traffic_source = TRAFFIC.get(config, (None, None))
@@ -388,7 +414,7 @@ def main():
         "dtype": s["dtype"],
         "data": "synthetic",
         "config": {"workload": s["workload"], "cases": len(cases),
-                   "bytes_per_step": s["bytes_per_step"], "plan": args.plan, "buffer_pairs": h.n_pairs,
+                   "bytes_per_step": s["bytes_per_step"], "plan": args.plan if args.plan == "measured" or args.selector == "fitted" else "heuristic (analytical model)", "buffer_pairs": h.n_pairs,
                    "mode": "accumulate (3 memory ops per element)" if args.accumulate else "transpose"},
         "pct_hbm_peak": s["pct_hbm_peak"],
         "case_median_GBs": s["case_median_GBs"],

@@ -54,6 +54,9 @@ typedef struct {
                          * addresses and take any element-aligned pointer)                   */
     int pair_elems;     /* moving two 4-byte elements as one 8-byte unit (paired in plan info): *
                          * 0 = default (on when no class or tile is forced), 1 = off, 2 = on   */
+    int selector;       /* how the tile is chosen when none is forced: 0 = the fitted cost      *
+                         * estimate (default); 1 = the analytical model of tperm_plan_model,    *
+                         * evaluated on the best-scored candidates (slower plan creation)       */
 } tperm_plan_opts_t;
 
 /* tperm_plan_create with overrides.  opts may be NULL (then it is tperm_plan_create).  A
@@ -83,6 +86,32 @@ tperm_status_t tperm_plan_create_candidate(tperm_plan_t *plan, int rank, const i
  * (see tperm_plan_info_t.paired) the map evaluated is that of the 8-byte twin, written out
  * per 4-byte element. */
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
+
+/* Analytical run-time estimate of a plan, after Section 2.3 (Eqs. (10)-(13)): the MWP-CWP form
+ * cycles = (cycles_mem + cycles_shmem + cycles_ac) * N_iter, with the memory latency driven by
+ * the transactions per request and stores to partially written lines counted double (Eq. (13)),
+ * re-derived for MI355X: 128-byte lines, 64-lane waves that keep all their requests in flight,
+ * 256 compute units, 8 TB/s.  The transaction counts are exact: up to 8 tiles spread over the
+ * tile index are walked on the host with the kernel's own index arithmetic and every touched
+ * line is tallied.  Host only; plans of the copy and naive classes give TPERM_ERR_KERNEL. */
+typedef struct {
+    double ld_tran, st_tran;       /* distinct 128-byte lines read / written per tile            */
+    double ld_req, st_req;         /* wave-wide load / store instructions per tile               */
+    double cl_full, cl_part;       /* written lines that receive all 128 bytes / fewer           */
+    double ld_runs, st_runs;       /* separate runs of consecutive lines read / written per tile *
+                                    * (reported; Eq. (13) has no term for them)                  */
+    double tpr_mem;                /* transactions per request, Eq. (13)                         */
+    double mem_lat;                /* cycles: base latency + (tpr_mem - 1) * departure delay     */
+    double mlp;                    /* independent requests per wave and tile (slots per thread)  */
+    double mwp;                    /* requests that overlap within one memory latency            */
+    double tpr_lds;                /* LDS passes per wave-wide LDS access (bank conflicts)       */
+    double cycles_mem, cycles_lds, cycles_ac; /* per iteration of a compute unit, Eq. (10), (11) */
+    double n_iter;                 /* iterations: tiles / (compute units * resident workgroups)  */
+    double cycles_total;
+    double microseconds;           /* cycles_total at 2.4 GHz                                    */
+    double useful_bytes_per_tile;  /* bytes a tile writes (= reads), ragged edges included       */
+} tperm_model_t;
+tperm_status_t tperm_plan_model(tperm_plan_t plan, tperm_model_t *model);
 
 /* The checking step of tperm_execute_verified on its own, for tests: compares the multisets of
  * the `count` words of elem_size (4 or 8) bytes at a and at b (DEVICE pointers aligned to the

@@ -34,7 +34,7 @@ EXPORTS = ["tperm_plan_create", "tperm_plan_create_forced", "tperm_plan_create_m
            "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
 # include/tperm_tuning.h
 TUNING_EXPORTS = ["tperm_plan_create_ex", "tperm_plan_candidate_count", "tperm_plan_create_candidate",
-                  "tperm_plan_index_map", "tperm_multiset_compare"]
+                  "tperm_plan_index_map", "tperm_plan_model", "tperm_multiset_compare"]
 
 
 class PlanOpts(ctypes.Structure):
@@ -45,7 +45,15 @@ class PlanOpts(ctypes.Structure):
                 ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
                 ("lds_buffers", ctypes.c_int), ("align_out", ctypes.c_int),
                 ("tile_order", ctypes.c_int), ("loads_first", ctypes.c_int),
-                ("vec2", ctypes.c_int), ("pair_elems", ctypes.c_int)]
+                ("vec2", ctypes.c_int), ("pair_elems", ctypes.c_int), ("selector", ctypes.c_int)]
+
+
+class Model(ctypes.Structure):
+    """tperm_model_t: analytical estimate of a plan (Section 2.3 re-derived for MI355X)."""
+    _fields_ = [(n, ctypes.c_double) for n in
+                ("ld_tran", "st_tran", "ld_req", "st_req", "cl_full", "cl_part", "ld_runs", "st_runs", "tpr_mem", "mem_lat", "mlp",
+                 "mwp", "tpr_lds", "cycles_mem", "cycles_lds", "cycles_ac", "n_iter", "cycles_total",
+                 "microseconds", "useful_bytes_per_tile")]
 
 
 class PlanInfo(ctypes.Structure):
@@ -103,6 +111,7 @@ def lib() -> ctypes.CDLL:
         L.tperm_multiset_compare.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_size_t, vp, vp, ctypes.c_size_t, vp]
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
+        L.tperm_plan_model.argtypes = [vp, ctypes.POINTER(Model)]
         L.tperm_plan_destroy.argtypes = [vp]
         L.tperm_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.tperm_transpose.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, vp, vp, vp]
@@ -183,7 +192,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                          blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
                          window_out: int = 0, threads: int = 0, lds_buffers: int = 0,
                          align_out: int = 0, tile_order: int = 0, pair_elems: int = 0,
-                         loads_first: int = 0, vec2: int = 0) -> Plan:
+                         loads_first: int = 0, vec2: int = 0, selector: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
                     tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
@@ -191,7 +200,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                     window_in=int(window_in), window_out=int(window_out), threads=int(threads),
                     lds_buffers=int(lds_buffers), align_out=int(align_out),
                     tile_order=int(tile_order), pair_elems=int(pair_elems),
-                    loads_first=int(loads_first), vec2=int(vec2))
+                    loads_first=int(loads_first), vec2=int(vec2), selector=int(selector))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:
@@ -313,6 +322,14 @@ def tperm_plan_index_map(plan: Plan):
     if st != OK:
         raise TpermError(st, "tperm_plan_index_map")
     return buf
+
+
+def tperm_plan_model(plan: Plan) -> Model:
+    m = Model()
+    st = lib().tperm_plan_model(plan.handle, ctypes.byref(m))
+    if st != OK:
+        raise TpermError(st, "tperm_plan_model")
+    return m
 
 
 def tperm_transpose(dims: Sequence[int], perm: Sequence[int], elem_size: int, in_ptr: int,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtperm.so")
-SOURCES = ["plan.cpp", "api.cpp", "cache.cpp", "kernels.hip", "verify.hip", "tile_inst_u64_256.hip", "tile_inst_u32_256.hip",
+SOURCES = ["plan.cpp", "model.cpp", "api.cpp", "cache.cpp", "kernels.hip", "verify.hip", "tile_inst_u64_256.hip", "tile_inst_u32_256.hip",
            "tile_inst_u64_64.hip", "tile_inst_u32_64.hip"]
 HEADERS = ["plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
            os.path.join("..", "..", "include", "tperm_tuning.h")]

@@ -373,6 +373,12 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
     return TPERM_OK;
 }
 
+tperm_status_t tperm_plan_model(tperm_plan_t plan, tperm_model_t* model) {
+    if (plan == nullptr || model == nullptr) return TPERM_ERR_NULL;
+    // the plan that runs on suitably aligned pointers, as tperm_plan_describe reports it
+    return tperm::model_plan(plan->wide.p ? *plan->wide.p : *plan->base.p, model);
+}
+
 tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t* out_to_in) {
     if (plan == nullptr || out_to_in == nullptr) return TPERM_ERR_NULL;
     if (plan->wide.p == nullptr) return tperm::index_map(*plan->base.p, out_to_in);

@@ -547,6 +547,11 @@ double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads) {
     return ConflictSampler(d, d, elem, nreg, threads).cost(0);
 }
 
+double lds_conflict_ratio(const TileDesc& d, int elem, int nreg, int threads) {
+    const ConflictSampler s(d, d, elem, nreg, threads);
+    return s.groups.empty() ? 1.0 : s.cost(0) / (double)s.groups.size();
+}
+
 // Fill the LDS strides of both dim lists for a given row padding; returns LDS elements.
 static uint32_t set_lds_strides(TileDesc* d, const int* dim_of_in, const int* dim_of_out,
                                 int run_dims, uint32_t pad) {
@@ -872,7 +877,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         // on small line-aligned tensors (few tiles per workgroup), but -2 to -5 % on large
         // line-aligned ones, which do better with single elements (and loads first).
         const double rounds = (double)d.num_tiles / (256.0 * std::max(2.0, std::min(8.0, std::round(20480.0 / ((double)cand.tile_vol * elem)))));
-        const bool worth_it = elem == 4 || !cand.aligned || rounds < 16.0;
+        const bool worth_it = elem == 4 || !cand.aligned || rounds < 16.0 || opts.vec2 == 2;  // 2: asked for explicitly
         // In line-aligned windows (4-byte elements only) the written pairs are 8-byte aligned
         // whatever the extents, and an odd row length on the read side is allowed as long as
         // dim 0 is chunked: the tile that holds the odd end reads element by element.
@@ -882,7 +887,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
                                   (split_dim[0] == 0 || cand.t[0] == c.dims[0]);
         const bool pair_plain = !align_out && worth_it && nreg2 > 0 && c.dims[0] % 2 == 0 &&
                                 c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 && cand.t[q] % 2 == 0;
-        if (opts.vec2 == 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
+        if (opts.vec2 >= 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
             dim_of_in[0] == 0 && dim_of_out[0] == q) {
             TileDim& a = d.in_order[0];
             a.ext /= 2;
@@ -1001,6 +1006,16 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (want == TPERM_KERNEL_COPY) return fail(TPERM_ERR_KERNEL);
     if (want < 0 || want > TPERM_KERNEL_NAIVE) return fail(TPERM_ERR_KERNEL);
 
+    TileBuildOpts bo;
+    bo.lds_pad = o.lds_pad;
+    bo.grid_mode = o.grid_mode == 0 ? kDefaultGridMode : (o.grid_mode < 0 ? 0 : o.grid_mode);
+    if (o.window_in > 0) bo.window_in = o.window_in;
+    if (o.window_out > 0) bo.window_out = o.window_out;
+    if (o.threads > 0) bo.threads = o.threads;
+    if (o.lds_buffers > 0) bo.lds_buffers = o.lds_buffers;
+    bo.align_out = o.align_out;
+    bo.tile_order = o.tile_order > 0 ? o.tile_order - 1 : kDefaultTileOrder;
+    bo.vec2 = o.vec2 == 2 ? 2 : 0;
     Candidate chosen;
     bool have = false;
     if (o.m > 0 || o.k > 0) {
@@ -1016,24 +1031,33 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
         have = true;
     } else {
         const auto cands = enumerate_candidates(p->c, p->elem);
-        for (const auto& cd : cands) {
-            if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
-            chosen = cd;
-            have = true;
-            break;
+        if (o.selector == 1) {
+            // Section 2.3's way: build the plans (here: of the 24 best-scored candidates) and
+            // keep the one the analytical model expects to finish first
+            double best_us = 0.0;
+            int tried = 0;
+            for (const auto& cd : cands) {
+                if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
+                if (tried++ >= 24) break;
+                Plan tmp = *p;
+                tperm_model_t m;
+                if (build_tile_plan(&tmp, cd, bo) != TPERM_OK || model_plan(tmp, &m) != TPERM_OK) continue;
+                if (!have || m.microseconds < best_us) {
+                    chosen = cd;
+                    best_us = m.microseconds;
+                    have = true;
+                }
+            }
+        } else {
+            for (const auto& cd : cands) {
+                if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
+                chosen = cd;
+                have = true;
+                break;
+            }
         }
     }
     if (!have) return fail(TPERM_ERR_KERNEL);
-    TileBuildOpts bo;
-    bo.lds_pad = o.lds_pad;
-    bo.grid_mode = o.grid_mode == 0 ? kDefaultGridMode : (o.grid_mode < 0 ? 0 : o.grid_mode);
-    if (o.window_in > 0) bo.window_in = o.window_in;
-    if (o.window_out > 0) bo.window_out = o.window_out;
-    if (o.threads > 0) bo.threads = o.threads;
-    if (o.lds_buffers > 0) bo.lds_buffers = o.lds_buffers;
-    bo.align_out = o.align_out;
-    bo.tile_order = o.tile_order > 0 ? o.tile_order - 1 : kDefaultTileOrder;
-    bo.vec2 = o.vec2 == 2 ? 1 : 0;
     st = build_tile_plan(p, chosen, bo);
     if (st != TPERM_OK) return fail(st);
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;

@@ -122,7 +122,7 @@ struct TileBuildOpts {
     int lds_buffers = kDefaultLdsBuffers;
     int align_out = 0;      // line-aligned output windows: 0 = as the candidate says, 1 = off, 2 = on where the tile allows
     int tile_order = kDefaultTileOrder;  // 0: input-major, 1: output-major
-    int vec2 = 0;           // 4-byte elements in pairs: 0 = off, 1 = where possible
+    int vec2 = 0;           // elements in pairs: 0 = off, 1 = where possible and worth it, 2 = wherever possible
 };
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts);
 void build_naive_desc(Plan* plan);
@@ -145,5 +145,12 @@ tperm_status_t index_map(const Plan& plan, int64_t* out_to_in);
 // (bank-conflict count evaluated from the slot positions, as Section 2.3 does for the
 // shared-memory term of its model).
 double lds_conflict_cost(const TileDesc& d, int elem, int nreg, int threads);
+// The same as a ratio: LDS passes per wave-wide access, 1 = conflict-free (the TPR_shmem of
+// Section 2.3).
+double lds_conflict_ratio(const TileDesc& d, int elem, int nreg, int threads);
+
+// Analytical estimate of a tile plan's run time (model.cpp): Eqs. (10)-(13) of Section 2.3 with
+// exact line counts from a sample of tiles and constants for MI355X.
+tperm_status_t model_plan(const Plan& plan, tperm_model_t* out);
 
 }  // namespace tperm

@@ -47,6 +47,7 @@ int main(int argc, char** argv) {
         const size_t elem = ((it / 4) & 1) ? 4 : 8;
         const int mode = long_q0 ? 2 : (int)(rng() % 4);
         if (mode == 1) o.kernel_class = 1 + (int)(rng() % 5);
+        if (mode == 0 && (rng() % 2)) o.selector = 1;  // tile chosen by the analytical model
         if (mode >= 2) {
             o.kernel_class = TPERM_KERNEL_PACKED;
             o.m = 1 + (int)(rng() % rank);
@@ -103,6 +104,16 @@ int main(int argc, char** argv) {
                 return 1;
             }
             seen[(size_t)map[(size_t)i]] = 1;
+        }
+        if (p->kclass == TPERM_KERNEL_ROWCOPY || p->kclass == TPERM_KERNEL_TILED || p->kclass == TPERM_KERNEL_PACKED) {
+            // the analytical model walks sampled tiles with the kernel's arithmetic: its byte
+            // count per tile can never exceed the tile, and the estimate must be finite
+            tperm_model_t m;
+            if (tperm::model_plan(*p, &m) != TPERM_OK || !(m.microseconds > 0.0) || !(m.microseconds < 1e12) ||
+                m.useful_bytes_per_tile > (double)p->cand.tile_vol * (double)elem + 0.5) {
+                std::printf("model failed at iteration %d\n", it);
+                return 1;
+            }
         }
         if (p->align_out) ++windows;
         if (p->align_out && p->vec2) ++pair_windows;

@@ -426,7 +426,8 @@ def test_planner_under_address_and_ub_sanitizers(tmp_path):
         pytest.skip("g++ not available")
     exe = str(tmp_path / "planner_fuzz")
     src = [os.path.join(ROOT, "tests", "planner_fuzz.cpp"),
-           os.path.join(ROOT, "paper_1705_01598_amd", "csrc", "plan.cpp")]
+           os.path.join(ROOT, "paper_1705_01598_amd", "csrc", "plan.cpp"),
+           os.path.join(ROOT, "paper_1705_01598_amd", "csrc", "model.cpp")]
     subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
                     "-fno-sanitize-recover=undefined", "-I" + os.path.join(ROOT, "include"),
                     *src, "-o", exe], check=True)
@@ -514,3 +515,66 @@ def test_plan_cache_is_thread_safe():
     assert not errors
     assert B.tperm_cache_stats()["entries"] <= 38
     B.tperm_cache_clear()
+
+
+# -- analytical model (Section 2.3, Eqs. (10)-(13)) --------------------------------------------
+def _lines_of(byte_ranges):
+    """Distinct 128-byte lines of a list of (begin, nbytes), and how many receive all 128 bytes."""
+    got = {}
+    for b0, nb in byte_ranges:
+        for byte in range(b0, b0 + nb):
+            got[byte // 128] = got.get(byte // 128, 0) + 1
+    return len(got), sum(1 for v in got.values() if v == 128)
+
+
+@pytest.mark.parametrize("d0,d1,t0,t1", [(40, 24, 20, 12), (33, 50, 33, 25), (64, 64, 32, 32), (35, 18, 16, 9)])
+def test_model_line_counts_against_enumeration(d0, d1, t0, t1):
+    """2-D transposes cut into at most 8 tiles: the model walks every tile, so its averages
+    must equal a direct enumeration of the bytes each tile reads and writes."""
+    plan = B.tperm_plan_create_ex((d0, d1), (1, 0), 8, kernel_class=B.KERNEL_PACKED, m=1, tile_in=t0, k=1,
+                                  tile_out=t1, vec2=1, align_out=1)
+    info = plan.describe()
+    assert list(info.tile_extent[:2]) == [t0, t1] and info.num_tiles <= 8
+    m = B.tperm_plan_model(plan)
+    ld = st = full = tiles = 0
+    for a0 in range(0, d0, t0):
+        for a1 in range(0, d1, t1):
+            i0 = range(a0, min(a0 + t0, d0))
+            i1 = range(a1, min(a1 + t1, d1))
+            n, _ = _lines_of([((x + d0 * y) * 8, 8) for x in i0 for y in i1])       # input: dims[0] fastest
+            ld += n
+            n, f = _lines_of([((y + d1 * x) * 8, 8) for x in i0 for y in i1])       # output: input dim 1 fastest
+            st += n
+            full += f
+            tiles += 1
+    assert tiles == info.num_tiles
+    assert m.ld_tran == pytest.approx(ld / tiles) and m.st_tran == pytest.approx(st / tiles)
+    assert m.cl_full == pytest.approx(full / tiles) and m.cl_part == pytest.approx((st - full) / tiles)
+    assert m.useful_bytes_per_tile == pytest.approx(d0 * d1 * 8 / tiles)
+    assert m.ld_req == info.nreg * info.threads / 64 and m.mlp == info.nreg
+    # Eq. (13) from the counted quantities
+    part = m.cl_part / max(1.0, m.cl_full + m.cl_part)
+    assert m.tpr_mem == pytest.approx((m.ld_tran + m.st_tran * (1 + part)) / (m.ld_req + m.st_req))
+    assert 1 <= m.ld_runs <= m.ld_tran and 1 <= m.st_runs <= m.st_tran
+    assert m.cycles_total == pytest.approx((m.cycles_mem + m.cycles_lds + m.cycles_ac) * m.n_iter)   # Eq. (10)
+
+
+def test_model_prices_partial_lines_and_short_runs():
+    us = lambda dims, perm, **kw: B.tperm_plan_model(B.tperm_plan_create_ex(dims, perm, 8, **kw)).microseconds
+    tile = dict(kernel_class=B.KERNEL_PACKED, m=1, k=1, vec2=1, align_out=1)
+    # rows that start anywhere in a line cost more than line-aligned ones of nearly the same size
+    assert us((4097, 4097), (1, 0), tile_in=32, tile_out=32, **tile) > 1.2 * us((4096, 4096), (1, 0), tile_in=32, tile_out=32, **tile)
+    # 4-element output pieces (partial lines everywhere) against 32-element ones
+    assert us((4096, 4096), (1, 0), tile_in=256, tile_out=4, **tile) > 1.5 * us((4096, 4096), (1, 0), tile_in=32, tile_out=32, **tile)
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_model(B.tperm_plan_create((5, 6, 7), (0, 1, 2), 8))           # a plain copy has no tile
+    assert e.value.status == B.ERR_KERNEL
+
+
+def test_model_selector_builds_valid_plans():
+    """Plans chosen by the analytical model (selector = 1) still map every element correctly."""
+    rng = np.random.default_rng(31)
+    for dims, perm, elem in [((70, 45, 33, 6), (2, 0, 3, 1), 8), ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4), 4),
+                             ((129, 7, 65), (2, 1, 0), 8), ((33, 5, 7, 16, 3), (0, 3, 1, 4, 2), 4), ((301, 299), (1, 0), 8)]:
+        plan = _map_ok(dims, perm, elem, selector=1)
+        assert plan.describe().kernel_class in (B.KERNEL_ROWCOPY, B.KERNEL_TILED, B.KERNEL_PACKED)
