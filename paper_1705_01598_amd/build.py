@@ -8,9 +8,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtperm.so")
+PROBE = os.path.join(HERE, "pattern_probe")
 SOURCES = ["plan.cpp", "model.cpp", "api.cpp", "cache.cpp", "kernels.hip", "verify.hip", "tile_inst_u64_256.hip", "tile_inst_u32_256.hip",
            "tile_inst_u64_64.hip", "tile_inst_u32_64.hip"]
-HEADERS = ["plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
+HEADERS = ["pattern_probe.hip", "plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
            os.path.join("..", "..", "include", "tperm_tuning.h")]
 
 # -packed-fp32-ops is switched off for all device code built here (no packed FP32
@@ -54,6 +55,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if p.wait() != 0:
             raise RuntimeError("compile failed: " + " ".join(cmd))
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    # the pattern probe: a stand-alone measurement tool (what a transpose tile's access pattern
+    # can reach on this memory system, whatever kernel issues it)
+    cmd = [hipcc(), *COMMON_FLAGS, *DEVICE_FLAGS, os.path.join(CSRC, "pattern_probe.hip"), "-o", PROBE]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

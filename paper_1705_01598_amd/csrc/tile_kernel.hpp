@@ -41,6 +41,44 @@ __device__ __forceinline__ uint32_t read_lane(uint32_t v, uint32_t lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane);
 }
 
+// Keeps a wave-uniform value in a scalar register from here on: the compiler may not go back
+// to the kernel-argument segment for it (it would otherwise reload such values where they are
+// used, one scalar load and one wait each).
+__device__ __forceinline__ void keep_scalar(uint32_t& v) { asm volatile("" : "+s"(v)); }
+
+__device__ __forceinline__ void keep_tile_dim(TileDim& t) {
+    keep_scalar(t.ext);
+    keep_scalar(t.div.magic);
+    keep_scalar(t.div.shift);
+    keep_scalar(t.gstride);
+    keep_scalar(t.ostride);
+    keep_scalar(t.lstride);
+    keep_scalar(t.sel);
+    keep_scalar(t.xshift);
+}
+
+__device__ __forceinline__ TileWalk pinned_tile_walk(const TileDesc& d) {
+    TileWalk w = tile_walk_of(d);
+    keep_scalar(w.num_tiles);
+    for (int s = 0; s < 2; ++s) {
+        keep_scalar(w.split_ext[s]);
+        keep_scalar(w.split_tile[s]);
+        keep_scalar(w.split_step[s]);
+        keep_scalar(w.split_halo[s]);
+        keep_scalar(w.chunk_pair[s]);
+        keep_scalar(w.pair[s].lane_lo);
+        keep_scalar(w.pair[s].lane_hi);
+        keep_scalar(w.pair[s].width);
+        keep_scalar(w.pair[s].count);
+    }
+    keep_scalar(w.grid_mode);
+    keep_scalar(w.tiles_per_xcd);
+    keep_scalar(w.group_log2);
+    keep_scalar(w.lane_a);
+    keep_scalar(w.lane_b);
+    return w;
+}
+
 struct MajorPos {
     uint32_t in, out;        // element offsets of the tile (wave-uniform)
     uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
@@ -54,7 +92,7 @@ struct MajorLane {
     uint32_t ext, stride_in, stride_out;
 };
 
-__device__ __forceinline__ MajorPos major_position(const TileDesc& d, const MajorLane& ml,
+__device__ __forceinline__ MajorPos major_position(const TileWalk& d, const MajorLane& ml,
                                                    uint32_t b) {
     const uint32_t q = fdiv(b, ml.cum);
     const uint32_t c = q - fdiv(q, ml.ext_div) * ml.ext;
@@ -162,7 +200,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 
 template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2>
 __global__ void __launch_bounds__(THREADS)
-tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uint32_t nbytes) {
+tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_arg, uint32_t nbytes_arg) {
+    const T* in = in_arg;
+    T* out = out_arg;
+    uint32_t nbytes = nbytes_arg;
     // VEC2: a slot is a pair of elements, moved through global memory with one access of
     // twice the element size; the LDS image stays in single elements.
     static_assert(!VEC2 || (USE_LDS && !ACC), "vec2 is an LDS-staged, non-accumulating form");
@@ -181,12 +222,56 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     extern __shared__ __align__(16) unsigned char smem_raw[];
     lds_t* lds = reinterpret_cast<lds_t*>(smem_raw);
     const uint32_t tid = threadIdx.x;
+    // This lane's term of the major sums.  The descriptor sits in the kernel-argument segment and
+    // a per-lane index into it becomes vector loads from there, which take a good half
+    // microsecond to come back: they are issued first, so that they travel while the prologue
+    // below computes.
+    const uint32_t lane16 = tid & 15u;
+    MajorLane ml;
+    ml.cum = d.major.cum[lane16];
+    ml.ext_div = d.major.ext_div[lane16];
+    ml.ext = d.major.ext[lane16];
+    ml.stride_in = d.major.stride_in[lane16];
+    ml.stride_out = d.major.stride_out[lane16];
+
+    // What the tile loop needs of the descriptor, and the constants of the first two tile dims,
+    // fetched now in one batch of scalar loads (one round trip to the kernel-argument segment
+    // instead of one per use) and kept in scalar registers.
+    TileDim first_out[2] = {d.out_order[0], d.out_order[1]};
+    TileDim first_in[2] = {d.in_order[0], d.in_order[1]};
+    const TileWalk walk = pinned_tile_walk(d);
+    for (int i = 0; i < 2; ++i) {
+        keep_tile_dim(first_out[i]);
+        if (USE_LDS) keep_tile_dim(first_in[i]);
+    }
+    asm volatile("" : "+s"(in), "+s"(out), "+s"(nbytes));  // the same batch
+    // the other loop constants of the descriptor, under short names
+    uint32_t n_tile_dims = d.n_tile_dims, tile_vol = d.tile_vol, lds_elems = d.lds_elems;
+    uint32_t lds_buffers = d.lds_buffers, pair_lstride = d.pair_lstride, pair_a_split = d.pair_a_split;
+    keep_scalar(n_tile_dims);
+    keep_scalar(tile_vol);
+    if (USE_LDS) {
+        keep_scalar(lds_elems);
+        keep_scalar(lds_buffers);
+    }
+    if (VEC2) {
+        keep_scalar(pair_lstride);
+        keep_scalar(pair_a_split);
+    }
+    OutAlign oa = d.oa;
+    if (ALIGN) {
+        keep_scalar(oa.line_elems);
+        keep_scalar(oa.total_slots);
+        keep_scalar(oa.lstride_b);
+        keep_scalar(oa.in_halo_elems);
+    }
+
     // ALIGN (line-aligned output windows): tile coordinates along the shifted dimension count
     // from a halo origin one line's worth of elements in front of the chunk, so both buffers
     // are described from that far in front of the tensors; the slots that would fall before
     // a tensor's first element are masked (lo_b).
-    const uint32_t halo_in = ALIGN ? d.oa.in_halo_elems * (uint32_t)sizeof(T) : 0u;
-    const uint32_t halo_out = ALIGN ? d.oa.line_elems * (uint32_t)sizeof(T) : 0u;
+    const uint32_t halo_in = ALIGN ? oa.in_halo_elems * (uint32_t)sizeof(T) : 0u;
+    const uint32_t halo_out = ALIGN ? oa.line_elems * (uint32_t)sizeof(T) : 0u;
     const __amdgpu_buffer_rsrc_t rsrc_in =
         make_rsrc(reinterpret_cast<const char*>(in) - halo_in, nbytes + halo_in);
     const __amdgpu_buffer_rsrc_t rsrc_out =
@@ -206,7 +291,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         constexpr int G = NREG <= 4 ? NREG : (NREG % 4 == 0 ? 4 : 3);
         static_assert(NREG % G == 0, "slot groups must tile the slots");
         // ALIGN: the write side has fewer slots than the read side (no halo)
-        const uint32_t write_slots = ALIGN ? d.oa.total_slots : d.tile_vol;
+        const uint32_t write_slots = ALIGN ? oa.total_slots : tile_vol;
 #pragma unroll
         for (int g0 = 0; g0 < NREG; g0 += G) {
             uint32_t rem_o[G], rem_i[G], loff_o[G], loff_i[G];
@@ -223,8 +308,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             // Entry i of both orders in one pass: the write side (output order; LDS-free
             // kernels read the same slots through ostride) and, with an LDS stage, the read
             // side (input order).
-            for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
-                const TileDim to = d.out_order[i];
+            auto digit_step = [&](const TileDim& to, const TileDim& ti) {
                 const uint32_t shift_o = to.sel == 2u ? 16u + to.xshift : to.xshift;
 #pragma unroll
                 for (int jj = 0; jj < G; ++jj) {
@@ -238,7 +322,6 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                     if (to.sel != 0u) wr_mask[j] |= x << shift_o;
                 }
                 if (USE_LDS) {
-                    const TileDim ti = d.in_order[i];
                     const uint32_t shift_i = ti.sel == 2u ? 16u + ti.xshift : ti.xshift;
 #pragma unroll
                     for (int jj = 0; jj < G; ++jj) {
@@ -251,22 +334,34 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                         if (ti.sel != 0u) rd_mask[j] |= x << shift_i;
                     }
                 }
+            };
+            // The first two entries are taken unconditionally, from the copies fetched at the top of
+            // the kernel; every turn of the loop below costs one more round trip to the descriptor.  (An entry beyond n_tile_dims is all
+            // zero, which is neutral here: quotient 0, no stride, no mask.)
+            digit_step(first_out[0], first_in[0]);
+            digit_step(first_out[1], first_in[1]);
+            for (uint32_t i = 2; i < n_tile_dims; ++i) {
+                // whole entries at once: one round trip per turn, not one per field
+                TileDim to = d.out_order[i], ti = d.in_order[i];
+                keep_tile_dim(to);
+                if (USE_LDS) keep_tile_dim(ti);
+                digit_step(to, ti);
             }
 #pragma unroll
             for (int jj = 0; jj < G; ++jj) {
                 const int j = g0 + jj;
                 const uint32_t k = tid + (uint32_t)j * THREADS;
-                const bool used_r = k < d.tile_vol, used_w = k < write_slots;
+                const bool used_r = k < tile_vol, used_w = k < write_slots;
                 wr_aux[j] = 0;
                 if (ALIGN) {
                     // p = position in the chunk (output stride 1); the slot reads the tile
                     // coordinate p + line_elems - shift and stores that many elements on
                     // from the halo origin, where shift is this row's phase in the tile
                     const uint32_t p = wr_mask[j] >> 16;
-                    const uint32_t rho = (wr_off[j] - p) & (d.oa.line_elems - 1u);
-                    wr_aux[j] = used_w ? ((p + d.oa.line_elems) | (rho << 16)) : 0u;
-                    wr_off[j] += d.oa.line_elems;
-                    loff_o[jj] += d.oa.line_elems * d.oa.lstride_b;
+                    const uint32_t rho = (wr_off[j] - p) & (oa.line_elems - 1u);
+                    wr_aux[j] = used_w ? ((p + oa.line_elems) | (rho << 16)) : 0u;
+                    wr_off[j] += oa.line_elems;
+                    loff_o[jj] += oa.line_elems * oa.lstride_b;
                 }
                 wr_off[j] = used_w ? wr_off[j] * (uint32_t)sizeof(T) : 0u;
                 rd_off[j] = used_r ? rd_off[j] * (uint32_t)sizeof(T) : 0u;
@@ -281,17 +376,9 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         }
     }
 
-    const uint32_t lane16 = tid & 15u;
-    MajorLane ml;
-    ml.cum = d.major.cum[lane16];
-    ml.ext_div = d.major.ext_div[lane16];
-    ml.ext = d.major.ext[lane16];
-    ml.stride_in = d.major.stride_in[lane16];
-    ml.stride_out = d.major.stride_out[lane16];
-
     const uint32_t grid = gridDim.x, block = blockIdx.x;
     uint32_t it = 0;
-    uint32_t b = tile_of(d, block, grid, it);
+    uint32_t b = tile_of(walk, block, grid, it);
     reg_t v[NREG];
     MajorPos pos, nxt;
     pos.in = pos.out = pos.rem_a = pos.rem_b = pos.lo_b = pos.span_b = 0;
@@ -306,7 +393,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
     auto read_ok_second = [&](int j, const MajorPos& t) {
         return read_ok(j, t) && slot_valid_from(rd_mask[j] + 1u, t.rem_a, t.lo_b, t.span_b);
     };
-    auto odd_row_end = [&](const MajorPos& t) { return PAIRWIN && d.pair_a_split != 0u && (t.rem_a & 1u) != 0u; };
+    auto odd_row_end = [&](const MajorPos& t) { return PAIRWIN && pair_a_split != 0u && (t.rem_a & 1u) != 0u; };
     auto load_tile = [&](const MajorPos& t) {
         const uint32_t soff = t.in * (uint32_t)sizeof(T);
         if constexpr (PAIRWIN) {
@@ -323,8 +410,8 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         for (int j = 0; j < NREG; ++j)
             v[j] = io::load(rsrc_in, read_ok(j, t) ? rd_off[j] : kDroppedOffset, soff);
     };
-    if (b < d.num_tiles) {
-        pos = major_position(d, ml, b);
+    if (b < walk.num_tiles) {
+        pos = major_position(walk, ml, b);
         load_tile(pos);
     }
     // As many dropped stores as a tile has real ones: every pass through the loop below then
@@ -337,15 +424,15 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             io::store(nothing, rsrc_out, kDroppedOffset + (LOADS_FIRST ? 0u : 4u * (uint32_t)j), 0u);
     }
     // the position of the tile after this one is worked out while the loads are in flight
-    uint32_t bn = tile_of(d, block, grid, it + 1);
+    uint32_t bn = tile_of(walk, block, grid, it + 1);
     const MajorPos no_tile = nxt;  // all zero: no slot is valid
-    if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
-    const bool two_buffers = d.lds_buffers == 2u;
+    if (bn < walk.num_tiles) nxt = major_position(walk, ml, bn);
+    const bool two_buffers = lds_buffers == 2u;
     // line-aligned windows: phase of the output base pointer within a 128-byte line
-    const uint32_t line_mask = ALIGN ? d.oa.line_elems - 1u : 0u;
+    const uint32_t line_mask = ALIGN ? oa.line_elems - 1u : 0u;
     const uint32_t out_phase =
         ALIGN ? (uint32_t)(reinterpret_cast<uintptr_t>(out) / sizeof(T)) & line_mask : 0u;
-    while (b < d.num_tiles) {
+    while (b < walk.num_tiles) {
         reg_t w[NREG];
         // Write side of this tile: byte offset of every slot, or kDroppedOffset.  ALIGN: the
         // slot's row starts `shift` elements past a line boundary (phase of the tile origin +
@@ -384,7 +471,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             // with two LDS images the tiles alternate between them and one barrier per
             // tile is enough: a wave can only overwrite an image two tiles later, after
             // the barrier of the tile in between
-            lds_t* img = lds + ((two_buffers && (it & 1u)) ? d.lds_elems : 0u);
+            lds_t* img = lds + ((two_buffers && (it & 1u)) ? lds_elems : 0u);
 #pragma unroll
             for (int j = 0; j < NREG; ++j)
                 if (read_ok(j, pos)) {
@@ -406,12 +493,12 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
             if (ALIGN) {
 #pragma unroll
                 for (int j = 0; j < NREG; ++j) {
-                    const uint32_t at = (lds_pos[j] >> 16) - row_shift(j) * d.oa.lstride_b;
+                    const uint32_t at = (lds_pos[j] >> 16) - row_shift(j) * oa.lstride_b;
                     if constexpr (PAIRWIN) {
                         // both elements of the pair lie inside the image whenever the row does
                         if ((wr_mask[j] & 0xFFFFu) < pos.rem_a) {
                             w[j].x = img[at];
-                            w[j].y = img[at + d.oa.lstride_b];
+                            w[j].y = img[at + oa.lstride_b];
                         }
                     } else if constexpr (!VEC2) {
                         if (write_at(j) != kDroppedOffset) w[j] = img[at];
@@ -425,10 +512,10 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
                             // neighbours along output dim 0 are pair_lstride apart
                             if constexpr (sizeof(T) == 4) {
                                 w[j].x = img[lds_pos[j] >> 16];
-                                w[j].y = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                                w[j].y = img[(lds_pos[j] >> 16) + pair_lstride];
                             } else {
                                 const lds_t lo = img[lds_pos[j] >> 16];
-                                const lds_t hi = img[(lds_pos[j] >> 16) + d.pair_lstride];
+                                const lds_t hi = img[(lds_pos[j] >> 16) + pair_lstride];
                                 w[j] = reg_t{lo.x, lo.y, hi.x, hi.y};
                             }
                         } else {
@@ -443,7 +530,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         if (LOADS_FIRST) {
             // under a branch on purpose: a conditional block is what keeps the compiler from
             // sinking these loads below the stores
-            if (bn < d.num_tiles) issue_next_loads();
+            if (bn < walk.num_tiles) issue_next_loads();
         }
         const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
         if (ACC) {
@@ -458,7 +545,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         bool stored = false;
         if constexpr (PAIRWIN) {
             // a window clipped by the ends of its output row: element by element
-            if (pos.lo_b != 0u || pos.rem_b != d.split_tile[1]) {
+            if (pos.lo_b != 0u || pos.rem_b != walk.split_tile[1]) {
 #pragma unroll
                 for (int j = 0; j < NREG; ++j) {
                     const uint32_t sh = row_shift(j);
@@ -479,9 +566,9 @@ tile_kernel(const TileDesc d, const T* __restrict__ in, T* __restrict__ out, uin
         b = bn;
         pos = nxt;
         ++it;
-        bn = tile_of(d, block, grid, it + 1);
+        bn = tile_of(walk, block, grid, it + 1);
         nxt = no_tile;
-        if (bn < d.num_tiles) nxt = major_position(d, ml, bn);
+        if (bn < walk.num_tiles) nxt = major_position(walk, ml, bn);
         if (USE_LDS && !two_buffers) __syncthreads();  // all waves are done reading the image
     }
 }

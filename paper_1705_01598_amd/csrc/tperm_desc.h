@@ -117,6 +117,41 @@ struct TileDesc {
     OutAlign oa;
 };
 
+// The fields of TileDesc that say which tile comes next and what is left of the split dims in
+// it (tile_of, tile_remaining), under the same names.  The kernel copies them out of the
+// kernel-argument segment once, in one batch of scalar loads, and keeps them in scalar
+// registers: read where they are used, each of them is a scalar load of its own with a wait
+// behind it, a dozen round trips in a row before the first tile's loads can leave and again
+// for every tile.
+struct TileWalk {
+    uint32_t num_tiles;
+    uint32_t split_ext[2], split_tile[2], split_step[2], split_halo[2];
+    uint32_t grid_mode, tiles_per_xcd, group_log2;
+    uint32_t lane_a, lane_b;
+    uint32_t chunk_pair[2];
+    SplitPair pair[2];
+};
+
+template <typename D>
+TPERM_HD TileWalk tile_walk_of(const D& d) {
+    TileWalk w;
+    w.num_tiles = d.num_tiles;
+    for (int s = 0; s < 2; ++s) {
+        w.split_ext[s] = d.split_ext[s];
+        w.split_tile[s] = d.split_tile[s];
+        w.split_step[s] = d.split_step[s];
+        w.split_halo[s] = d.split_halo[s];
+        w.chunk_pair[s] = d.chunk_pair[s];
+        w.pair[s] = d.pair[s];
+    }
+    w.grid_mode = d.grid_mode;
+    w.tiles_per_xcd = d.tiles_per_xcd;
+    w.group_log2 = d.group_log2;
+    w.lane_a = d.lane_a;
+    w.lane_b = d.lane_b;
+    return w;
+}
+
 // Per-thread, per-slot minor position for the read side (Eq. (4) and the LDS store slot).
 // k is the position inside the tile in input order.  xa/xb are the coordinates along the
 // split dims, used to mask ragged edge tiles.
@@ -163,8 +198,9 @@ TPERM_HD uint32_t split_remaining(uint32_t full_ext, uint32_t tile_ext, uint32_t
 // tile exist, and what is left of the split dims in it.  A tile that does not exist gets
 // remaining extents of 0, which masks every slot.  lo_b: first valid coordinate of split dim B
 // in this tile (non-zero only in the first chunk of a dim with a halo).
-template <typename CoordFn>
-TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, uint32_t* rem_b,
+// D: the descriptor, or a copy of its tile-walk fields (see TileWalk).
+template <typename D, typename CoordFn>
+TPERM_HD void tile_remaining(const D& d, CoordFn coord, uint32_t* rem_a, uint32_t* rem_b,
                              uint32_t* lo_b) {
     bool exists = true;
     uint32_t counter[2] = {0u, 0u};
@@ -188,7 +224,8 @@ TPERM_HD void tile_remaining(const TileDesc& d, CoordFn coord, uint32_t* rem_a, 
 // grid_mode 2 deals groups of 2^group_log2 consecutive tiles to the XCDs in turn: tiles
 // that share cache lines at their edges meet in one L2, while all XCDs still work on the
 // same neighbourhood of the tensors.  Modes 1 and 2 need grid % 8 == 0.
-TPERM_HD uint32_t tile_of(const TileDesc& d, uint32_t block, uint32_t grid, uint32_t i) {
+template <typename D>
+TPERM_HD uint32_t tile_of(const D& d, uint32_t block, uint32_t grid, uint32_t i) {
     if (d.grid_mode == 1u) {
         const uint32_t xcd = block & 7u, slot = block >> 3, per = grid >> 3;
         const uint32_t local = slot + i * per;
