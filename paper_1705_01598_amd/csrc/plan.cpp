@@ -287,10 +287,22 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     static const double kWeightRc[10] = {1.4, 1.05, 0.95, 0.9, 0.9, 1.0, 1.06, 1.1, 1.16, 1.2};
     // A 4-byte candidate that can move its elements in pairs (see build_tile_plan) has half
     // the slots and behaves like the 8-byte kernel of the same tile bytes.
-    const bool pairs = elem == 4 && cd->use_lds && !cd->align && q0 != 0 && c.dims[0] % 2 == 0 &&
-                       c.dims[q0] % 2 == 0 && cd->t[0] % 2 == 0 && cd->t[q0] % 2 == 0;
+    const bool pairable = cd->use_lds && !cd->align && q0 != 0 && c.dims[0] % 2 == 0 &&
+                          c.dims[q0] % 2 == 0 && cd->t[0] % 2 == 0 && cd->t[q0] % 2 == 0;
+    const bool pairs = elem == 4 && pairable;
+    // 8-byte elements in pairs (16-byte accesses) where every run starts and ends on a line
+    // boundary: half the memory instructions per byte, and the sweet spot moves to tiles of
+    // 16 KiB (four pair slots per thread).  Table fitted to the measured times of every
+    // candidate of 50 line-aligned 8-byte problems of 16 MiB to 680 MiB (squares, cubes,
+    // power-of-two and 48^4 / 96^4 tensors), with and without pairs: picks +3 % on the
+    // mid-size ones, +0.4 % on the 96^4 set; ragged shapes keep single elements in the score
+    // (their pairs run where possible, measured neutral).
+    const bool line_aligned = gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
+                              std::fmod(rout, 128.0) == 0.0;
+    const bool pairs8 = elem == 8 && pairable && line_aligned;
+    static const double kWeight8Pairs[10] = {1.4, 0.85, 0.9, 0.8, 1.0, 1.0, 1.06, 1.1, 1.16, 1.2};
     const bool window_pairs = elem == 4 && cd->align;
-    const int64_t slots_needed = pairs ? vol / 2 : (window_pairs ? read_vol / 2 : read_vol);
+    const int64_t slots_needed = (pairs || pairs8) ? vol / 2 : (window_pairs ? read_vol / 2 : read_vol);
     const int64_t need = (slots_needed + TPERM_MAX_THREADS - 1) / TPERM_MAX_THREADS;
     int bucket = 9;
     for (int i = 0; i < 10; ++i)
@@ -298,7 +310,7 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
             bucket = i;
             break;
         }
-    cost *= (!cd->use_lds && n_tile_dims >= 2 ? kWeightRc : (elem == 4 && !pairs && !window_pairs ? kWeight4 : kWeight8))[bucket];
+    cost *= (!cd->use_lds && n_tile_dims >= 2 ? kWeightRc : (pairs8 ? kWeight8Pairs : (elem == 4 && !pairs && !window_pairs ? kWeight4 : kWeight8)))[bucket];
     // A tile that does not fill the 256 lanes of its workgroup wastes the rest of them.
     if (need == 1) cost /= std::pow((double)slots_needed / TPERM_MAX_THREADS, 0.75);
     // Pipeline fill and drain: a persistent workgroup spends about four tile times without
@@ -332,15 +344,16 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     if (cd->use_lds) cost *= 1.1;
     if (cd->align) cost *= al4 ? kAlign4Weight : kAlignWeight;
     // Tiny tensors (a few rounds of tiles at most) are bound by latency, not bandwidth: what
-    // counts is how long one workgroup needs for its tiles, about 1 us per slot of a thread
-    // and a little more per tile dim (the prologue evaluates every slot's position), spread
-    // over the rounds that overlap.  Expressed in the units of `cost` (1 = the time 15 MB
-    // take), so that it fades out as the tensor grows.  Fitted to the measured times of all
-    // candidates of 100 problems of 8 Ki to 2 Mi elements; picks went from 66 % to 92 % of
-    // the best candidate there, and no pick changed on the large benchmark sets.
+    // counts is how long one workgroup needs for its tiles, a good half microsecond per slot
+    // of a thread and a little more per tile dim (the prologue evaluates every slot's
+    // position), spread over the rounds that overlap.  Expressed in the units of `cost` (1 =
+    // the time 9 MB take), so that it fades out as the tensor grows.  Fitted to the measured
+    // times of all candidates of 100 problems of 8 Ki to 2 Mi elements (picks went from 66 %
+    // to 92 % of the best candidate there) and rescaled by 0.6 after the kernel's start-up
+    // path got shorter (52 problems of 0.25 to 128 MiB: 91.9 % -> 92.7 % of the best candidate).
     double total_bytes = (double)elem;
     for (int z = 0; z < r; ++z) total_bytes *= (double)c.dims[z];
-    cost += (double)need * (1.0 + 0.2 * n_tile_dims) / std::max(1.0, rounds) * (15.0e6 / total_bytes);
+    cost += (double)need * (1.0 + 0.2 * n_tile_dims) / std::max(1.0, rounds) * (9.0e6 / total_bytes);
     // Nontemporal loads and stores when every run starts and ends on a line boundary.
     cd->aligned = (gin >= 128.0 && gout >= 128.0 && std::fmod(rin, 128.0) == 0.0 &&
                    std::fmod(rout, 128.0) == 0.0);
@@ -884,11 +897,10 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     {
         const int q = c.perm[0];
         const int nreg2 = pick_nreg(cand.tile_vol / 2, threads);
-        // 8-byte elements in 16-byte accesses: measured neutral to +1 % on ragged shapes, +6 %
-        // on small line-aligned tensors (few tiles per workgroup), but -2 to -5 % on large
-        // line-aligned ones, which do better with single elements (and loads first).
-        const double rounds = (double)d.num_tiles / (256.0 * std::max(2.0, std::min(8.0, std::round(20480.0 / ((double)cand.tile_vol * elem)))));
-        const bool worth_it = elem == 4 || !cand.aligned || rounds < 16.0 || opts.vec2 == 2;  // 2: asked for explicitly
+        // 8-byte elements in 16-byte accesses wherever the shape allows: measured neutral to
+        // +1 % on ragged shapes, +3 to +14 % on line-aligned tensors once the selector sizes such
+        // tiles by pair slots (see finish_candidate).
+        const bool worth_it = true;
         // In line-aligned windows (4-byte elements only) the written pairs are 8-byte aligned
         // whatever the extents, and an odd row length on the read side is allowed as long as
         // dim 0 is chunked: the tile that holds the odd end reads element by element.
