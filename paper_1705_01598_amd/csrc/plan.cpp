@@ -840,6 +840,12 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         ++run_dims;
         if (cand.t[i] < c.dims[i]) break;
     }
+    // A tile that is one contiguous piece of the input (every tile dim belongs to the run) needs
+    // a padded pitch all the same: the write side walks the image across the run's last dim,
+    // with a power-of-two stride if the dims in front are powers of two (measured on 16 x 2^20
+    // fp32: 16-way bank conflicts, 3.6 TB/s against 5.1 with a padded pitch).  The pad then
+    // goes in front of the tile's last dim.
+    if (run_dims >= (int)n && n >= 2) run_dims = (int)n - 1;
     auto lay = [&](uint32_t p) { return set_lds_strides(&d, dim_of_in, dim_of_out, run_dims, p); };
     const int layout_run_dims = run_dims;
     int pad = 0;
