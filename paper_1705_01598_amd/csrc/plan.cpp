@@ -1067,6 +1067,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
             int tried = 0;
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
+                if (o.align_out == 1 && cd.align) continue;
                 if (tried++ >= 24) break;
                 Plan tmp = *p;
                 tperm_model_t m;
@@ -1080,6 +1081,8 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
         } else {
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
+                // windows switched off: a candidate scored and flagged for them is not this plan
+                if (o.align_out == 1 && cd.align) continue;
                 chosen = cd;
                 have = true;
                 break;
