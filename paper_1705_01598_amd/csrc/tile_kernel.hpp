@@ -79,6 +79,13 @@ __device__ __forceinline__ TileWalk pinned_tile_walk(const TileDesc& d) {
     return w;
 }
 
+// The tile-walk fields as the kernel uses them: a pinned copy, or the descriptor itself.
+template <bool PIN>
+__device__ __forceinline__ typename std::conditional<PIN, TileWalk, const TileDesc&>::type tile_walk_source(const TileDesc& d) {
+    if constexpr (PIN) return pinned_tile_walk(d);
+    else return d;
+}
+
 struct MajorPos {
     uint32_t in, out;        // element offsets of the tile (wave-uniform)
     uint32_t rem_a, rem_b;   // remaining extent of the split dims in this tile
@@ -92,8 +99,8 @@ struct MajorLane {
     uint32_t ext, stride_in, stride_out;
 };
 
-__device__ __forceinline__ MajorPos major_position(const TileWalk& d, const MajorLane& ml,
-                                                   uint32_t b) {
+template <typename D>
+__device__ __forceinline__ MajorPos major_position(const D& d, const MajorLane& ml, uint32_t b) {
     const uint32_t q = fdiv(b, ml.cum);
     const uint32_t c = q - fdiv(q, ml.ext_div) * ml.ext;
     const uint32_t sum_in = row_scan_add(c * ml.stride_in);
@@ -236,35 +243,34 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
 
     // What the tile loop needs of the descriptor, and the constants of the first two tile dims,
     // fetched now in one batch of scalar loads (one round trip to the kernel-argument segment
-    // instead of one per use) and kept in scalar registers.
+    // instead of one per use) and kept in scalar registers.  Not in the kernels with
+    // line-aligned windows: their loop keeps so many scalars alive that pinned ones end up
+    // spilled into vector lanes, which costs the pairs-in-windows form 7 %; there the compiler
+    // reads the descriptor where it needs it.
+    constexpr bool PIN = !ALIGN;
     TileDim first_out[2] = {d.out_order[0], d.out_order[1]};
     TileDim first_in[2] = {d.in_order[0], d.in_order[1]};
-    const TileWalk walk = pinned_tile_walk(d);
-    for (int i = 0; i < 2; ++i) {
-        keep_tile_dim(first_out[i]);
-        if (USE_LDS) keep_tile_dim(first_in[i]);
-    }
-    asm volatile("" : "+s"(in), "+s"(out), "+s"(nbytes));  // the same batch
-    // the other loop constants of the descriptor, under short names
+    typename std::conditional<PIN, const TileWalk, const TileDesc&>::type walk = tile_walk_source<PIN>(d);
     uint32_t n_tile_dims = d.n_tile_dims, tile_vol = d.tile_vol, lds_elems = d.lds_elems;
     uint32_t lds_buffers = d.lds_buffers, pair_lstride = d.pair_lstride, pair_a_split = d.pair_a_split;
-    keep_scalar(n_tile_dims);
-    keep_scalar(tile_vol);
-    if (USE_LDS) {
-        keep_scalar(lds_elems);
-        keep_scalar(lds_buffers);
+    if constexpr (PIN) {
+        for (int i = 0; i < 2; ++i) {
+            keep_tile_dim(first_out[i]);
+            if (USE_LDS) keep_tile_dim(first_in[i]);
+        }
+        asm volatile("" : "+s"(in), "+s"(out), "+s"(nbytes));  // the same batch
+        keep_scalar(n_tile_dims);
+        keep_scalar(tile_vol);
+        if (USE_LDS) {
+            keep_scalar(lds_elems);
+            keep_scalar(lds_buffers);
+        }
+        if (VEC2) {
+            keep_scalar(pair_lstride);
+            keep_scalar(pair_a_split);
+        }
     }
-    if (VEC2) {
-        keep_scalar(pair_lstride);
-        keep_scalar(pair_a_split);
-    }
-    OutAlign oa = d.oa;
-    if (ALIGN) {
-        keep_scalar(oa.line_elems);
-        keep_scalar(oa.total_slots);
-        keep_scalar(oa.lstride_b);
-        keep_scalar(oa.in_halo_elems);
-    }
+    const OutAlign oa = d.oa;
 
     // ALIGN (line-aligned output windows): tile coordinates along the shifted dimension count
     // from a halo origin one line's worth of elements in front of the chunk, so both buffers
@@ -338,13 +344,17 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
             // The first two entries are taken unconditionally, from the copies fetched at the top of
             // the kernel; every turn of the loop below costs one more round trip to the descriptor.  (An entry beyond n_tile_dims is all
             // zero, which is neutral here: quotient 0, no stride, no mask.)
-            digit_step(first_out[0], first_in[0]);
-            digit_step(first_out[1], first_in[1]);
-            for (uint32_t i = 2; i < n_tile_dims; ++i) {
+            if constexpr (PIN) {
+                digit_step(first_out[0], first_in[0]);
+                digit_step(first_out[1], first_in[1]);
+            }
+            for (uint32_t i = PIN ? 2u : 0u; i < n_tile_dims; ++i) {
                 // whole entries at once: one round trip per turn, not one per field
                 TileDim to = d.out_order[i], ti = d.in_order[i];
-                keep_tile_dim(to);
-                if (USE_LDS) keep_tile_dim(ti);
+                if constexpr (PIN) {
+                    keep_tile_dim(to);
+                    if (USE_LDS) keep_tile_dim(ti);
+                }
                 digit_step(to, ti);
             }
 #pragma unroll
