@@ -342,11 +342,11 @@ class Harness:
 
 def device_memory_figures(torch):
     """What the device itself reports about its memory system, next to the vendor's 8 TB/s."""
+    from paper_1705_01598_amd import binding as B
     p = torch.cuda.get_device_properties(0)
-    width = getattr(p, "memory_bus_width", None)
-    clock_khz = getattr(p, "memory_clock_rate", None)
-    out = {"name": p.name, "memory_bus_width_bits": width, "memory_clock_kHz": clock_khz,
-           "compute_units": p.multi_processor_count, "l2_cache_bytes": getattr(p, "L2_cache_size", None)}
+    out = {"name": p.name, "l2_cache_bytes": getattr(p, "L2_cache_size", None)}
+    out.update(B.tperm_device_memory_info())
+    width, clock_khz = out["memory_bus_width_bits"], out["memory_clock_kHz"]
     if width and clock_khz:
         # double data rate: two transfers per reported clock
         out["bus_width_x_clock_x2_GBs"] = round(width / 8 * clock_khz * 1e3 * 2 / 1e9, 1)

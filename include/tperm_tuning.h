@@ -113,6 +113,12 @@ typedef struct {
 } tperm_model_t;
 tperm_status_t tperm_plan_model(tperm_plan_t plan, tperm_model_t *model);
 
+/* What the current HIP device reports about itself, for the benchmark's record next to the
+ * vendor's 8 TB/s figure that Section 3's STREAM-style normalisation is replaced by here: memory
+ * bus width in bits, peak memory clock in kHz, compute units.  Any pointer may be NULL.
+ * TPERM_ERR_HIP without a device. */
+tperm_status_t tperm_device_memory_info(int *bus_width_bits, int *memory_clock_khz, int *compute_units);
+
 /* The checking step of tperm_execute_verified on its own, for tests: compares the multisets of
  * the `count` words of elem_size (4 or 8) bytes at a and at b (DEVICE pointers aligned to the
  * word size; they may be equal).  verdict, workspace and workspace_bytes as for

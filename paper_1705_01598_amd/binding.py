@@ -34,7 +34,8 @@ EXPORTS = ["tperm_plan_create", "tperm_plan_create_forced", "tperm_plan_create_m
            "tperm_cache_tune", "tperm_cache_stats", "tperm_cache_clear"]
 # include/tperm_tuning.h
 TUNING_EXPORTS = ["tperm_plan_create_ex", "tperm_plan_candidate_count", "tperm_plan_create_candidate",
-                  "tperm_plan_index_map", "tperm_plan_model", "tperm_multiset_compare"]
+                  "tperm_plan_index_map", "tperm_plan_model", "tperm_multiset_compare",
+                  "tperm_device_memory_info"]
 
 
 class PlanOpts(ctypes.Structure):
@@ -112,6 +113,7 @@ def lib() -> ctypes.CDLL:
         L.tperm_plan_describe.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.tperm_plan_index_map.argtypes = [vp, i64p]
         L.tperm_plan_model.argtypes = [vp, ctypes.POINTER(Model)]
+        L.tperm_device_memory_info.argtypes = [ip, ip, ip]
         L.tperm_plan_destroy.argtypes = [vp]
         L.tperm_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.tperm_transpose.argtypes = [ctypes.c_int, i64p, ip, ctypes.c_size_t, vp, vp, vp]
@@ -322,6 +324,15 @@ def tperm_plan_index_map(plan: Plan):
     if st != OK:
         raise TpermError(st, "tperm_plan_index_map")
     return buf
+
+
+def tperm_device_memory_info() -> dict:
+    """Memory bus width (bits), peak memory clock (kHz) and compute units of the current device."""
+    w, c, n = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    st = lib().tperm_device_memory_info(ctypes.byref(w), ctypes.byref(c), ctypes.byref(n))
+    if st != OK:
+        raise TpermError(st, "tperm_device_memory_info")
+    return {"memory_bus_width_bits": w.value, "memory_clock_kHz": c.value, "compute_units": n.value}
 
 
 def tperm_plan_model(plan: Plan) -> Model:

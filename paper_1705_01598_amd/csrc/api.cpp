@@ -373,6 +373,28 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
     return TPERM_OK;
 }
 
+tperm_status_t tperm_device_memory_info(int* bus_width_bits, int* memory_clock_khz, int* compute_units) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return TPERM_ERR_HIP;
+    }
+    const struct {
+        int* out;
+        hipDeviceAttribute_t attr;
+    } want[] = {{bus_width_bits, hipDeviceAttributeMemoryBusWidth},
+                {memory_clock_khz, hipDeviceAttributeMemoryClockRate},
+                {compute_units, hipDeviceAttributeMultiprocessorCount}};
+    for (const auto& w : want) {
+        if (w.out == nullptr) continue;
+        if (hipDeviceGetAttribute(w.out, w.attr, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return TPERM_ERR_HIP;
+        }
+    }
+    return TPERM_OK;
+}
+
 tperm_status_t tperm_plan_model(tperm_plan_t plan, tperm_model_t* model) {
     if (plan == nullptr || model == nullptr) return TPERM_ERR_NULL;
     // the plan that runs on suitably aligned pointers, as tperm_plan_describe reports it
