@@ -322,9 +322,10 @@ static bool finish_candidate(const Canonical& c, int elem, Candidate* cd) {
     cost *= 1.0 + 4.0 / std::max(rounds, 4.0);
     // Rows a large power of two apart land in the same memory channels: when the pitch of the
     // rows a tile reads (the input stride of its first dim beyond the input run) is a multiple
-    // of 8 KiB, more than 32 of them per tile cost (measured on the 96^4 permutations, whose
-    // pitches are 2^13 * 9 and 2^18 * 27 bytes: 32 x 32 tiles beat 32 x 96 ones by 2-13 %
-    // there although their output runs are short; no other benchmark set has such pitches).
+    // of 8 KiB, more than 32 of them per tile cost.  A rule about the pitch, whatever the
+    // tensor: with it the 96^4 permutations (pitches 2^13 * 9 and 2^18 * 27 bytes) run 1.7 %
+    // faster as a set (32 x 32 tiles replace 32 x 96 ones there although their output runs are
+    // short), the power-of-two fp32 set and the ragged rank sweep are unchanged (same-box A/B).
     if (cd->use_lds && !cd->align) {
         int z = 0;
         while (z < r) {  // skip the input run
