@@ -55,7 +55,22 @@ SHAPES = [
     ((129, 67, 5), (2, 0, 1)),
     ((8, 8, 8, 8, 8), (1, 3, 0, 2, 4)),         # contraction-style, power-of-two strides
     ((16, 16, 16, 16), (2, 3, 0, 1)),           # fuses to a 256 x 256 matrix transpose
+    ((16, 6000), (1, 0)),                       # thin matrix: the tile is one contiguous piece of the input
+    ((32, 3000), (1, 0)),
+    ((5, 3, 7, 4, 8, 3, 9), (6, 4, 1, 3, 0, 2, 5)),   # input run ends at a dim boundary, next dim has 7 values
+    ((17, 7, 15, 45, 7), (3, 2, 0, 4, 1)),
+    ((128, 128, 32), (1, 0, 2)),                # line-aligned 8-byte shape: pairs sized by pair slots
 ]
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("dims,perm", SHAPES[::3])
+def test_plans_chosen_by_the_analytical_model_match_oracle(dims, perm, elem):
+    """selector = 1: the tile is the one the Section-2.3-style model expects to finish first."""
+    case = wl.make_case(0, 31, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, selector=1)
+    _check(case, plan)
+    plan.destroy()
 
 
 @pytest.mark.parametrize("elem", [8, 4])
