@@ -91,9 +91,13 @@ tperm_status_t tperm_plan_index_map(tperm_plan_t plan, int64_t *out_to_in);
  * cycles = (cycles_mem + cycles_shmem + cycles_ac) * N_iter, with the memory latency driven by
  * the transactions per request and stores to partially written lines counted double (Eq. (13)),
  * re-derived for MI355X: 128-byte lines, 64-lane waves that keep all their requests in flight,
- * 256 compute units, 8 TB/s.  The transaction counts are exact: up to 8 tiles spread over the
- * tile index are walked on the host with the kernel's own index arithmetic and every touched
- * line is tallied.  Host only; plans of the copy and naive classes give TPERM_ERR_KERNEL. */
+ * 256 compute units, 8 TB/s, latencies and departure delay as measured on the chip by pointer
+ * chasing (the counterpart of the paper's Table I).  The transaction counts are exact per tile:
+ * up to 16 tiles spread over the tile index are walked on the host with the kernel's own index
+ * arithmetic and every touched line is tallied; the per-tile figures below are the sample's
+ * counts per useful byte times the bytes an average tile index carries (volume * element size /
+ * tiles), so they are averages over all tiles, ragged ones in their true proportion.
+ * Host only; plans of the copy and naive classes give TPERM_ERR_KERNEL. */
 typedef struct {
     double ld_tran, st_tran;       /* distinct 128-byte lines read / written per tile            */
     double ld_req, st_req;         /* wave-wide load / store instructions per tile               */
@@ -109,7 +113,7 @@ typedef struct {
     double n_iter;                 /* iterations: tiles / (compute units * resident workgroups)  */
     double cycles_total;
     double microseconds;           /* cycles_total at 2.4 GHz                                    */
-    double useful_bytes_per_tile;  /* bytes a tile writes (= reads), ragged edges included       */
+    double useful_bytes_per_tile;  /* bytes an average tile writes (= reads): volume * E / tiles  */
 } tperm_model_t;
 tperm_status_t tperm_plan_model(tperm_plan_t plan, tperm_model_t *model);
 

@@ -9,9 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtperm.so")
 PROBE = os.path.join(HERE, "pattern_probe")
+LATENCY_PROBE = os.path.join(HERE, "latency_probe")
 SOURCES = ["plan.cpp", "model.cpp", "api.cpp", "cache.cpp", "kernels.hip", "verify.hip", "tile_inst_u64_256.hip", "tile_inst_u32_256.hip",
            "tile_inst_u64_64.hip", "tile_inst_u32_64.hip"]
-HEADERS = ["pattern_probe.hip", "plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
+HEADERS = ["pattern_probe.hip", "latency_probe.hip", "plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
            os.path.join("..", "..", "include", "tperm_tuning.h")]
 
 # -packed-fp32-ops is switched off for all device code built here (no packed FP32
@@ -61,6 +62,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
     # the pattern probe: a stand-alone measurement tool (what a transpose tile's access pattern
     # can reach on this memory system, whatever kernel issues it)
     cmd = [hipcc(), *COMMON_FLAGS, *DEVICE_FLAGS, os.path.join(CSRC, "pattern_probe.hip"), "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    # the latency probe: pointer-chasing measurement of the machine constants the analytical
+    # model takes (memory and LDS latency, departure delay)
+    cmd = [hipcc(), *COMMON_FLAGS, *DEVICE_FLAGS, os.path.join(CSRC, "latency_probe.hip"), "-o", LATENCY_PROBE]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -19,20 +19,22 @@ namespace tperm {
 
 namespace {
 
-// MI355X (gfx950) parameters of the model.  Published: 256 compute units, 2.4 GHz, 8 TB/s.
-// Estimated from measurements on the chip: an unloaded HBM read takes about 0.7 us (the
-// read-latency counters give 2300-3300 cycles under full load); a compute unit hands one
-// 128-byte line to the memory system every ~8 cycles when a single wave streams; an LDS access
-// costs ~64 cycles, one more pass per bank conflict; ~300 cycles of address arithmetic, waits
-// and barriers per tile.
+// MI355X (gfx950) parameters of the model, the counterpart of the paper's Table I.
+// Published: 256 compute units, 2.4 GHz, 8 TB/s.  Measured on the chip with the pointer-chasing
+// probe that ships beside this file (latency_probe.hip): a wave-wide load of lines that sit in
+// HBM returns after 1080 cycles on an idle machine; every further independent request of the
+// same wave adds 40 cycles per four lines, and one compute unit streaming with 16 waves takes a
+// line every 9.1 cycles, hence a departure delay of 10 cycles per line; a dependent LDS load
+// takes 64-68 cycles.  Estimated: ~300 cycles of address arithmetic, waits and barriers per tile.
 constexpr double kFreq = 2.4e9;
 constexpr double kNumCU = 256.0;
 constexpr double kMemBW = 8.0e12;
-constexpr double kBaseLat = 1600.0;
-constexpr double kDelta = 8.0;
-constexpr double kLdsLat = 64.0;
+constexpr double kBaseLat = 1080.0;
+constexpr double kDelta = 10.0;
+constexpr double kLdsLat = 66.0;
 constexpr double kCyclesAc = 300.0;
 constexpr double kLine = 128.0;
+constexpr uint32_t kModelSamples = 16;
 
 // Bytes each touched line receives: a small open-addressing table keyed by line number.
 struct LineTally {
@@ -89,11 +91,17 @@ tperm_status_t model_plan(const Plan& plan, tperm_model_t* out) {
     const OutAlign& oa = d.oa;
     const bool windows = plan.use_lds && oa.enabled != 0u;
     LineTally rd(15), wr(15);  // up to 8192 slots of up to 16 bytes: at most 2 lines each
-    // tiles sampled evenly over the tile index, the last one (ragged corner) included
-    const uint32_t n_samples = std::min<uint32_t>(d.num_tiles, 8u);
+    // Tiles are sampled, as in the paper; one per equal stretch of the tile index, at a position
+    // inside the stretch that moves by the golden ratio from one stretch to the next, so the
+    // samples do not fall in step with the period of any tile counter.
+    const uint32_t n_samples = std::min<uint32_t>(d.num_tiles, kModelSamples);
     double ld_lines = 0, st_lines = 0, st_full = 0, st_part = 0, useful = 0, existing = 0, dummy1 = 0, dummy2 = 0, ld_runs = 0, st_runs = 0;
     for (uint32_t s = 0; s < n_samples; ++s) {
-        const uint32_t b = n_samples == 1 ? 0u : (uint32_t)(((uint64_t)s * (d.num_tiles - 1u)) / (n_samples - 1u));
+        uint32_t b = s;
+        if (d.num_tiles > n_samples) {
+            const double inside = std::fmod(0.5 + 0.6180339887498949 * (double)s, 1.0);
+            b = std::min<uint32_t>(d.num_tiles - 1u, (uint32_t)(((double)s + inside) * (double)d.num_tiles / (double)n_samples));
+        }
         uint64_t maj_in = 0, maj_out = 0;
         uint32_t coord[TPERM_DESC_MAX_DIMS];
         for (uint32_t l = 0; l < TPERM_DESC_MAX_DIMS; ++l) {
@@ -152,18 +160,26 @@ tperm_status_t model_plan(const Plan& plan, tperm_model_t* out) {
         wr.count(&st_lines, &st_full, &st_part, &st_runs);
         useful += elems * elem;
     }
-    if (existing == 0.0) return TPERM_ERR_INTERNAL;
+    if (existing == 0.0 || useful == 0.0) return TPERM_ERR_INTERNAL;
     const double waves = (double)plan.threads / 64.0;
-    out->ld_tran = ld_lines / existing;
-    out->st_tran = st_lines / existing;
-    out->cl_full = st_full / existing;
-    out->cl_part = st_part / existing;
-    out->useful_bytes_per_tile = useful / existing;
+    // Ratio estimate: the sample gives lines per useful byte; the bytes an average tile index
+    // carries are known exactly (all tile indices together write the tensor once, the
+    // combinations of split counters that do not exist write nothing).  Ragged tiles that the
+    // sample over- or under-represents then do not shift the totals.
+    double volume = 1.0;
+    for (int i = 0; i < plan.rank; ++i) volume *= (double)plan.dims[i];
+    const double bytes_per_tile = volume * (double)elem / (double)d.num_tiles;
+    const double per_byte = bytes_per_tile / useful;
+    out->ld_tran = ld_lines * per_byte;
+    out->st_tran = st_lines * per_byte;
+    out->cl_full = st_full * per_byte;
+    out->cl_part = st_part * per_byte;
+    out->useful_bytes_per_tile = bytes_per_tile;
     // one request = one wave-wide memory instruction; a thread issues nreg loads and nreg stores per tile
     out->ld_req = out->st_req = (double)plan.nreg * waves;
     const double part_frac = out->cl_part / std::max(1.0, out->cl_full + out->cl_part);
-    out->ld_runs = ld_runs / existing;
-    out->st_runs = st_runs / existing;
+    out->ld_runs = ld_runs * per_byte;
+    out->st_runs = st_runs * per_byte;
     out->tpr_mem = (out->ld_tran + out->st_tran * (1.0 + part_frac)) / (out->ld_req + out->st_req);  // Eq. (13)
     out->mem_lat = kBaseLat + std::max(0.0, out->tpr_mem - 1.0) * kDelta;
     out->mlp = (double)plan.nreg;  // independent requests per wave per iteration (the paper's nReg for Packed)

@@ -559,6 +559,35 @@ def test_model_line_counts_against_enumeration(d0, d1, t0, t1):
     assert m.cycles_total == pytest.approx((m.cycles_mem + m.cycles_lds + m.cycles_ac) * m.n_iter)   # Eq. (10)
 
 
+def test_model_sampled_line_counts_track_the_whole_tensor():
+    """More tiles than the model samples: line-aligned tiles have a closed form, and on a ragged
+    matrix the sampled estimate stays close to an enumeration of every tile (the ragged edge
+    tiles, which a sample can over- or under-represent, must not shift the totals)."""
+    tile = dict(kernel_class=B.KERNEL_PACKED, m=1, k=1, vec2=1, align_out=1)
+    m = B.tperm_plan_model(B.tperm_plan_create_ex((4096, 4096), (1, 0), 8, tile_in=32, tile_out=32, **tile))
+    assert (m.ld_tran, m.st_tran, m.cl_full, m.cl_part) == (64, 64, 64, 0)     # 32 rows of 256 bytes either way
+    assert m.useful_bytes_per_tile == 32 * 32 * 8
+    d0, d1, t = 301, 299, 32
+    plan = B.tperm_plan_create_ex((d0, d1), (1, 0), 8, tile_in=t, tile_out=t, **tile)
+    info = plan.describe()
+    m = B.tperm_plan_model(plan)
+    ld = st = full = tiles = 0
+    for a0 in range(0, d0, t):
+        for a1 in range(0, d1, t):
+            i0 = range(a0, min(a0 + t, d0))
+            i1 = range(a1, min(a1 + t, d1))
+            n, _ = _lines_of([((x + d0 * y) * 8, 8) for x in i0 for y in i1])
+            ld += n
+            n, f = _lines_of([((y + d1 * x) * 8, 8) for x in i0 for y in i1])
+            st += n
+            full += f
+            tiles += 1
+    assert tiles == info.num_tiles == 100
+    assert m.useful_bytes_per_tile == pytest.approx(d0 * d1 * 8 / tiles)
+    assert m.ld_tran == pytest.approx(ld / tiles, rel=0.05) and m.st_tran == pytest.approx(st / tiles, rel=0.05)
+    assert m.cl_part == pytest.approx((st - full) / tiles, rel=0.10)
+
+
 def test_model_prices_partial_lines_and_short_runs():
     us = lambda dims, perm, **kw: B.tperm_plan_model(B.tperm_plan_create_ex(dims, perm, 8, **kw)).microseconds
     tile = dict(kernel_class=B.KERNEL_PACKED, m=1, k=1, vec2=1, align_out=1)
