@@ -14,7 +14,8 @@
 //   burst:  one wave issues N independent wave-wide loads (64 lanes x 8 bytes = four lines
 //           each) to lines nobody has touched since the caches were flushed, then waits for
 //           all of them: T(N) = latency + (N - 1) * departure delay.
-//   stream: one workgroup on one compute unit streams 256 MiB; bytes per cycle per compute unit.
+//   stream: one workgroup on one compute unit streams 256 MiB with 1, 4 or 8 loads in flight
+//           per thread; bytes per cycle per compute unit.
 // Time base: the constant-rate wall clock the kernels read (hipDeviceAttributeWallClockRate),
 // converted to cycles of the published 2.4 GHz engine clock.
 #include <hip/hip_runtime.h>
@@ -109,15 +110,21 @@ __global__ void __launch_bounds__(64) burst_kernel(const uint64_t* __restrict__ 
     if (s == 0x123456789ull) out[1] = s;  // practically never true; keeps the loads
 }
 
-// One workgroup streams `n16` 16-byte words; the sum keeps the loads.
+// One workgroup streams `n16` 16-byte words, every thread with U independent loads in flight
+// (n16 is a multiple of U * blockDim.x); the sum keeps the loads.
 typedef uint32_t word4 __attribute__((ext_vector_type(4)));
 
+template <int U>
 __global__ void __launch_bounds__(1024) stream_kernel(const word4* __restrict__ src, size_t n16, uint64_t* __restrict__ out) {
     uint32_t acc = 0;
+    const size_t step = (size_t)U * blockDim.x;
     const uint64_t t0 = wall_clock64();
-    for (size_t i = threadIdx.x; i < n16; i += blockDim.x) {
-        const word4 v = __builtin_nontemporal_load(src + i);
-        acc += v.x ^ v.y ^ v.z ^ v.w;
+    for (size_t i = threadIdx.x; i < n16; i += step) {
+        word4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + (size_t)u * blockDim.x);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     asm volatile("" : "+v"(acc));
     __syncthreads();
@@ -299,22 +306,30 @@ int main(int argc, char** argv) {
     // ---- stream: what one compute unit can pull ---------------------------------------------
     {
         std::printf("\nstream: one workgroup on one compute unit reads 256 MiB with 16-byte nontemporal loads\n");
-        std::printf("%8s %12s %14s %16s\n", "threads", "GB/s", "bytes/cycle", "cycles per line");
+        std::printf("%8s %10s %12s %14s %16s\n", "threads", "in flight", "GB/s", "bytes/cycle", "cycles per line");
         const size_t bytes = std::min<size_t>(max_bytes, (size_t)256 << 20);
-        for (int threads : {64, 256, 512, 1024}) {
-            double best = 1e30;
-            for (int rep = 0; rep < 2; ++rep) {
-                hipLaunchKernelGGL(stream_kernel, dim3(1), dim3(threads), 0, 0, reinterpret_cast<const word4*>(lines), bytes / 16, out_dev);
-                CHECK(hipGetLastError());
-                CHECK(hipDeviceSynchronize());
-                uint64_t ticks = 0;
-                CHECK(hipMemcpy(&ticks, out_dev, sizeof(ticks), hipMemcpyDeviceToHost));
-                best = std::min(best, (double)ticks * tick_ns);
+        for (int unroll : {1, 4, 8}) {
+            for (int threads : {64, 256, 512, 1024}) {
+                if ((bytes / 16) % ((size_t)unroll * threads) != 0) continue;
+                double best = 1e30;
+                for (int rep = 0; rep < 2; ++rep) {
+                    const word4* src = reinterpret_cast<const word4*>(lines);
+                    if (unroll == 1) hipLaunchKernelGGL(stream_kernel<1>, dim3(1), dim3(threads), 0, 0, src, bytes / 16, out_dev);
+                    else if (unroll == 4) hipLaunchKernelGGL(stream_kernel<4>, dim3(1), dim3(threads), 0, 0, src, bytes / 16, out_dev);
+                    else hipLaunchKernelGGL(stream_kernel<8>, dim3(1), dim3(threads), 0, 0, src, bytes / 16, out_dev);
+                    CHECK(hipGetLastError());
+                    CHECK(hipDeviceSynchronize());
+                    uint64_t ticks = 0;
+                    CHECK(hipMemcpy(&ticks, out_dev, sizeof(ticks), hipMemcpyDeviceToHost));
+                    best = std::min(best, (double)ticks * tick_ns);
+                }
+                const double gbs = (double)bytes / best;
+                const double bpc = gbs / kEngineGHz;
+                char inflight[32];
+                std::snprintf(inflight, sizeof inflight, "%d KiB", unroll * threads * 16 / 1024);
+                std::printf("%8d %10s %12.1f %14.2f %16.1f\n", threads, inflight, gbs, bpc, 128.0 / bpc);
+                std::fflush(stdout);
             }
-            const double gbs = (double)bytes / best;
-            const double bpc = gbs / kEngineGHz;
-            std::printf("%8d %12.1f %14.2f %16.1f\n", threads, gbs, bpc, 128.0 / bpc);
-            std::fflush(stdout);
         }
     }
     CHECK(hipFree(flush));

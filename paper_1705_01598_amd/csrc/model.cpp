@@ -22,15 +22,16 @@ namespace {
 // MI355X (gfx950) parameters of the model, the counterpart of the paper's Table I.
 // Published: 256 compute units, 2.4 GHz, 8 TB/s.  Measured on the chip with the pointer-chasing
 // probe that ships beside this file (latency_probe.hip): a wave-wide load of lines that sit in
-// HBM returns after 1080 cycles on an idle machine; every further independent request of the
-// same wave adds 40 cycles per four lines, and one compute unit streaming with 16 waves takes a
-// line every 9.1 cycles, hence a departure delay of 10 cycles per line; a dependent LDS load
-// takes 64-68 cycles.  Estimated: ~300 cycles of address arithmetic, waits and barriers per tile.
+// HBM returns after 1080 cycles on an idle machine; a single wave gets a further independent
+// four-line request under way every 40 cycles, and a whole compute unit with 32 KiB or more in
+// flight takes a line every 5 cycles (26 bytes per cycle), which is the departure delay of a
+// compute unit; a dependent LDS load takes 64-68 cycles.  Estimated: ~300 cycles of address
+// arithmetic, waits and barriers per tile.
 constexpr double kFreq = 2.4e9;
 constexpr double kNumCU = 256.0;
 constexpr double kMemBW = 8.0e12;
 constexpr double kBaseLat = 1080.0;
-constexpr double kDelta = 10.0;
+constexpr double kDelta = 5.0;
 constexpr double kLdsLat = 66.0;
 constexpr double kCyclesAc = 300.0;
 constexpr double kLine = 128.0;
