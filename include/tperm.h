@@ -115,7 +115,13 @@ typedef struct {
                                             * input dim 0, any extents, any element-aligned *
                                             * pointers; odd row ends and clipped windows    *
                                             * move single elements).                         */
-    int reserved[2];
+    int large;                             /* 1: a tensor of 4 GiB or more (or a plan made  *
+                                            * to run like one): byte offsets no longer fit  *
+                                            * 32 bits, so every tile addresses its pieces   *
+                                            * from its own origin; plain LDS-staged tiles   *
+                                            * of 256 threads (no windows, pairs or twins),  *
+                                            * or the gather kernel when no tile fits.       */
+    int reserved[1];
 } tperm_plan_info_t;
 
 /* Create a plan: the first call of the create / execute / destroy triple of Section 2.3.  The
@@ -123,8 +129,11 @@ typedef struct {
  * and a tile with its cost estimate (the paper's heuristic selection, Section 2.3; its
  * classes are those of Section 2.2).  dims[rank] and perm[rank] are host arrays, copied; the
  * caller keeps ownership.  elem_size is in bytes (4 or 8, the two widths of Section 3).  Host
- * only.  On failure *plan is set to NULL and the status says why: NULL (plan, dims or perm),
- * RANK, DIMS, PERM, ELEM_SIZE, TOO_LARGE, NOMEM. */
+ * only.  Tensors of up to 2^31 - 1 elements are accepted (element indices are 31-bit, as the
+ * int indices of Algorithm 1); those of 4 GiB and more run a form of the tile kernels that
+ * addresses every tile from its own origin (large in tperm_plan_info_t).  On failure *plan is
+ * set to NULL and the status says why: NULL (plan, dims or perm), RANK, DIMS, PERM, ELEM_SIZE,
+ * TOO_LARGE, NOMEM. */
 tperm_status_t tperm_plan_create(tperm_plan_t *plan, int rank, const int64_t *dims,
                                  const int *perm, size_t elem_size);
 

@@ -57,6 +57,9 @@ typedef struct {
     int selector;       /* how the tile is chosen when none is forced: 0 = the fitted cost      *
                          * estimate (default); 1 = the analytical model of tperm_plan_model,    *
                          * evaluated on the best-scored candidates (slower plan creation)       */
+    int large;          /* 1 = plan and run the tensor the way tensors of 4 GiB and more are     *
+                         * (large in tperm_plan_info_t), whatever its size: the form can then   *
+                         * be checked on tensors a test can afford; 0 = by size                  */
 } tperm_plan_opts_t;
 
 /* tperm_plan_create with overrides.  opts may be NULL (then it is tperm_plan_create).  A

@@ -46,7 +46,8 @@ class PlanOpts(ctypes.Structure):
                 ("window_out", ctypes.c_int), ("threads", ctypes.c_int),
                 ("lds_buffers", ctypes.c_int), ("align_out", ctypes.c_int),
                 ("tile_order", ctypes.c_int), ("loads_first", ctypes.c_int),
-                ("vec2", ctypes.c_int), ("pair_elems", ctypes.c_int), ("selector", ctypes.c_int)]
+                ("vec2", ctypes.c_int), ("pair_elems", ctypes.c_int), ("selector", ctypes.c_int),
+                ("large", ctypes.c_int)]
 
 
 class Model(ctypes.Structure):
@@ -68,8 +69,8 @@ class PlanInfo(ctypes.Structure):
                 ("lds_pad", ctypes.c_int), ("score", ctypes.c_double),
                 ("blocks_per_cu", ctypes.c_int), ("cache_policy", ctypes.c_int),
                 ("align_out", ctypes.c_int), ("paired", ctypes.c_int),
-                ("loads_first", ctypes.c_int), ("vec2", ctypes.c_int),
-                ("reserved", ctypes.c_int * 2)]
+                ("loads_first", ctypes.c_int), ("vec2", ctypes.c_int), ("large", ctypes.c_int),
+                ("reserved", ctypes.c_int * 1)]
 
 
 class TpermError(RuntimeError):
@@ -194,7 +195,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                          blocks_per_cu: int = 0, cache_policy: int = 0, window_in: int = 0,
                          window_out: int = 0, threads: int = 0, lds_buffers: int = 0,
                          align_out: int = 0, tile_order: int = 0, pair_elems: int = 0,
-                         loads_first: int = 0, vec2: int = 0, selector: int = 0) -> Plan:
+                         loads_first: int = 0, vec2: int = 0, selector: int = 0, large: int = 0) -> Plan:
     rank, cd, cp = _marshal(dims, perm)
     opts = PlanOpts(kernel_class=int(kernel_class), m=int(m), tile_in=int(tile_in), k=int(k),
                     tile_out=int(tile_out), lds_pad=int(lds_pad), grid_mode=int(grid_mode),
@@ -202,7 +203,7 @@ def tperm_plan_create_ex(dims: Sequence[int], perm: Sequence[int], elem_size: in
                     window_in=int(window_in), window_out=int(window_out), threads=int(threads),
                     lds_buffers=int(lds_buffers), align_out=int(align_out),
                     tile_order=int(tile_order), pair_elems=int(pair_elems),
-                    loads_first=int(loads_first), vec2=int(vec2), selector=int(selector))
+                    loads_first=int(loads_first), vec2=int(vec2), selector=int(selector), large=int(large))
     h = ctypes.c_void_p()
     st = lib().tperm_plan_create_ex(ctypes.byref(h), rank, cd, cp, int(elem_size), ctypes.byref(opts))
     if st != OK:

@@ -319,7 +319,7 @@ tperm_status_t tperm_multiset_compare(const void* a, const void* b, int64_t coun
     if (a == nullptr || b == nullptr) return TPERM_ERR_NULL;
     if (elem_size != 4 && elem_size != 8) return TPERM_ERR_ELEM_SIZE;
     if (count < 1) return TPERM_ERR_DIMS;
-    if (count >= ((int64_t)1 << 31) || (uint64_t)count * elem_size >= ((uint64_t)1 << 32) - 256) return TPERM_ERR_TOO_LARGE;
+    if (count >= ((int64_t)1 << 31)) return TPERM_ERR_TOO_LARGE;
     if (((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) % elem_size) != 0) return TPERM_ERR_ALIGN;
     tperm_status_t st = check_verify_args(a, b, (size_t)count * elem_size, verdict, workspace, workspace_bytes,
                                           tperm::verify_scratch_bytes((uint64_t)count));
@@ -367,7 +367,9 @@ tperm_status_t tperm_plan_describe(tperm_plan_t plan, tperm_plan_info_t* info) {
         info->align_out = p.align_out ? 1 : 0;
         info->loads_first = p.loads_first ? 1 : 0;
         info->vec2 = p.vec2 ? 1 : 0;
+        info->large = p.big ? 1 : 0;
     } else {
+        info->large = (p.kclass == TPERM_KERNEL_NAIVE && p.big) ? 1 : 0;
         info->threads = 256;
     }
     return TPERM_OK;

@@ -12,6 +12,7 @@ const void* tile_kernel_u64_256(int nreg, bool use_lds, int nt, bool align, bool
 const void* tile_kernel_u32_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
 const void* tile_kernel_u64_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
 const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
+const void* tile_kernel_big(int elem, int nreg, int nt, bool acc);
 
 
 // ---------------------------------------------------------------------------------------
@@ -100,6 +101,10 @@ static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_align
     const int pol = tile_launch_policy(plan, acc, sector_aligned_out);
     const int nt = pol == 2 ? 2 : (pol == 3 ? 1 : (pol == 4 ? 3 : 0));  // template parameter NT
     const bool align = plan.align_out;
+    if (plan.big) {
+        if (!plan.use_lds || align || plan.vec2 || plan.loads_first || plan.threads != 256) return nullptr;
+        return tile_kernel_big(plan.elem, plan.nreg, nt, acc);
+    }
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)
                                   : tile_kernel_u64_256(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2);
@@ -123,7 +128,8 @@ hipError_t launch_tile(const Plan& plan, const void* in, void* out, hipStream_t 
     const void* f = tile_kernel_for(plan, accumulate, (reinterpret_cast<uintptr_t>(out) & 31u) == 0);
     if (f == nullptr || grid < 1) return hipErrorInvalidValue;
     TileDesc d = plan.tile;
-    uint32_t nbytes = (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
+    // large tensors: the range one buffer description covers from a tile's origin
+    uint32_t nbytes = plan.big ? TPERM_BIG_RANGE : (uint32_t)((uint64_t)plan.c.volume * (uint64_t)plan.elem);
     void* args[] = {(void*)&d, (void*)&in, (void*)&out, (void*)&nbytes};
     return hipLaunchKernel(f, dim3((unsigned)grid), dim3((unsigned)plan.threads), args,
                            (size_t)plan.lds_bytes * plan.tile.lds_buffers, stream);

@@ -45,8 +45,6 @@ tperm_status_t validate(int rank, const int64_t* dims, const int* perm, size_t e
         vol *= dims[z];
         if (vol >= ((int64_t)1 << 31)) return TPERM_ERR_TOO_LARGE;
     }
-    // byte offsets inside the tensor are kept in 32 bits (buffer addressing)
-    if (vol * (int64_t)elem >= ((int64_t)1 << 32) - 256) return TPERM_ERR_TOO_LARGE;
     return TPERM_OK;
 }
 
@@ -588,6 +586,8 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     const int lds_pad = opts.lds_pad, grid_mode = opts.grid_mode, window_in = opts.window_in,
               window_out = opts.window_out, threads = opts.threads, lds_buffers = opts.lds_buffers;
     if (threads != 64 && threads != 256) return TPERM_ERR_KERNEL;
+    // large tensors run plain LDS-staged tiles of 256 threads (the forms instantiated for them)
+    if (opts.big && (!cand.use_lds || threads != 256)) return TPERM_ERR_KERNEL;
     const Canonical& c = plan->c;
     const int r = c.rank;
     const int elem = plan->elem;
@@ -614,7 +614,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     const int q0 = c.perm[0];
     const int64_t line_elems = 128 / elem;
     bool align_out = false;
-    if ((opts.align_out == 2 || (opts.align_out == 0 && cand.align)) && cand.use_lds && threads == 256 &&
+    if (!opts.big && (opts.align_out == 2 || (opts.align_out == 0 && cand.align)) && cand.use_lds && threads == 256 &&
         q0 != 0 && cand.k == 1 && cand.t[q0] < c.dims[q0] &&
         cand.t[q0] >= line_elems && cand.t[q0] % line_elems == 0 &&
         cand.t[q0] + line_elems <= 0x7FFF &&
@@ -917,7 +917,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
                                   (split_dim[0] == 0 || cand.t[0] == c.dims[0]);
         const bool pair_plain = !align_out && worth_it && nreg2 > 0 && c.dims[0] % 2 == 0 &&
                                 c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 && cand.t[q] % 2 == 0;
-        if (opts.vec2 >= 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
+        if (!opts.big && opts.vec2 >= 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
             dim_of_in[0] == 0 && dim_of_out[0] == q) {
             TileDim& a = d.in_order[0];
             a.ext /= 2;
@@ -943,6 +943,16 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         }
     }
 
+    plan->big = opts.big;
+    if (opts.big) {
+        // every position inside a tile, on either side, within the range of one buffer description
+        uint64_t span_in = 0, span_out = 0;
+        for (uint32_t i = 0; i < d.n_tile_dims; ++i) {
+            span_in += (uint64_t)(d.in_order[i].ext - 1u) * d.in_order[i].gstride;
+            span_out += (uint64_t)(d.out_order[i].ext - 1u) * d.out_order[i].gstride;
+        }
+        if ((std::max(span_in, span_out) + 1u) * (uint64_t)elem > (uint64_t)TPERM_BIG_RANGE) return TPERM_ERR_KERNEL;
+    }
     plan->tile = d;
     plan->cand = cand;
     plan->kclass = cand.kclass;
@@ -962,7 +972,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
         plan->cache_policy = cand.aligned ? 2 : (store_nt ? (cand.load_nt ? 2 : 3) : (cand.load_nt ? 4 : 1));
         // loads before stores pays on line-aligned shapes with small LDS-staged tiles only
         // (measured per case over all benchmark sets; see tile_kernel)
-        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6 && !plan->vec2 && !align_out;
+        plan->loads_first = cand.aligned && cand.use_lds && nreg <= 6 && !plan->vec2 && !align_out && !opts.big;
     }
     plan->lds_pad = pad;
     plan->align_out = align_out;
@@ -992,6 +1002,11 @@ void build_naive_desc(Plan* plan) {
 // plan creation
 // ---------------------------------------------------------------------------------------
 
+// Tensors whose byte offsets do not fit the 32-bit operands of buffer addressing.
+static bool is_big(const Canonical& c, int elem) {
+    return (uint64_t)c.volume * (uint64_t)elem >= ((uint64_t)1 << 32) - 256u;
+}
+
 tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int* perm,
                            size_t elem, const tperm_plan_opts_t* opts) {
     if (out == nullptr) return TPERM_ERR_NULL;
@@ -1016,6 +1031,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     if (opts) o = *opts;
     const int want = o.kernel_class;
     const bool identity = (p->c.rank == 1);
+    p->big = is_big(p->c, p->elem) || o.large == 1;
 
     auto fail = [&](tperm_status_t s) {
         delete p;
@@ -1046,6 +1062,14 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     bo.align_out = o.align_out;
     bo.tile_order = o.tile_order > 0 ? o.tile_order - 1 : kDefaultTileOrder;
     bo.vec2 = o.vec2 == 2 ? 2 : 0;
+    bo.big = p->big;
+    if (bo.big && want == TPERM_KERNEL_ROWCOPY) return fail(TPERM_ERR_KERNEL);
+    // can this candidate run the problem as given (large tensors: a tile whose positions fit)
+    auto runnable = [&](const Candidate& cd) {
+        if (!bo.big) return true;
+        Plan tmp = *p;
+        return build_tile_plan(&tmp, cd, bo) == TPERM_OK;
+    };
     Candidate chosen;
     bool have = false;
     if (o.m > 0 || o.k > 0) {
@@ -1068,7 +1092,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
             int tried = 0;
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
-                if (o.align_out == 1 && cd.align) continue;
+                if ((o.align_out == 1 || bo.big) && cd.align) continue;
                 if (tried++ >= 24) break;
                 Plan tmp = *p;
                 tperm_model_t m;
@@ -1083,16 +1107,30 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
                 // windows switched off: a candidate scored and flagged for them is not this plan
-                if (o.align_out == 1 && cd.align) continue;
+                if ((o.align_out == 1 || bo.big) && cd.align) continue;
+                if (!runnable(cd)) continue;
                 chosen = cd;
                 have = true;
                 break;
             }
         }
     }
-    if (!have) return fail(TPERM_ERR_KERNEL);
+    if (!have) {
+        // a large tensor none of whose tiles fits the range of a buffer description: the gather
+        // kernel, which computes whole addresses, moves it
+        if (bo.big && want == TPERM_KERNEL_AUTO) {
+            p->kclass = TPERM_KERNEL_NAIVE;
+            *out = p;
+            return TPERM_OK;
+        }
+        return fail(TPERM_ERR_KERNEL);
+    }
     st = build_tile_plan(p, chosen, bo);
     if (st != TPERM_OK) return fail(st);
+    if (bo.big) {
+        // options that large tensors have no kernels for are ignored
+        o.loads_first = 0;
+    }
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy >= 1 && o.cache_policy <= 4) p->cache_policy = o.cache_policy;
     if (o.loads_first == 1 || o.loads_first == 2) p->loads_first = o.loads_first == 2;
@@ -1120,6 +1158,7 @@ tperm_status_t create_plan_with_candidate(Plan** out, int rank, const int64_t* d
     build_naive_desc(p);
     TileBuildOpts bo;
     bo.vec2 = vec2 ? 1 : 0;
+    bo.big = is_big(p->c, p->elem);
     st = build_tile_plan(p, cand, bo);
     if (st != TPERM_OK) {
         delete p;

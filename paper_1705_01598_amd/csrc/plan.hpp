@@ -96,6 +96,7 @@ struct Plan {
     bool vec2 = false;         // 4-byte elements move in pairs; needs 8-byte aligned pointers
     bool loads_first = false;  // next tile's loads are issued before this tile's stores
     int cache_policy = 1;    // 1 = cached, 2 = nontemporal loads and stores, 3 = nontemporal stores, 4 = nontemporal loads
+    bool big = false;        // tensor of 4 GiB or more: tiles describe their buffers from their own origin
     TileDesc tile;
     NaiveDesc naive;
     // launch geometry, resolved on first execute (needs the device); 0 = not yet
@@ -123,6 +124,7 @@ struct TileBuildOpts {
     int align_out = 0;      // line-aligned output windows: 0 = as the candidate says, 1 = off, 2 = on where the tile allows
     int tile_order = kDefaultTileOrder;  // 0: input-major, 1: output-major
     int vec2 = 0;           // elements in pairs: 0 = off, 1 = where possible and worth it, 2 = wherever possible
+    bool big = false;       // tensor of 4 GiB or more: plain LDS-staged tiles of 256 threads whose positions stay below TPERM_BIG_RANGE
 };
 tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuildOpts& opts);
 void build_naive_desc(Plan* plan);

@@ -205,9 +205,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // the tile kernel
 // ---------------------------------------------------------------------------------------
 
-template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2>
+// BIG: tensors of 4 GiB and more.  A tile's origin (its major offset) no longer fits the 32-bit
+// scalar offset of a buffer access, so it goes into the base address instead: every tile
+// describes its buffers anew, starting at its own origin, and the scalar offset stays zero.  The
+// lane offsets (positions inside the tile, which the planner keeps below kBigRange bytes) and
+// the dropped-offset masking work as before; nbytes is then kBigRange, the range one such
+// description covers.  Plain LDS-staged tiles only.
+template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2, bool BIG = false>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_arg, uint32_t nbytes_arg) {
+    static_assert(!BIG || (USE_LDS && !ALIGN && !VEC2 && !LOADS_FIRST), "large tensors: plain LDS-staged tiles");
     const T* in = in_arg;
     T* out = out_arg;
     uint32_t nbytes = nbytes_arg;
@@ -278,9 +285,9 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
     // a tensor's first element are masked (lo_b).
     const uint32_t halo_in = ALIGN ? oa.in_halo_elems * (uint32_t)sizeof(T) : 0u;
     const uint32_t halo_out = ALIGN ? oa.line_elems * (uint32_t)sizeof(T) : 0u;
-    const __amdgpu_buffer_rsrc_t rsrc_in =
+    const __amdgpu_buffer_rsrc_t rsrc_in_whole =
         make_rsrc(reinterpret_cast<const char*>(in) - halo_in, nbytes + halo_in);
-    const __amdgpu_buffer_rsrc_t rsrc_out =
+    const __amdgpu_buffer_rsrc_t rsrc_out_whole =
         make_rsrc(reinterpret_cast<char*>(out) - halo_out, nbytes + halo_out);
 
     // minor positions of this thread's slots; global offsets are kept in BYTES
@@ -404,8 +411,19 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
         return read_ok(j, t) && slot_valid_from(rd_mask[j] + 1u, t.rem_a, t.lo_b, t.span_b);
     };
     auto odd_row_end = [&](const MajorPos& t) { return PAIRWIN && pair_a_split != 0u && (t.rem_a & 1u) != 0u; };
+    // the buffer description and scalar offset that reach element `origin` of a tensor
+    auto reach = [&](const __amdgpu_buffer_rsrc_t& whole, const void* base, uint32_t origin, uint32_t* soff) {
+        if constexpr (BIG) {
+            *soff = 0u;
+            return make_rsrc(reinterpret_cast<const char*>(base) + (uint64_t)origin * sizeof(T), nbytes);
+        } else {
+            *soff = origin * (uint32_t)sizeof(T);
+            return whole;
+        }
+    };
     auto load_tile = [&](const MajorPos& t) {
-        const uint32_t soff = t.in * (uint32_t)sizeof(T);
+        uint32_t soff;
+        const __amdgpu_buffer_rsrc_t rsrc_in = reach(rsrc_in_whole, in, t.in, &soff);
         if constexpr (PAIRWIN) {
             if (odd_row_end(t)) {
 #pragma unroll
@@ -431,7 +449,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
         const reg_t nothing = {};
 #pragma unroll
         for (int j = 0; j < NREG; ++j)  // distinct offsets, or the compiler folds them into one
-            io::store(nothing, rsrc_out, kDroppedOffset + (LOADS_FIRST ? 0u : 4u * (uint32_t)j), 0u);
+            io::store(nothing, rsrc_out_whole, kDroppedOffset + (LOADS_FIRST ? 0u : 4u * (uint32_t)j), 0u);
     }
     // the position of the tile after this one is worked out while the loads are in flight
     uint32_t bn = tile_of(walk, block, grid, it + 1);
@@ -542,7 +560,8 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
             // sinking these loads below the stores
             if (bn < walk.num_tiles) issue_next_loads();
         }
-        const uint32_t soff_out = pos.out * (uint32_t)sizeof(T);
+        uint32_t soff_out;
+        const __amdgpu_buffer_rsrc_t rsrc_out = reach(rsrc_out_whole, out, pos.out, &soff_out);
         if (ACC) {
             // out = out + transposed in: fetch the old output values (all loads first), add
             reg_t old[NREG];
@@ -585,12 +604,12 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
 
 // Kernel pointer for one element type and workgroup size; nullptr if the combination is
 // not instantiated.  Accumulating kernels (ACC) exist for 256 threads, cached policy.
-template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST = false, bool VEC2 = false>
+template <typename T, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST = false, bool VEC2 = false, bool BIG = false>
 static const void* tile_kernel_ptr(int nreg) {
     switch (nreg) {
 #define TPERM_CASE(N) \
     case N:           \
-        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, LOADS_FIRST, VEC2>);
+        return reinterpret_cast<const void*>(&tile_kernel<T, N, THREADS, USE_LDS, NT, ALIGN, ACC, LOADS_FIRST, VEC2, BIG>);
         TPERM_CASE(4)
         TPERM_CASE(8)
         TPERM_CASE(12)

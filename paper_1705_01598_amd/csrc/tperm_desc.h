@@ -18,6 +18,9 @@
 #define TPERM_DESC_MAX_DIMS 16   // canonical rank limit = lanes of one DPP row
 #define TPERM_MAX_THREADS 256    // largest workgroup of the tile kernels (4 wavefronts)
 #define TPERM_NO_REM 0xFFFFu     // "no split on this side": every real coordinate is below it
+// Tensors of 4 GiB and more: bytes one buffer description covers, counted from a tile's origin
+// (every position inside a tile must lie below it); also the lane offset of a masked slot.
+#define TPERM_BIG_RANGE 0xFFFFFF00u
 
 namespace tperm {
 

@@ -202,3 +202,53 @@ def test_figure8_squares_full(side):
     per row, and rows that start anywhere in a line (pairs inside line-aligned windows; odd
     sides end every input row with a single element)."""
     _full_stamp_compare(next(c for c in wl.square_sweep() if c.dims[0] == side))
+
+
+# --- tensors of 4 GiB and more ----------------------------------------------------------------
+
+BIG_CASES = [
+    # dims, perm, element size, forced class (None = the selector's plan)
+    ((1031, 1024, 521), (2, 0, 1), 8, None),      # 4.40 GB, ragged, rank 3
+    ((40000, 27000), (1, 0), 4, None),            # 4.32 GB of 4-byte elements, a plain matrix transpose
+    ((96, 96, 96, 96, 7), (3, 1, 4, 0, 2), 8, None),   # 4.76 GB, the 96^4 block seven times over
+    ((1031, 1024, 521), (1, 2, 0), 8, "naive"),   # the gather kernel, which such tensors fall back to
+]
+
+
+@pytest.mark.parametrize("dims,perm,elem,forced", BIG_CASES)
+def test_tensors_beyond_4_gib_full(dims, perm, elem, forced):
+    """Byte offsets beyond 2^32: every tile addresses its pieces from its own origin (the plan
+    reports large = 1).  Whole-tensor comparison with the oracle on scrambled index stamps,
+    sentinel pre-fill and guard bands as everywhere else; then the accumulating form on the
+    same plan (out = out + transposed in, with integer-valued doubles / floats so that the one
+    addition per element is exact and cheap to predict from the first result)."""
+    case = wl.make_case(9, 0, dims, perm, elem)
+    assert case.volume * elem >= (1 << 32)
+    plan = (B.tperm_plan_create_forced(dims, perm, elem, B.KERNEL_NAIVE) if forced == "naive"
+            else B.tperm_plan_create(dims, perm, elem))
+    info = plan.describe()
+    assert info.large == 1
+    if forced is None:
+        assert info.kernel_class in (B.KERNEL_TILED, B.KERNEL_PACKED)
+    a = wl.scrambled_stamp_values(case.volume, elem)
+    a_dev = to_device(a)
+    out = torch.full((case.volume + 2 * GUARD,), SENT, dtype=a_dev.dtype, device="cuda")
+    B.tperm_execute(plan, a_dev.data_ptr(), out.data_ptr() + GUARD * elem, _stream())
+    torch.cuda.synchronize()
+    ref = oracle.transpose(a, dims, perm)
+    _assert_equal_to_oracle(out, ref, case, plan)
+    del a_dev, out
+    torch.cuda.empty_cache()
+    if forced is None:
+        # accumulate: in = small integers as floating point, out starts at 1.0 everywhere
+        ftype = np.float64 if elem == 8 else np.float32
+        small = (np.arange(case.volume, dtype=np.int64) % 1021).astype(ftype)
+        in_dev = to_device(small)
+        acc = torch.ones(case.volume, dtype=torch.float64 if elem == 8 else torch.float32, device="cuda")
+        B.tperm_execute_accumulate(plan, in_dev.data_ptr(), acc.data_ptr(), _stream())
+        torch.cuda.synchronize()
+        expect = to_device(oracle.transpose(small, dims, perm)).view(acc.dtype) + 1.0
+        assert torch.equal(acc, expect), f"accumulate on {dims} {perm}"
+        del in_dev, acc, expect
+    del a, ref
+    torch.cuda.empty_cache()

@@ -97,6 +97,39 @@ def test_forced_class_matches_oracle(dims, perm, kclass, elem):
     plan.destroy()
 
 
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("kclass", [B.KERNEL_AUTO, B.KERNEL_TILED, B.KERNEL_PACKED])
+@pytest.mark.parametrize("dims,perm", SHAPES)
+def test_large_tensor_form_matches_oracle(dims, perm, kclass, elem):
+    """large = 1: the plan and the kernels that tensors of 4 GiB and more get (every tile
+    addresses its pieces from its own origin), on shapes a test can afford."""
+    case = wl.make_case(0, 17, dims, perm, elem)
+    try:
+        plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=kclass, large=1)
+    except B.TpermError as e:
+        assert e.status == B.ERR_KERNEL and kclass != B.KERNEL_AUTO
+        pytest.skip("class cannot run this shape")
+    info = plan.describe()
+    assert info.large == 1 and (info.align_out, info.vec2, info.loads_first) == (0, 0, 0)
+    _check(case, plan, offset=(1 if kclass == B.KERNEL_AUTO else 0))
+    plan.destroy()
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("cache_policy", [1, 2, 3, 4])
+@pytest.mark.parametrize("dims,perm,m,tin,k,tout", [((257, 131), (1, 0), 1, 64, 1, 48), ((70, 45, 33), (2, 1, 0), 1, 16, 2, 9),
+                                                   ((6, 5, 4, 7, 3, 8), (3, 0, 5, 2, 1, 4), 3, 3, 3, 5),
+                                                   ((5, 45, 33, 7), (0, 2, 1, 3), 2, 45, 2, 30)])
+def test_large_tensor_form_explicit_tiles_and_policies(dims, perm, m, tin, k, tout, cache_policy, elem):
+    """The same form with ragged explicit tiles, under each cache policy, with one or two LDS images."""
+    case = wl.make_case(0, 18, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, kernel_class=B.KERNEL_PACKED, m=m, tile_in=tin, k=k, tile_out=tout,
+                                  cache_policy=cache_policy, lds_buffers=1 + cache_policy % 2, large=1)
+    assert plan.describe().large == 1
+    _check(case, plan, kind="stamp")
+    plan.destroy()
+
+
 TILES = [
     # dims, perm, m, tile_in, k, tile_out  -> ragged chunks on both split dims
     ((257, 131), (1, 0), 1, 32, 1, 32),
@@ -586,6 +619,21 @@ def test_accumulate_matches_oracle(dims, perm, kclass, elem):
     ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
     bad = np.nonzero(got != ref)[0]
     assert bad.size == 0, (dims, perm, elem, kclass, bad[:5])
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("dims,perm", SHAPES[::2])
+def test_large_tensor_form_accumulates(dims, perm, elem):
+    case = wl.make_case(0, 19, dims, perm, elem)
+    plan = B.tperm_plan_create_ex(dims, perm, elem, large=1)
+    a = wl.uniform_values(case)
+    b = wl.uniform_values(wl.make_case(0, 20, dims, perm, elem)) * 3
+    a_dev, b_dev = to_device(a), to_device(b)
+    B.tperm_execute_accumulate(plan, a_dev.data_ptr(), b_dev.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = np_uint(b_dev.cpu().numpy())
+    ref = np_uint(oracle.transpose_accumulate(a, b, dims, perm))
+    assert np.array_equal(got, ref), (dims, perm, elem)
 
 
 def test_cached_one_call_interface():

@@ -76,7 +76,8 @@ def test_status_strings():
     ((2, 3), (0, 1), 2, B.ERR_ELEM_SIZE),
     ((2, 3), (0, 1), 16, B.ERR_ELEM_SIZE),
     ((1 << 16, 1 << 16), (1, 0), 4, B.ERR_TOO_LARGE),
-    ((1 << 15, 1 << 15), (1, 0), 8, B.ERR_TOO_LARGE),     # 8 GiB: byte offsets exceed 32 bits
+    ((1 << 16, 1 << 15), (1, 0), 8, B.ERR_TOO_LARGE),     # 2^31 elements: element indices are 31-bit
+    ((1 << 31, 1), (1, 0), 8, B.ERR_TOO_LARGE),
     ((2,) * 17, tuple(range(17)), 8, B.ERR_RANK),
     ((), (), 8, B.ERR_RANK),
 ])
@@ -84,6 +85,58 @@ def test_plan_create_rejects_bad_arguments(dims, perm, elem, status):
     with pytest.raises(B.TpermError) as e:
         B.tperm_plan_create(dims, perm, elem)
     assert e.value.status == status
+
+
+@pytest.mark.parametrize("dims,perm,elem", [
+    ((1 << 15, 1 << 15), (1, 0), 8),            # 8 GiB
+    ((1 << 16, 1 << 13, 2), (2, 1, 0), 4),      # 4 GiB of 4-byte elements
+    ((1024, 769, 700), (2, 0, 1), 8),           # 4.4 GB, ragged
+    ((16, (1 << 27) - 7), (1, 0), 4),           # nearly 2^31 elements; 16 rows half a GiB apart: the tile takes fewer
+])
+def test_tensors_of_4_gib_and_more_get_plain_tile_plans(dims, perm, elem):
+    """Byte offsets beyond 32 bits: the plan is flagged large and uses only the forms that exist
+    for such tensors (plain LDS-staged tiles of 256 threads whose positions inside a tile stay
+    within the range of one buffer description; no windows, pairs, twins, loads-first)."""
+    info = B.tperm_plan_create(dims, perm, elem).describe()
+    assert info.large == 1 and info.volume == math.prod(dims)
+    assert info.kernel_class in (B.KERNEL_TILED, B.KERNEL_PACKED)
+    assert (info.threads, info.align_out, info.vec2, info.paired, info.loads_first) == (256, 0, 0, 0, 0)
+    assert info.lds_bytes > 0 and info.nreg >= 1
+    span_limit = 0xFFFFFF00
+    strides_in = np.cumprod([1] + list(info.canon_dims[:info.canon_rank - 1]))
+    out_dims = [info.canon_dims[info.canon_perm[j]] for j in range(info.canon_rank)]
+    strides_out_by_pos = np.cumprod([1] + out_dims[:-1])
+    inv = {info.canon_perm[j]: j for j in range(info.canon_rank)}
+    t = info.tile_extent[:info.canon_rank]
+    span_in = sum((t[z] - 1) * int(strides_in[z]) for z in range(info.canon_rank))
+    span_out = sum((t[z] - 1) * int(strides_out_by_pos[inv[z]]) for z in range(info.canon_rank))
+    assert (max(span_in, span_out) + 1) * elem <= span_limit
+
+
+def test_large_tensor_whose_tiles_cannot_fit_falls_back_to_the_gather_kernel():
+    """A 4-row matrix of 2^28 + 3 columns: any tile that holds two rows of the transposed side
+    spans more than 4 GiB of the other; the gather kernel computes whole addresses."""
+    info = B.tperm_plan_create(((1 << 28) + 3, 4), (1, 0), 8).describe()
+    assert info.large == 1 and info.kernel_class == B.KERNEL_NAIVE
+    info = B.tperm_plan_create((4, (1 << 29) - 7), (1, 0), 4).describe()
+    assert info.large == 1 and info.kernel_class == B.KERNEL_NAIVE
+    with pytest.raises(B.TpermError) as e:
+        B.tperm_plan_create_forced(((1 << 28) + 3, 4), (1, 0), 8, B.KERNEL_ROWCOPY)
+    assert e.value.status == B.ERR_KERNEL
+    # identity permutations stay plain copies at any size
+    assert B.tperm_plan_create((1 << 15, 1 << 15), (0, 1), 8).describe().kernel_class == B.KERNEL_COPY
+
+
+@pytest.mark.parametrize("elem", [8, 4])
+@pytest.mark.parametrize("dims,perm", [((70, 45, 33), (2, 0, 1)), ((301, 299), (1, 0)), ((64, 64, 64), (0, 2, 1)),
+                                       ((5, 3, 7, 4, 8, 3, 9), (6, 2, 4, 0, 5, 1, 3)), ((16, 6000), (1, 0)),
+                                       ((128, 128, 32), (1, 0, 2)), ((9, 7), (1, 0))])
+def test_large_form_index_maps_on_small_tensors(dims, perm, elem):
+    """large = 1 plans a small tensor the way a 4 GiB one is planned: the index maps of those
+    plans, evaluated on the host with the kernel's arithmetic, against the oracle."""
+    plan = _map_ok(dims, perm, elem, large=1)
+    info = plan.describe()
+    assert info.large == 1 and info.align_out == 0 and info.vec2 == 0 and info.loads_first == 0
 
 
 def test_null_arguments():
