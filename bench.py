@@ -353,6 +353,41 @@ def device_memory_figures(torch):
     return out
 
 
+def large_tensor_sample(torch, steps=12):
+    """One tensor beyond 4 GiB (byte offsets no longer fit the 32-bit operands of buffer
+    addressing; the plan reports large = 1): the 32768 x 32768 fp64 matrix transpose, 8 GiB each
+    way, timed like every other case (two events around back-to-back launches)."""
+    from paper_1705_01598_amd import binding as B
+    dims, perm, elem = (1 << 15, 1 << 15), (1, 0), 8
+    nbytes = dims[0] * dims[1] * elem
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    a.random_(0, 255)
+    plan = B.tperm_plan_create(dims, perm, elem)
+    info = plan.describe()
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(4):
+        B.tperm_execute(plan, a.data_ptr(), b.data_ptr(), stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        B.tperm_execute(plan, a.data_ptr(), b.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    # checked on the device: a transpose moves every element once, none lost or duplicated
+    verdict = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    ws = torch.empty(B.verify_workspace_bytes(dims[0] * dims[1]), dtype=torch.uint8, device="cuda:0")
+    B.tperm_execute_verified(plan, a.data_ptr(), b.data_ptr(), stream, verdict.data_ptr(), ws.data_ptr(), ws.numel())
+    torch.cuda.synchronize()
+    out = {"workload": "32768 x 32768 fp64 matrix transpose, 8 GiB each way", "large": int(info.large),
+           "GBs": round(2.0 * nbytes / ms / 1e6, 1), "ms": round(ms, 3), "multiset_verdict": int(verdict.item())}
+    del a, b, ws
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -485,6 +520,7 @@ def main():
             del oh
             torch.cuda.empty_cache()
         result["per_config"] = dict(sorted(per.items()))
+        result["large_tensor"] = large_tensor_sample(torch)
         medians = [v["case_median_GBs"] for v in per.values()]
         result["all_configs_min_case_median_pct_hbm_peak"] = round(100.0 * min(medians) / HBM_PEAK_GBS, 2)
     if checks:

@@ -237,6 +237,14 @@ def test_tensors_beyond_4_gib_full(dims, perm, elem, forced):
     torch.cuda.synchronize()
     ref = oracle.transpose(a, dims, perm)
     _assert_equal_to_oracle(out, ref, case, plan)
+    if len(dims) == 5:
+        # a plan chosen by timing candidates (Section 2.3) on such a tensor: same bar
+        measured = B.tperm_plan_create_measured(dims, perm, elem, a_dev.data_ptr(), out.data_ptr() + GUARD * elem, _stream(), 6)
+        assert measured.describe().large == 1
+        out.fill_(SENT)
+        B.tperm_execute(measured, a_dev.data_ptr(), out.data_ptr() + GUARD * elem, _stream())
+        torch.cuda.synchronize()
+        _assert_equal_to_oracle(out, ref, case, measured)
     del a_dev, out
     torch.cuda.empty_cache()
     if forced is None:
