@@ -118,9 +118,10 @@ typedef struct {
     int large;                             /* 1: a tensor of 4 GiB or more (or a plan made  *
                                             * to run like one): byte offsets no longer fit  *
                                             * 32 bits, so every tile addresses its pieces   *
-                                            * from its own origin; plain LDS-staged tiles   *
-                                            * of 256 threads (no windows, pairs or twins),  *
-                                            * or the gather kernel when no tile fits.       */
+                                            * from its own origin; LDS-staged tiles of 256  *
+                                            * threads, single elements or pairs, without    *
+                                            * line-aligned windows, or the gather kernel    *
+                                            * when no tile fits.                            */
     int reserved[1];
 } tperm_plan_info_t;
 

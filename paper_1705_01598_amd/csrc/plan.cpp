@@ -917,7 +917,7 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
                                   (split_dim[0] == 0 || cand.t[0] == c.dims[0]);
         const bool pair_plain = !align_out && worth_it && nreg2 > 0 && c.dims[0] % 2 == 0 &&
                                 c.dims[q] % 2 == 0 && cand.t[0] % 2 == 0 && cand.t[q] % 2 == 0;
-        if (!opts.big && opts.vec2 >= 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
+        if (opts.vec2 >= 1 && cand.use_lds && threads == 256 && q != 0 && (pair_plain || pair_windows) &&
             dim_of_in[0] == 0 && dim_of_out[0] == q) {
             TileDim& a = d.in_order[0];
             a.ext /= 2;
@@ -951,7 +951,8 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
             span_in += (uint64_t)(d.in_order[i].ext - 1u) * d.in_order[i].gstride;
             span_out += (uint64_t)(d.out_order[i].ext - 1u) * d.out_order[i].gstride;
         }
-        if ((std::max(span_in, span_out) + 1u) * (uint64_t)elem > (uint64_t)TPERM_BIG_RANGE) return TPERM_ERR_KERNEL;
+        // (+ 2: the last access may be a pair of elements)
+        if ((std::max(span_in, span_out) + 2u) * (uint64_t)elem > (uint64_t)TPERM_BIG_RANGE) return TPERM_ERR_KERNEL;
     }
     plan->tile = d;
     plan->cand = cand;

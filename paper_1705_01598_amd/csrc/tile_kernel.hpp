@@ -214,7 +214,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2, bool BIG = false>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_arg, uint32_t nbytes_arg) {
-    static_assert(!BIG || (USE_LDS && !ALIGN && !VEC2 && !LOADS_FIRST), "large tensors: plain LDS-staged tiles");
+    static_assert(!BIG || (USE_LDS && !ALIGN && !LOADS_FIRST), "large tensors: LDS-staged tiles, stores first, no windows");
     const T* in = in_arg;
     T* out = out_arg;
     uint32_t nbytes = nbytes_arg;

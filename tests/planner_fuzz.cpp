@@ -93,7 +93,7 @@ int main(int argc, char** argv) {
             continue;
         }
         if (o.large == 1 && p->kclass != TPERM_KERNEL_COPY &&
-            (!p->big || p->align_out || p->vec2 || p->loads_first || (p->kclass != TPERM_KERNEL_NAIVE && (!p->use_lds || p->threads != 256)))) {
+            (!p->big || p->align_out || p->loads_first || (p->kclass != TPERM_KERNEL_NAIVE && (!p->use_lds || p->threads != 256)))) {
             std::printf("a large plan uses a form large tensors have no kernel for, iteration %d\n", it);
             return 1;
         }

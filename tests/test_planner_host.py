@@ -96,11 +96,11 @@ def test_plan_create_rejects_bad_arguments(dims, perm, elem, status):
 def test_tensors_of_4_gib_and_more_get_plain_tile_plans(dims, perm, elem):
     """Byte offsets beyond 32 bits: the plan is flagged large and uses only the forms that exist
     for such tensors (plain LDS-staged tiles of 256 threads whose positions inside a tile stay
-    within the range of one buffer description; no windows, pairs, twins, loads-first)."""
+    within the range of one buffer description; no windows, no loads-first)."""
     info = B.tperm_plan_create(dims, perm, elem).describe()
     assert info.large == 1 and info.volume == math.prod(dims)
     assert info.kernel_class in (B.KERNEL_TILED, B.KERNEL_PACKED)
-    assert (info.threads, info.align_out, info.vec2, info.paired, info.loads_first) == (256, 0, 0, 0, 0)
+    assert (info.threads, info.align_out, info.loads_first) == (256, 0, 0)
     assert info.lds_bytes > 0 and info.nreg >= 1
     span_limit = 0xFFFFFF00
     strides_in = np.cumprod([1] + list(info.canon_dims[:info.canon_rank - 1]))
@@ -110,7 +110,7 @@ def test_tensors_of_4_gib_and_more_get_plain_tile_plans(dims, perm, elem):
     t = info.tile_extent[:info.canon_rank]
     span_in = sum((t[z] - 1) * int(strides_in[z]) for z in range(info.canon_rank))
     span_out = sum((t[z] - 1) * int(strides_out_by_pos[inv[z]]) for z in range(info.canon_rank))
-    assert (max(span_in, span_out) + 1) * elem <= span_limit
+    assert (max(span_in, span_out) + 1) * info.elem_size <= span_limit
 
 
 def test_large_tensor_whose_tiles_cannot_fit_falls_back_to_the_gather_kernel():
@@ -136,7 +136,7 @@ def test_large_form_index_maps_on_small_tensors(dims, perm, elem):
     plans, evaluated on the host with the kernel's arithmetic, against the oracle."""
     plan = _map_ok(dims, perm, elem, large=1)
     info = plan.describe()
-    assert info.large == 1 and info.align_out == 0 and info.vec2 == 0 and info.loads_first == 0
+    assert info.large == 1 and info.align_out == 0 and info.loads_first == 0
 
 
 def test_null_arguments():
