@@ -1064,6 +1064,11 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     bo.tile_order = o.tile_order > 0 ? o.tile_order - 1 : kDefaultTileOrder;
     bo.vec2 = o.vec2 == 2 ? 2 : 0;
     bo.big = p->big;
+    if (bo.big) {
+        // options that large tensors have no kernels for are ignored
+        bo.threads = kDefaultThreads;
+        o.loads_first = 0;
+    }
     if (bo.big && want == TPERM_KERNEL_ROWCOPY) return fail(TPERM_ERR_KERNEL);
     // can this candidate run the problem as given (large tensors: a tile whose positions fit)
     auto runnable = [&](const Candidate& cd) {
@@ -1128,10 +1133,6 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
     }
     st = build_tile_plan(p, chosen, bo);
     if (st != TPERM_OK) return fail(st);
-    if (bo.big) {
-        // options that large tensors have no kernels for are ignored
-        o.loads_first = 0;
-    }
     if (o.blocks_per_cu > 0) p->blocks_per_cu = o.blocks_per_cu;
     if (o.cache_policy >= 1 && o.cache_policy <= 4) p->cache_policy = o.cache_policy;
     if (o.loads_first == 1 || o.loads_first == 2) p->loads_first = o.loads_first == 2;
