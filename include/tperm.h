@@ -119,9 +119,8 @@ typedef struct {
                                             * to run like one): byte offsets no longer fit  *
                                             * 32 bits, so every tile addresses its pieces   *
                                             * from its own origin; LDS-staged tiles of 256  *
-                                            * threads, single elements or pairs, without    *
-                                            * line-aligned windows, or the gather kernel    *
-                                            * when no tile fits.                            */
+                                            * threads in all their forms, or the gather     *
+                                            * kernel when no tile fits.                     */
     int reserved[1];
 } tperm_plan_info_t;
 

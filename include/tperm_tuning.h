@@ -60,7 +60,7 @@ typedef struct {
     int large;          /* 1 = plan and run the tensor the way tensors of 4 GiB and more are     *
                          * (large in tperm_plan_info_t), whatever its size: the form can then   *
                          * be checked on tensors a test can afford; 0 = by size.  Such plans     *
-                         * ignore threads and loads_first and never use line-aligned windows     */
+                         * ignore threads and loads_first                                        */
 } tperm_plan_opts_t;
 
 /* tperm_plan_create with overrides.  opts may be NULL (then it is tperm_plan_create).  A

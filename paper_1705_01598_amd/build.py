@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libtperm.so")
 PROBE = os.path.join(HERE, "pattern_probe")
 LATENCY_PROBE = os.path.join(HERE, "latency_probe")
 SOURCES = ["plan.cpp", "model.cpp", "api.cpp", "cache.cpp", "kernels.hip", "verify.hip", "tile_inst_u64_256.hip", "tile_inst_u32_256.hip",
-           "tile_inst_u64_64.hip", "tile_inst_u32_64.hip", "tile_inst_big.hip"]
+           "tile_inst_u64_64.hip", "tile_inst_u32_64.hip", "tile_inst_big_u64.hip", "tile_inst_big_u32.hip"]
 HEADERS = ["pattern_probe.hip", "latency_probe.hip", "plan.hpp", "kernels.hpp", "verify.hpp", "tperm_desc.h", "tile_kernel.hpp", os.path.join("..", "..", "include", "tperm.h"),
            os.path.join("..", "..", "include", "tperm_tuning.h")]
 

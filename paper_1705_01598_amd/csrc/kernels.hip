@@ -12,7 +12,8 @@ const void* tile_kernel_u64_256(int nreg, bool use_lds, int nt, bool align, bool
 const void* tile_kernel_u32_256(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
 const void* tile_kernel_u64_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
 const void* tile_kernel_u32_64(int nreg, bool use_lds, int nt, bool align, bool acc, bool loads_first, bool vec2);
-const void* tile_kernel_big(int elem, int nreg, int nt, bool acc, bool vec2);
+const void* tile_kernel_big_u64(int nreg, int nt, bool align, bool acc, bool vec2);
+const void* tile_kernel_big_u32(int nreg, int nt, bool align, bool acc, bool vec2);
 
 
 // ---------------------------------------------------------------------------------------
@@ -102,8 +103,9 @@ static const void* tile_kernel_for(const Plan& plan, bool acc, bool sector_align
     const int nt = pol == 2 ? 2 : (pol == 3 ? 1 : (pol == 4 ? 3 : 0));  // template parameter NT
     const bool align = plan.align_out;
     if (plan.big) {
-        if (!plan.use_lds || align || plan.loads_first || plan.threads != 256) return nullptr;
-        return tile_kernel_big(plan.elem, plan.nreg, nt, acc, plan.vec2);
+        if (!plan.use_lds || plan.loads_first || plan.threads != 256) return nullptr;
+        return plan.elem == 8 ? tile_kernel_big_u64(plan.nreg, nt, align, acc, plan.vec2)
+                              : tile_kernel_big_u32(plan.nreg, nt, align, acc, plan.vec2);
     }
     if (plan.elem == 8)
         return plan.threads == 64 ? tile_kernel_u64_64(plan.nreg, plan.use_lds, nt, align, acc, plan.loads_first, plan.vec2)

@@ -614,11 +614,14 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
     const int q0 = c.perm[0];
     const int64_t line_elems = 128 / elem;
     bool align_out = false;
-    if (!opts.big && (opts.align_out == 2 || (opts.align_out == 0 && cand.align)) && cand.use_lds && threads == 256 &&
+    // the halo in front of the tensors has to fit the 32-bit byte offsets: with the whole tensor
+    // behind it, or, for large tensors, within the range of one buffer description
+    const bool halo_fits = opts.big ? line_elems * sI[q0] * elem < (int64_t)TPERM_BIG_RANGE / 2
+                                    : (c.volume + line_elems * sI[q0]) * elem + 512 < ((int64_t)1 << 32) - 256;
+    if ((opts.align_out == 2 || (opts.align_out == 0 && cand.align)) && cand.use_lds && threads == 256 &&
         q0 != 0 && cand.k == 1 && cand.t[q0] < c.dims[q0] &&
         cand.t[q0] >= line_elems && cand.t[q0] % line_elems == 0 &&
-        cand.t[q0] + line_elems <= 0x7FFF &&
-        (c.volume + line_elems * sI[q0]) * elem + 512 < ((int64_t)1 << 32) - 256) {
+        cand.t[q0] + line_elems <= 0x7FFF && halo_fits) {
         align_out = true;
         // the shifted dimension is always split dim B
         if (split_dim[0] == q0) std::swap(split_dim[0], split_dim[1]);
@@ -951,8 +954,10 @@ tperm_status_t build_tile_plan(Plan* plan, const Candidate& cand, const TileBuil
             span_in += (uint64_t)(d.in_order[i].ext - 1u) * d.in_order[i].gstride;
             span_out += (uint64_t)(d.out_order[i].ext - 1u) * d.out_order[i].gstride;
         }
-        // (+ 2: the last access may be a pair of elements)
-        if ((std::max(span_in, span_out) + 2u) * (uint64_t)elem > (uint64_t)TPERM_BIG_RANGE) return TPERM_ERR_KERNEL;
+        // (+ 2: the last access may be a pair of elements; + one line: written windows are
+        // placed from a halo origin one line in front of the tile)
+        if ((std::max(span_in, span_out) + 2u + (uint64_t)line_elems) * (uint64_t)elem > (uint64_t)TPERM_BIG_RANGE)
+            return TPERM_ERR_KERNEL;
     }
     plan->tile = d;
     plan->cand = cand;
@@ -1098,7 +1103,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
             int tried = 0;
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
-                if ((o.align_out == 1 || bo.big) && cd.align) continue;
+                if (o.align_out == 1 && cd.align) continue;
                 if (tried++ >= 24) break;
                 Plan tmp = *p;
                 tperm_model_t m;
@@ -1113,7 +1118,7 @@ tperm_status_t create_plan(Plan** out, int rank, const int64_t* dims, const int*
             for (const auto& cd : cands) {
                 if (want != TPERM_KERNEL_AUTO && cd.kclass != want) continue;
                 // windows switched off: a candidate scored and flagged for them is not this plan
-                if ((o.align_out == 1 || bo.big) && cd.align) continue;
+                if (o.align_out == 1 && cd.align) continue;
                 if (!runnable(cd)) continue;
                 chosen = cd;
                 have = true;

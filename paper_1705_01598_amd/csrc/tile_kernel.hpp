@@ -214,7 +214,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2, bool BIG = false>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_arg, uint32_t nbytes_arg) {
-    static_assert(!BIG || (USE_LDS && !ALIGN && !LOADS_FIRST), "large tensors: LDS-staged tiles, stores first, no windows");
+    static_assert(!BIG || (USE_LDS && !LOADS_FIRST), "large tensors: LDS-staged tiles, stores first");
     const T* in = in_arg;
     T* out = out_arg;
     uint32_t nbytes = nbytes_arg;
@@ -285,10 +285,11 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
     // a tensor's first element are masked (lo_b).
     const uint32_t halo_in = ALIGN ? oa.in_halo_elems * (uint32_t)sizeof(T) : 0u;
     const uint32_t halo_out = ALIGN ? oa.line_elems * (uint32_t)sizeof(T) : 0u;
-    const __amdgpu_buffer_rsrc_t rsrc_in_whole =
-        make_rsrc(reinterpret_cast<const char*>(in) - halo_in, nbytes + halo_in);
-    const __amdgpu_buffer_rsrc_t rsrc_out_whole =
-        make_rsrc(reinterpret_cast<char*>(out) - halo_out, nbytes + halo_out);
+    // (BIG: nbytes is already the whole range of a description, counted from a tile's origin)
+    const char* const in_origin = reinterpret_cast<const char*>(in) - halo_in;
+    char* const out_origin = reinterpret_cast<char*>(out) - halo_out;
+    const __amdgpu_buffer_rsrc_t rsrc_in_whole = make_rsrc(in_origin, BIG ? nbytes : nbytes + halo_in);
+    const __amdgpu_buffer_rsrc_t rsrc_out_whole = make_rsrc(out_origin, BIG ? nbytes : nbytes + halo_out);
 
     // minor positions of this thread's slots; global offsets are kept in BYTES
     uint32_t rd_off[NREG], wr_off[NREG], rd_mask[NREG], wr_mask[NREG];
@@ -423,7 +424,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
     };
     auto load_tile = [&](const MajorPos& t) {
         uint32_t soff;
-        const __amdgpu_buffer_rsrc_t rsrc_in = reach(rsrc_in_whole, in, t.in, &soff);
+        const __amdgpu_buffer_rsrc_t rsrc_in = reach(rsrc_in_whole, in_origin, t.in, &soff);
         if constexpr (PAIRWIN) {
             if (odd_row_end(t)) {
 #pragma unroll
@@ -561,7 +562,7 @@ tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_
             if (bn < walk.num_tiles) issue_next_loads();
         }
         uint32_t soff_out;
-        const __amdgpu_buffer_rsrc_t rsrc_out = reach(rsrc_out_whole, out, pos.out, &soff_out);
+        const __amdgpu_buffer_rsrc_t rsrc_out = reach(rsrc_out_whole, out_origin, pos.out, &soff_out);
         if (ACC) {
             // out = out + transposed in: fetch the old output values (all loads first), add
             reg_t old[NREG];

@@ -110,7 +110,7 @@ def test_large_tensor_form_matches_oracle(dims, perm, kclass, elem):
         assert e.status == B.ERR_KERNEL and kclass != B.KERNEL_AUTO
         pytest.skip("class cannot run this shape")
     info = plan.describe()
-    assert info.large == 1 and (info.align_out, info.loads_first) == (0, 0)
+    assert info.large == 1 and info.loads_first == 0
     _check(case, plan, offset=(1 if kclass == B.KERNEL_AUTO else 0))
     plan.destroy()
 
@@ -186,16 +186,18 @@ ALIGNED_WINDOW_TILES = [
 ]
 
 
+@pytest.mark.parametrize("large", [0, 1])
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("offset", [0, 1, 7, 15, 16, 31])
 @pytest.mark.parametrize("dims,perm,m,tin,k,lines", ALIGNED_WINDOW_TILES)
-def test_line_aligned_windows_match_oracle(dims, perm, m, tin, k, lines, offset, elem):
+def test_line_aligned_windows_match_oracle(dims, perm, m, tin, k, lines, offset, elem, large):
     """Line-aligned output windows (halo on the read side, every row shifted to whole lines),
-    with the output base pointer at several phases inside a cache line."""
+    with the output base pointer at several phases inside a cache line; large = 1: in the form
+    tensors of 4 GiB and more run."""
     case = wl.make_case(0, 21, dims, perm, elem)
     plan = B.tperm_plan_create_ex(dims, perm, elem, m=m, tile_in=tin, k=k,
-                                  tile_out=lines * (128 // elem), align_out=2, cache_policy=1 + offset % 4)
-    assert plan.describe().align_out == 1
+                                  tile_out=lines * (128 // elem), align_out=2, cache_policy=1 + offset % 4, large=large)
+    assert plan.describe().align_out == 1 and plan.describe().large == large
     _check(case, plan, offset=offset)
     plan.destroy()
 
@@ -212,17 +214,18 @@ PAIR_WINDOW_TILES = [
 ]
 
 
+@pytest.mark.parametrize("large", [0, 1])
 @pytest.mark.parametrize("in_offset", [0, 1])
 @pytest.mark.parametrize("offset", [0, 1, 2, 7, 16, 31])
 @pytest.mark.parametrize("dims,perm,tin,lines", PAIR_WINDOW_TILES)
-def test_pair_windows_match_oracle(dims, perm, tin, lines, offset, in_offset):
+def test_pair_windows_match_oracle(dims, perm, tin, lines, offset, in_offset, large):
     """Pairs of 4-byte elements inside line-aligned output windows: any phase of the output
     pointer, input pointers aligned to one element only, rows of odd length."""
     case = wl.make_case(0, 25, dims, perm, 4)
     plan = B.tperm_plan_create_ex(dims, perm, 4, m=1, tile_in=tin, k=1, tile_out=32 * lines,
-                                  align_out=2, vec2=2, cache_policy=1 + (offset + in_offset) % 4)
+                                  align_out=2, vec2=2, cache_policy=1 + (offset + in_offset) % 4, large=large)
     info = plan.describe()
-    assert info.align_out == 1 and info.vec2 == 1, B.info_dict(info)
+    assert info.align_out == 1 and info.vec2 == 1 and info.large == large, B.info_dict(info)
     a = wl.bitpattern_values(case)
     buf = torch.empty(case.volume + 64, dtype=torch.int32, device="cuda")
     a_dev = buf[32 + in_offset:32 + in_offset + case.volume]
@@ -233,14 +236,15 @@ def test_pair_windows_match_oracle(dims, perm, tin, lines, offset, in_offset):
     plan.destroy()
 
 
+@pytest.mark.parametrize("large", [0, 1])
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("dims,perm", [((5001, 4777), (1, 0)), ((2001, 15, 2003), (2, 1, 0))])
-def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem):
+def test_heuristic_picks_aligned_windows_and_matches_oracle(dims, perm, elem, large):
     """Misaligned low-rank transposes: the selector takes the aligned-window form by itself;
     plain execution and accumulation both go through it."""
     case = wl.make_case(0, 22, dims, perm, elem)
-    plan = B.tperm_plan_create(dims, perm, elem)
-    assert plan.describe().align_out == 1, B.info_dict(plan.describe())
+    plan = B.tperm_plan_create_ex(dims, perm, elem, large=large)
+    assert plan.describe().align_out == 1 and plan.describe().large == large, B.info_dict(plan.describe())
     assert plan.describe().vec2 == (1 if elem == 4 else 0)
     _check(case, plan, offset=3)
     a = wl.uniform_values(case)

@@ -93,14 +93,14 @@ def test_plan_create_rejects_bad_arguments(dims, perm, elem, status):
     ((1024, 769, 700), (2, 0, 1), 8),           # 4.4 GB, ragged
     ((16, (1 << 27) - 7), (1, 0), 4),           # nearly 2^31 elements; 16 rows half a GiB apart: the tile takes fewer
 ])
-def test_tensors_of_4_gib_and_more_get_plain_tile_plans(dims, perm, elem):
+def test_tensors_of_4_gib_and_more_get_tile_plans(dims, perm, elem):
     """Byte offsets beyond 32 bits: the plan is flagged large and uses only the forms that exist
-    for such tensors (plain LDS-staged tiles of 256 threads whose positions inside a tile stay
-    within the range of one buffer description; no windows, no loads-first)."""
+    for such tensors (LDS-staged tiles of 256 threads, stores first, whose positions inside a
+    tile stay within the range of one buffer description)."""
     info = B.tperm_plan_create(dims, perm, elem).describe()
     assert info.large == 1 and info.volume == math.prod(dims)
     assert info.kernel_class in (B.KERNEL_TILED, B.KERNEL_PACKED)
-    assert (info.threads, info.align_out, info.loads_first) == (256, 0, 0)
+    assert (info.threads, info.loads_first) == (256, 0)
     assert info.lds_bytes > 0 and info.nreg >= 1
     span_limit = 0xFFFFFF00
     strides_in = np.cumprod([1] + list(info.canon_dims[:info.canon_rank - 1]))
@@ -130,13 +130,14 @@ def test_large_tensor_whose_tiles_cannot_fit_falls_back_to_the_gather_kernel():
 @pytest.mark.parametrize("elem", [8, 4])
 @pytest.mark.parametrize("dims,perm", [((70, 45, 33), (2, 0, 1)), ((301, 299), (1, 0)), ((64, 64, 64), (0, 2, 1)),
                                        ((5, 3, 7, 4, 8, 3, 9), (6, 2, 4, 0, 5, 1, 3)), ((16, 6000), (1, 0)),
-                                       ((128, 128, 32), (1, 0, 2)), ((9, 7), (1, 0))])
+                                       ((128, 128, 32), (1, 0, 2)), ((9, 7), (1, 0)), ((97, 150, 11), (1, 0, 2)),
+                                       ((45, 300), (1, 0)), ((33, 257, 3), (1, 2, 0))])
 def test_large_form_index_maps_on_small_tensors(dims, perm, elem):
     """large = 1 plans a small tensor the way a 4 GiB one is planned: the index maps of those
     plans, evaluated on the host with the kernel's arithmetic, against the oracle."""
     plan = _map_ok(dims, perm, elem, large=1)
     info = plan.describe()
-    assert info.large == 1 and info.align_out == 0 and info.loads_first == 0
+    assert info.large == 1 and info.loads_first == 0
 
 
 def test_null_arguments():
