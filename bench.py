@@ -52,6 +52,8 @@ WORKLOAD_NAMES = {
     6: "the paper's rank-8 (205M el) and rank-12 (328M el) fp64 shapes, seeded permutations + trivial + reverse",
     7: "square fp32 matrices, side 13952..13968",
     8: "held-out selector check: ranks 2..12, 2^25 and 2^27 elements, both element sizes, fresh seeds",
+    9: "tensors of 4 GiB and more (4.0-8.0 GiB), both element sizes",
+    10: "selector check on round extents: ranks 2-3, extents multiples of 2..16 elements, both element sizes",
 }
 # steps / warm-up of the families timed beside the headline one (their steps take 0.02-70 ms)
 SIDE_STEPS = {1: (200, 20), 3: (10, 2), 4: (5, 1), 5: (20, 3)}
@@ -65,7 +67,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=0,
                     help="time one workload family only: 1..5; 6 = the paper's printed rank-8/rank-12 "
                          "shapes (Section 3.2), 7 = its square fp32 matrices of side 13952..13968, "
-                         "8 = held-out shapes for the selector check.  Default: family 2 as the "
+                         "8 = held-out shapes for the selector check, 9 = tensors of 4 GiB and more, "
+                         "10 = round extents for the selector check.  Default: family 2 as the "
                          "headline, families 1, 3, 4, 5 beside it under per_config")
     ap.add_argument("--accumulate", action="store_true",
                     help="time out = out + transpose(in) (Section 3.3); bytes = 3 * vol * E")
@@ -139,6 +142,10 @@ def family(args, config):
         return wl.square_sweep()[:: args.stride]
     if config == 8:
         return wl.heldout()[:: args.stride]
+    if config == 9:
+        return wl.large_tensors()[:: args.stride]
+    if config == 10:
+        return wl.even_extents()[:: args.stride]
     return wl.all_configs()[config][:: args.stride]
 
 
@@ -465,7 +472,7 @@ def main():
                      "traffic": traffic, "traffic_source": traffic_source, "kernel": "tperm::tile_kernel",
                      "avg_launch_us": s["tile_kernel_avg_launch_us"]},
     }
-    if config == 8 and args.plan == "heuristic":
+    if config in (8, 10) and args.plan == "heuristic":
         # selector check: the same cases with measurement-selected plans, case by case
         heur = h.case_gbs.copy()
         h.plans[:] = [h.measured_plan(c, 0) for c in cases]

@@ -398,4 +398,4 @@ def info_dict(info: PlanInfo) -> dict:
             "lds_pad": info.lds_pad, "score": round(info.score, 4),
             "blocks_per_cu": info.blocks_per_cu, "cache_policy": info.cache_policy,
             "align_out": info.align_out, "paired": info.paired,
-            "loads_first": info.loads_first, "vec2": info.vec2}
+            "loads_first": info.loads_first, "vec2": info.vec2, "large": info.large}

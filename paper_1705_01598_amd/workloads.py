@@ -289,6 +289,61 @@ def heldout(per_cell: int = 2) -> List[Case]:
     return cases
 
 
+def even_extents() -> List[Case]:
+    """Shapes with "round" extents, as application tensors tend to have: every extent a multiple
+    of 2, 4, 8 or 16 elements but not of a whole 128-byte line, or one side line-aligned and the
+    other not; ranks 2 and 3, 0.1 to 1.2 GB, both element sizes, seeded.  The selector's constants
+    were fitted on random (mostly odd) extents; this family checks it where pairs of elements,
+    sector-aligned pieces and line-aligned rows on one side only all come into play."""
+    rng = np.random.default_rng(SEED_BASE + 10_000_000)
+
+    def mult(lo, hi, m, not_m=None):
+        while True:
+            v = int(rng.integers(lo // m, hi // m + 1)) * m
+            if not_m is None or v % not_m != 0:
+                return v
+
+    shapes = []
+    for elem in (8, 4):
+        line = 128 // elem
+        granules = (2, 4, 8) if elem == 8 else (4, 8, 16)
+        for _ in range(3):
+            for g in granules:      # matrices: input rows line-aligned, output rows on a granule of g elements
+                shapes.append(((mult(4000, 20000, line), mult(4000, 16000, g, 2 * g)), (1, 0), elem, f"in-aligned-g{g * elem}"))
+        for _ in range(2):
+            for g in granules:      # the other way round
+                shapes.append(((mult(4000, 16000, g, 2 * g), mult(4000, 20000, line)), (1, 0), elem, f"out-aligned-g{g * elem}"))
+        for g in granules:          # both sides on the granule
+            shapes.append(((mult(4000, 16000, g, 2 * g), mult(4000, 16000, g, 2 * g)), (1, 0), elem, f"both-g{g * elem}"))
+        perms = [(2, 0, 1), (1, 0, 2), (2, 1, 0), (1, 2, 0)]
+        for i in range(6):          # rank 3, every extent on the granule
+            g = granules[i % 3]
+            shapes.append(((mult(200, 800, g, 2 * g), mult(200, 800, g, 2 * g), mult(100, 400, g)), perms[i % 4], elem, f"rank3-g{g * elem}"))
+        for i in range(4):          # rank 3, leading dimension line-aligned
+            g = granules[i % 3]
+            shapes.append(((mult(256, 1024, line), mult(200, 800, g, 2 * g), mult(100, 400, g)), perms[i % 4], elem, f"rank3-in-aligned-g{g * elem}"))
+    return [make_case(10, i, d, p, e, t) for i, (d, p, e, t) in enumerate(shapes)]
+
+
+def large_tensors() -> List[Case]:
+    """Tensors of 4 GiB and more (byte offsets beyond 32 bits; up to 2^31 - 1 elements): square
+    and rank-3 power-of-two shapes, the 96^4 block of the second set seven times over, a ragged
+    rank-3 tensor and a matrix with odd sides, in both element sizes.  Not from the paper, whose
+    largest tensor is 2.6 GB: sized for a GPU with 288 GB of memory."""
+    shapes = [
+        ((1 << 15, 1 << 15), (1, 0), 8, "sq32768"),
+        ((2048, 2048, 160), (1, 0, 2), 8, "batched"),
+        ((2048, 2048, 160), (2, 1, 0), 8, "reverse"),
+        ((96, 96, 96, 96, 7), (3, 1, 4, 0, 2), 8, "96^4x7"),
+        ((96, 96, 96, 96, 7), (0, 2, 1, 3, 4), 8, "96^4x7keep0"),
+        ((1031, 1024, 521), (2, 0, 1), 8, "ragged3"),
+        ((1 << 15, 1 << 15), (1, 0), 4, "sq32768"),
+        ((40000, 27000), (1, 0), 4, "matrix"),
+        ((40001, 27001), (1, 0), 4, "oddmatrix"),
+    ]
+    return [make_case(9, i, d, p, e, t) for i, (d, p, e, t) in enumerate(shapes)]
+
+
 def contraction_cases(n_cases: int = 24, target_volume: int = 1 << 24) -> list:
     """Seeded sample of binary tensor contractions D += L * R in the style of the paper's
     contraction benchmark (Section 3.4): tensors of rank up to 8, contracted and uncontracted
