@@ -208,9 +208,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 // BIG: tensors of 4 GiB and more.  A tile's origin (its major offset) no longer fits the 32-bit
 // scalar offset of a buffer access, so it goes into the base address instead: every tile
 // describes its buffers anew, starting at its own origin, and the scalar offset stays zero.  The
-// lane offsets (positions inside the tile, which the planner keeps below kBigRange bytes) and
-// the dropped-offset masking work as before; nbytes is then kBigRange, the range one such
-// description covers.  Plain LDS-staged tiles only.
+// lane offsets (positions inside the tile, which the planner keeps below TPERM_BIG_RANGE bytes)
+// and the dropped-offset masking work as before; nbytes is then TPERM_BIG_RANGE, the range one
+// such description covers.  With line-aligned windows the halo origin in front of the tensors
+// moves along with the tile's.  LDS-staged tiles in every form, stores first.
 template <typename T, int NREG, int THREADS, bool USE_LDS, int NT, bool ALIGN, bool ACC, bool LOADS_FIRST, bool VEC2, bool BIG = false>
 __global__ void __launch_bounds__(THREADS)
 tile_kernel(const TileDesc d, const T* __restrict__ in_arg, T* __restrict__ out_arg, uint32_t nbytes_arg) {
