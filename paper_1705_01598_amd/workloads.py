@@ -292,7 +292,7 @@ def heldout(per_cell: int = 2) -> List[Case]:
 def even_extents() -> List[Case]:
     """Shapes with "round" extents, as application tensors tend to have: every extent a multiple
     of 2, 4, 8 or 16 elements but not of a whole 128-byte line, or one side line-aligned and the
-    other not; ranks 2 and 3, 0.1 to 1.2 GB, both element sizes, seeded.  The selector's constants
+    other not; ranks 2 and 3, 0.05 to 2 GB, both element sizes, seeded.  The selector's constants
     were fitted on random (mostly odd) extents; this family checks it where pairs of elements,
     sector-aligned pieces and line-aligned rows on one side only all come into play."""
     rng = np.random.default_rng(SEED_BASE + 10_000_000)
