@@ -84,6 +84,10 @@ def parse_args():
                     help="after the main pass, time the same step with measurement-selected plans")
     ap.add_argument("--also-graph", action="store_true",
                     help="additionally replay one step captured in a HIP graph (reported as graph_value)")
+    ap.add_argument("--also-two-streams", action="store_true",
+                    help="additionally run the steps with the launches alternating between two streams and two "
+                         "output buffers, so that one transpose starts while the other drains (reported as "
+                         "two_stream_value; never the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-verify", action="store_true", help="skip the whole-tensor oracle comparison")
     ap.add_argument("--cases-out", default="", help="write per-case results (JSON lines) here")
@@ -491,6 +495,27 @@ def main():
         h.plans[:] = [h.measured_plan(c, 64) for c in cases]
         elapsed, _ = h.timed(args.steps, args.warmup)
         result["measured_plans_value"] = round(s["bytes_per_step"] * args.steps / elapsed / 1e9, 1)
+    if args.also_two_streams:
+        # independent transposes on two streams, each stream with an output buffer of its own:
+        # the first workgroups of one launch take the compute units the other's last ones leave
+        b2 = torch.empty_like(h.b)
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        outs = [h.b.data_ptr(), b2.data_ptr()]
+
+        def two_stream_step(k):
+            for i, plan in enumerate(h.plans):
+                off = ((k * len(h.plans) + i) % h.places[i]) * h.place[i]
+                h.run(plan, h.a.data_ptr() + off, outs[i % 2] + off, streams[i % 2].cuda_stream)
+        torch.cuda.synchronize()
+        for w in range(max(1, args.warmup)):
+            two_stream_step(w)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            two_stream_step(k)
+        torch.cuda.synchronize()
+        result["two_stream_value"] = round(s["bytes_per_step"] * args.steps / (time.perf_counter() - t0) / 1e9, 1)
+        del b2
     if args.also_graph:
         # the same step as a HIP graph: what a caller with a fixed sequence of transposes gets
         # once the gaps between dependent launches are gone (one buffer pair per launch as in
