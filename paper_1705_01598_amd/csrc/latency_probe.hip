@@ -201,8 +201,9 @@ int main(int argc, char** argv) {
         return 1;
     }
     tick_ns = 1.0e6 / (double)wall_khz;
-    std::printf("device: %s, %d compute units, engine clock %d MHz, wall clock %d kHz (tick %.1f ns)\n", prop.name,
-                prop.multiProcessorCount, prop.clockRate / 1000, wall_khz, tick_ns);
+    std::printf("device: %s (%s), %d compute units, engine clock %d MHz, wall clock %d kHz (tick %.1f ns)\n",
+                prop.name[0] ? prop.name : "unnamed", prop.gcnArchName, prop.multiProcessorCount, prop.clockRate / 1000,
+                wall_khz, tick_ns);
     std::printf("cycles below are at the published %.1f GHz engine clock\n\n", kEngineGHz);
 
     uint64_t* out_dev = nullptr;
