@@ -224,7 +224,7 @@ int tto_contract(int nlab, const int64_t *ext, int nd, const int *dl, int nl, co
                  int nr, const int *rl, size_t elem, const void *l, const void *r, void *d)
 {
     int in_d[TTO_MAX_RANK], in_l[TTO_MAX_RANK], in_r[TTO_MAX_RANK];
-    int64_t sd[TTO_MAX_RANK], sl[TTO_MAX_RANK], sr[TTO_MAX_RANK];   /* stride of a label, 0 if absent */
+    int64_t sl[TTO_MAX_RANK], sr[TTO_MAX_RANK];   /* stride of a label in L / R, 0 if absent */
     int summed[TTO_MAX_RANK], ns = 0;
     if (nlab < 1 || nlab > TTO_MAX_RANK || nd < 1 || nl < 1 || nr < 1) return TTO_BAD_RANK;
     if (nd > nlab || nl > nlab || nr > nlab) return TTO_BAD_RANK;
@@ -232,14 +232,13 @@ int tto_contract(int nlab, const int64_t *ext, int nd, const int *dl, int nl, co
     for (int a = 0; a < nlab; ++a) {
         if (ext[a] < 1) return TTO_BAD_DIMS;
         in_d[a] = in_l[a] = in_r[a] = 0;
-        sd[a] = sl[a] = sr[a] = 0;
+        sl[a] = sr[a] = 0;
+    }
+    for (int j = 0; j < nd; ++j) {   /* D is walked by its own scalar position o: no strides needed */
+        if (dl[j] < 0 || dl[j] >= nlab || in_d[dl[j]]) return TTO_BAD_PERM;
+        in_d[dl[j]] = 1;
     }
     int64_t c = 1;
-    for (int j = 0; j < nd; ++j) {
-        if (dl[j] < 0 || dl[j] >= nlab || in_d[dl[j]]) return TTO_BAD_PERM;
-        in_d[dl[j]] = 1; sd[dl[j]] = c; c *= ext[dl[j]];
-    }
-    c = 1;
     for (int j = 0; j < nl; ++j) {
         if (ll[j] < 0 || ll[j] >= nlab || in_l[ll[j]]) return TTO_BAD_PERM;
         in_l[ll[j]] = 1; sl[ll[j]] = c; c *= ext[ll[j]];
